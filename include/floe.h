@@ -1,0 +1,185 @@
+/*
+ * floe.h -- C ABI of the MI355X (gfx950) implementation of FloE's compressed sparse expert FFN at decode.
+ *
+ * The path (paper Sec. 3.2 "Expert Hybrid Compression", Alg. 1 "Efficient Sparse Kernel", Sec. 3.4):
+ *   S0  quantize W_up to `bits`-bit group codes (offline)                       Sec. 3.2.2
+ *   S1  router: softmax over x.W_r, top-k, optional renormalisation             Sec. 3.3 (first paragraph)
+ *   S2  v = x . W_up^Q            (dequant GEMV over all f channels)            Alg. 1 line 2
+ *   S3  idx = { j : |v_j| > tau } (ascending), K = |idx|                        Alg. 1 line 3, Eq. 5
+ *   S4  h_k = SiLU(x . W_gate[:, idx_k]) * v[idx_k]                             Alg. 1 line 4, Eq. 2
+ *   S5  y = sum_k h_k * W_down[idx_k, :]                                        Alg. 1 line 5
+ *   S6  out = fp16( sum over selected experts of weight_e * y_e )               Sec. 3.3 (router), Eq. 1
+ *   S7  copy the selected [gate column | down row] chunks host -> HBM           Sec. 3.4.2
+ *
+ * General rules for every entry point
+ *  - "dev" pointers are HIP device pointers owned by the CALLER.  The library never allocates, frees
+ *    or keeps them.  Work is enqueued on `stream` (a hipStream_t passed as void*; NULL = the null
+ *    stream) and the call returns without synchronising unless stated.
+ *  - fp16 values are IEEE binary16 bit patterns (floe_half).  x is a row vector (Eq. 1).
+ *  - All matrices are channel-major: row j holds the d numbers of intermediate channel j
+ *    (column j of W_up / W_gate, row j of W_down, i.e. W_down is stored transposed as Sec. 3.4.1 asks).
+ *    Gate and down are co-located per channel, gd[rows][2][d] (compact layout of Sec. 3.4.2).
+ *  - Quantized up projection: codes uint32 [f][d*bits/32], a little-endian bit stream per channel
+ *    (code i at bits [bits*i, bits*i+bits)); scale, zero fp16 [f][d/group]; groups run along d.
+ *    w_hat = (code - zero) * scale.
+ *  - Supported shapes: bits in {2,3,4}; group a power of two in [32, 256]; d % 512 == 0, d <= 8192,
+ *    d % group == 0; 1 <= f <= 2^20; 0 <= T <= 4096.  Anything else returns an error code and
+ *    enqueues nothing.
+ *  - Return value: FLOE_OK (0) or a negative floe_status.  No exceptions, no errno.
+ *  - Nothing falls back to the host: if no HIP device is usable every call returns FLOE_EHIP.
+ */
+#ifndef FLOE_H
+#define FLOE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef uint16_t floe_half;
+
+typedef enum {
+    FLOE_OK = 0,
+    FLOE_EINVAL = -1,       /* NULL pointer, negative size, misaligned buffer */
+    FLOE_ESHAPE = -2,       /* d % group != 0, (group*bits) % 32 != 0, d % 512 != 0 ... */
+    FLOE_EUNSUPPORTED = -3, /* bits not in {2,3,4}, group not in {32,64,128,256}, d > 8192 ... */
+    FLOE_EWORKSPACE = -4,   /* workspace_bytes smaller than the matching *_workspace_bytes() */
+    FLOE_EHIP = -5          /* a HIP runtime call failed (see floe_last_hip_error) */
+} floe_status;
+
+typedef struct {
+    int32_t d;     /* hidden size (reduction length of up / gate, output length of down) */
+    int32_t f;     /* intermediate size = number of channels */
+    int32_t bits;  /* code width of the quantized up projection */
+    int32_t group; /* quantization group length along d */
+} floe_shape;
+
+const char* floe_status_string(int status);
+/* hipError_t of the most recent failing HIP call made by this library on the calling thread (0 if none). */
+int floe_last_hip_error(void);
+/* ABI version, bumped when a struct layout changes. */
+int floe_abi_version(void);
+
+/* ------------------------------------------------------------------------------------------------
+ * S0 -- Sec. 3.2.2.  Asymmetric uniform group quantizer, bit-exact with this definition in IEEE
+ * binary32 (one rounding per operation, no fused multiply-add), qmax = 2^bits - 1:
+ *   mn, mx = min / max of the group;  scale = fp16_rne((mx - mn) / qmax);  S = (float)scale
+ *   zero = fp16_rne(clamp(-mn / S, +-65504));  Z = (float)zero
+ *   code = clamp(rint(w / S + Z), 0, qmax)            (rint = ties to even)
+ * Degenerate group (mx == mn, or S below 2^-14): scale = 1, zero = fp16_rne(-mn), codes 0.
+ * w_up_cm dev [f][d] fp16 in; codes dev [f][d*bits/32], scale dev [f][d/group], zero dev [f][d/group] out.
+ */
+int floe_quantize_expert(const floe_shape* s, const floe_half* w_up_cm, uint32_t* codes, floe_half* scale,
+                         floe_half* zero, void* stream);
+
+/* ------------------------------------------------------------------------------------------------
+ * S2 -- Alg. 1 line 2 on the quantized matrix, for T tokens: v[t][j] = sum_i x[t][i] * w_hat[j][i],
+ * fp32 accumulation.  x dev [T][d] fp16, v dev [T][f] fp32 (written).
+ */
+int floe_up_gemv(const floe_shape* s, const uint32_t* codes, const floe_half* scale, const floe_half* zero,
+                 const floe_half* x, int T, float* v, void* stream);
+
+/* S3 -- Alg. 1 line 3 for T tokens: idx[t][0..count[t]) = ascending { j : |v[t][j]| > tau[t] }.
+ * v dev [T][f]; tau dev [T]; idx dev [T][f] (capacity f per token; entries past count[t] are left
+ * untouched); count dev [T].  The comparison is done in binary32 and is strict.
+ */
+int floe_select_channels(const float* v, int f, int T, const float* tau, int32_t* idx, int32_t* count,
+                         void* stream);
+
+/* One compressed expert (plain pointers, no ownership). */
+typedef struct {
+    floe_shape s;
+    const uint32_t* up_codes;  /* dev */
+    const floe_half* up_scale; /* dev */
+    const floe_half* up_zero;  /* dev */
+    const floe_half* gd;       /* dev, compact layout [gd_rows][2][d]: gate column then down row */
+    int32_t gd_is_staged;      /* 0: gd_rows == f and row j is channel j;
+                                  1: row k holds channel idx[k] (filled by floe_stage_channels) */
+    int32_t gd_rows;           /* rows actually present in gd (capacity when staged) */
+} floe_expert;
+
+/* Bytes of scratch floe_gate_down_sparse / floe_expert_ffn_sparse need for T tokens of this shape. */
+size_t floe_expert_workspace_bytes(const floe_shape* s, int T);
+
+/*
+ * S4 + S5 -- Alg. 1 lines 4-5 for T tokens on index lists that already exist:
+ *   y_acc[t][:] += out_scale[t] * sum_{k < count[t]} SiLU(x[t] . gate(idx[t][k])) * v[t][idx[t][k]] * down(idx[t][k])
+ * v dev [T][f]; idx dev [T][f]; count dev [T]; out_scale dev [T] or NULL (= 1); y_acc dev [T][d] fp32,
+ * read-modify-written (the caller zeroes it; this is how the top-k combine of S6 is folded in).
+ * With a staged gd, row k of token t's list is read from gd row k, so T must be 1 and count[0] must
+ * not exceed gd_rows (rows beyond gd_rows are ignored).
+ * workspace: dev, 256-byte aligned, at least floe_expert_workspace_bytes(); contents are scratch.
+ */
+int floe_gate_down_sparse(const floe_expert* e, const floe_half* x, int T, const float* v, const int32_t* idx,
+                          const int32_t* count, const float* out_scale, float* y_acc, void* workspace,
+                          size_t workspace_bytes, void* stream);
+
+/*
+ * S2..S5 -- the whole of Alg. 1 for one expert and T independent tokens (each token has its own
+ * threshold tau[t], its own mask and its own result):
+ *   v = x . W_up^Q;  idx, count from |v| > tau;  y_acc += out_scale * (sparse gate/down product).
+ * idx dev [T][f] and count dev [T] are outputs (the staging call and the parity checks consume them).
+ * The intermediate v lives in the workspace.  e->gd must be the full (unstaged) matrix.
+ */
+int floe_expert_ffn_sparse(const floe_expert* e, const floe_half* x, int T, const float* tau,
+                           const float* out_scale, float* y_acc, int32_t* idx, int32_t* count, void* workspace,
+                           size_t workspace_bytes, void* stream);
+
+/* ------------------------------------------------------------------------------------------------
+ * One MoE layer (S1..S6).  Routed experts come first in `experts`, the n_shared always-on experts
+ * (weight 1) follow.  All experts of a layer share one floe_shape.
+ */
+typedef struct {
+    int32_t n_experts, top_k, n_shared, renormalize;
+    floe_shape s;
+    const floe_half* router_cm; /* dev [n_experts][d] (may be NULL when top_k == 0) */
+    const floe_expert* experts; /* HOST array of n_experts + n_shared entries (read by floe_layer_build_table) */
+    const float* tau;           /* dev; threshold of (token t, expert e) at tau[t * tau_stride_t + e] */
+    int32_t tau_stride_t;       /* n_experts + n_shared for per-token thresholds, 0 to broadcast the
+                                   per-expert constant t_ij that Alg. 1 takes as input */
+    const void* dev_table;      /* dev, written by floe_layer_build_table: the experts' pointers in HBM */
+} floe_layer;
+
+/* Per (token, slot) record written by floe_moe_layer_decode when `stats` is not NULL;
+ * slots 0..top_k-1 are the routed experts by descending probability, then the shared ones. */
+typedef struct {
+    int32_t expert; /* expert id */
+    int32_t count;  /* K: number of selected channels */
+    float weight;   /* combine weight */
+    int32_t pad;
+} floe_slot_stat;
+
+size_t floe_layer_table_bytes(const floe_layer* L);
+/* Copies the experts' device pointers into dev_table (dev, 256-byte aligned, floe_layer_table_bytes()).
+ * Synchronises `stream` before returning (the host array may be freed afterwards). One-time set-up. */
+int floe_layer_build_table(const floe_layer* L, void* dev_table, size_t bytes, void* stream);
+
+size_t floe_layer_workspace_bytes(const floe_layer* L, int T);
+/*
+ * x dev [T][d] fp16 -> y dev [T][d] fp16.  Router: logits = x . W_r, softmax, top_k (ties to the lower
+ * expert id), weights p_e / sum_selected p if renormalize else p_e.  For every (token, selected expert):
+ * Alg. 1 with threshold tau[t*tau_stride_t + e]; y[t] = fp16_rne(sum_e weight_e * y_e) accumulated in fp32.
+ * stats: dev [T][top_k + n_shared] floe_slot_stat or NULL.  L->dev_table must have been built.
+ */
+int floe_moe_layer_decode(const floe_layer* L, const floe_half* x, int T, floe_half* y, floe_slot_stat* stats,
+                          void* workspace, size_t workspace_bytes, void* stream);
+
+/* ------------------------------------------------------------------------------------------------
+ * S7 -- Sec. 3.4.2 (compact asynchronous transfer), done the MI355X way: a copy kernel on a side
+ * stream reads the selected 4*d-byte [gate | down] chunks straight out of pinned, device-mapped host
+ * memory, so the device-resident index list never travels to the host.
+ *   for k < min(count[0], capacity_rows):  hbm_dst[k][:][:] = host_gd[idx[k]][:][:]
+ * host_gd: pinned host memory [f][2][d] (hipHostMalloc / torch pin_memory); idx, count: dev.
+ * List entries outside [0, f) are skipped (their destination rows are left untouched).
+ * overflow: dev int32 or NULL; set to 1 when count[0] > capacity_rows (the extra rows are skipped), else 0.
+ * done: a hipEvent_t (as void*) recorded on side_stream after the copy, or NULL.
+ */
+int floe_stage_channels(const floe_half* host_gd, int d, int f, const int32_t* idx, const int32_t* count,
+                        int capacity_rows, floe_half* hbm_dst, int32_t* overflow, void* side_stream, void* done);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FLOE_H */

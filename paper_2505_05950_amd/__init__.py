@@ -1,0 +1,13 @@
+"""MI355X-native FloE decode path: compressed sparse expert FFN (quantized up GEMV, threshold
+selection, gathered gate/down GEMVs, top-k combine) behind a C ABI (include/floe.h).
+
+`paper_2505_05950_amd.binding` marshals torch tensors into that ABI; every step runs in the HIP
+library.  There is no host fallback: loading fails loudly when the library has not been built.
+"""
+from .binding import (  # noqa: F401
+    FloeError, Expert, Layer, lib_path, load,
+    floe_quantize_expert, floe_up_gemv, floe_select_channels, floe_gate_down_sparse,
+    floe_expert_ffn_sparse, floe_expert_workspace_bytes, floe_layer_build_table, floe_layer_table_bytes,
+    floe_layer_workspace_bytes, floe_moe_layer_decode, floe_stage_channels, floe_status_string,
+    words_per_channel, SLOT_STAT_DTYPE,
+)

@@ -1,0 +1,322 @@
+// C ABI of the library (declared in include/floe.h): argument checks, workspace carving, launches.
+// Nothing here computes on the host, and there is no host fallback: without a usable HIP device the
+// launches fail and the error is returned.
+#include "../../include/floe.h"
+
+#include <hip/hip_runtime.h>
+
+#include <vector>
+
+#include "launch.h"
+
+using namespace floe;
+
+static_assert(sizeof(floe_slot_stat) == sizeof(SlotStat), "stat record layout");
+static_assert(sizeof(DevExpert) == 32, "expert table entry");
+
+namespace {
+
+thread_local int g_last_hip_error = 0;
+
+int hip_fail(hipError_t e) {
+    g_last_hip_error = (int)e;
+    return FLOE_EHIP;
+}
+
+#define FLOE_HIP(call)                             \
+    do {                                           \
+        hipError_t e__ = (call);                   \
+        if (e__ != hipSuccess) return hip_fail(e__); \
+    } while (0)
+
+constexpr size_t kAlign = 256;
+size_t align_up(size_t n) { return (n + kAlign - 1) / kAlign * kAlign; }
+bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
+
+int check_shape(const floe_shape* s) {
+    if (!s) return FLOE_EINVAL;
+    if (s->d <= 0 || s->f <= 0 || s->group <= 0) return FLOE_EINVAL;
+    if (s->bits != 2 && s->bits != 3 && s->bits != 4) return FLOE_EUNSUPPORTED;
+    if (s->group != 32 && s->group != 64 && s->group != 128 && s->group != 256) return FLOE_EUNSUPPORTED;
+    if (s->d % s->group != 0) return FLOE_ESHAPE;
+    if ((s->group * s->bits) % 32 != 0) return FLOE_ESHAPE;
+    if (s->d % 512 != 0) return FLOE_ESHAPE;
+    if (s->d > 8192) return FLOE_EUNSUPPORTED;
+    if (s->f > (1 << 20)) return FLOE_EUNSUPPORTED;
+    return FLOE_OK;
+}
+
+int check_T(int T) {
+    if (T < 0) return FLOE_EINVAL;
+    if (T > 4096) return FLOE_EUNSUPPORTED;
+    return FLOE_OK;
+}
+
+TaskMap single_map(const floe_expert* e) {
+    TaskMap m;
+    m.single.codes = e->up_codes;
+    m.single.scale = reinterpret_cast<const h16*>(e->up_scale);
+    m.single.zero = reinterpret_cast<const h16*>(e->up_zero);
+    m.single.gd = reinterpret_cast<const h16*>(e->gd);
+    m.table = nullptr;
+    m.task_expert = nullptr;
+    m.slots = 1;
+    return m;
+}
+
+// workspace of the one-expert entry points: [v: T*f floats][partial: T*nblk*d floats]
+struct ExpertWs {
+    size_t v_off, partial_off, total;
+    int nblk;
+};
+ExpertWs expert_ws(const floe_shape* s, int T) {
+    ExpertWs w;
+    w.nblk = gd_blocks(T, s->f);
+    w.v_off = 0;
+    w.partial_off = align_up((size_t)T * s->f * sizeof(float));
+    w.total = w.partial_off + align_up((size_t)T * w.nblk * s->d * sizeof(float));
+    return w;
+}
+
+// workspace of the layer: task table, counts, v, idx, partial
+struct LayerWs {
+    size_t expert_off, weight_off, tau_off, count_off, v_off, idx_off, partial_off, total;
+    int n_tasks, nblk;
+};
+LayerWs layer_ws(const floe_layer* L, int T) {
+    LayerWs w;
+    const int slots = L->top_k + L->n_shared;
+    w.n_tasks = T * slots;
+    w.nblk = gd_blocks(w.n_tasks, L->s.f);
+    size_t o = 0;
+    w.expert_off = o; o += align_up((size_t)w.n_tasks * 4);
+    w.weight_off = o; o += align_up((size_t)w.n_tasks * 4);
+    w.tau_off = o;    o += align_up((size_t)w.n_tasks * 4);
+    w.count_off = o;  o += align_up((size_t)w.n_tasks * 4);
+    w.v_off = o;      o += align_up((size_t)w.n_tasks * L->s.f * 4);
+    w.idx_off = o;    o += align_up((size_t)w.n_tasks * L->s.f * 4);
+    w.partial_off = o; o += align_up((size_t)w.n_tasks * w.nblk * L->s.d * 4);
+    w.total = o;
+    return w;
+}
+
+int check_layer(const floe_layer* L) {
+    if (!L) return FLOE_EINVAL;
+    int rc = check_shape(&L->s);
+    if (rc) return rc;
+    if (L->n_experts < 0 || L->top_k < 0 || L->n_shared < 0) return FLOE_EINVAL;
+    if (L->top_k > L->n_experts) return FLOE_EINVAL;
+    if (L->top_k + L->n_shared <= 0) return FLOE_EINVAL;
+    if (L->n_experts > 1024 || L->top_k + L->n_shared > 64) return FLOE_EUNSUPPORTED;
+    if (L->top_k > 0 && !L->router_cm) return FLOE_EINVAL;
+    if (!L->tau) return FLOE_EINVAL;
+    if (L->tau_stride_t != 0 && L->tau_stride_t != L->n_experts + L->n_shared) return FLOE_EINVAL;
+    return FLOE_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* floe_status_string(int status) {
+    switch (status) {
+        case FLOE_OK: return "ok";
+        case FLOE_EINVAL: return "invalid argument (null pointer, negative size or misaligned buffer)";
+        case FLOE_ESHAPE: return "shape violates a divisibility rule (d % group, group*bits % 32, d % 512)";
+        case FLOE_EUNSUPPORTED: return "unsupported configuration (bits, group, d, f, T or expert count out of range)";
+        case FLOE_EWORKSPACE: return "workspace too small";
+        case FLOE_EHIP: return "HIP runtime error (see floe_last_hip_error)";
+        default: return "unknown status";
+    }
+}
+
+int floe_last_hip_error(void) { return g_last_hip_error; }
+int floe_abi_version(void) { return 1; }
+
+int floe_quantize_expert(const floe_shape* s, const floe_half* w_up_cm, uint32_t* codes, floe_half* scale,
+                         floe_half* zero, void* stream) {
+    int rc = check_shape(s);
+    if (rc) return rc;
+    if (!w_up_cm || !codes || !scale || !zero) return FLOE_EINVAL;
+    if (!aligned(w_up_cm, 16) || !aligned(codes, 4) || !aligned(scale, 2) || !aligned(zero, 2)) return FLOE_EINVAL;
+    FLOE_HIP(launch_quantize(reinterpret_cast<const h16*>(w_up_cm), codes, reinterpret_cast<h16*>(scale),
+                             reinterpret_cast<h16*>(zero), s->d, s->f, s->bits, s->group, (hipStream_t)stream));
+    return FLOE_OK;
+}
+
+int floe_up_gemv(const floe_shape* s, const uint32_t* codes, const floe_half* scale, const floe_half* zero,
+                 const floe_half* x, int T, float* v, void* stream) {
+    int rc = check_shape(s);
+    if (rc) return rc;
+    if ((rc = check_T(T))) return rc;
+    if (T == 0) return FLOE_OK;  // empty batch: pointers of empty arrays may be NULL
+    if (!codes || !scale || !zero || !x || !v) return FLOE_EINVAL;
+    if (!aligned(codes, 16) || !aligned(x, 16) || !aligned(v, 4)) return FLOE_EINVAL;
+    floe_expert e{};
+    e.up_codes = codes; e.up_scale = scale; e.up_zero = zero;
+    FLOE_HIP(launch_up_gemv(single_map(&e), reinterpret_cast<const h16*>(x), v, s->d, s->f, s->bits, s->group, T,
+                            (hipStream_t)stream));
+    return FLOE_OK;
+}
+
+int floe_select_channels(const float* v, int f, int T, const float* tau, int32_t* idx, int32_t* count, void* stream) {
+    if (f <= 0) return FLOE_EINVAL;
+    if (f > (1 << 20)) return FLOE_EUNSUPPORTED;
+    int rc = check_T(T);
+    if (rc) return rc;
+    if (T == 0) return FLOE_OK;
+    if (!v || !tau || !idx || !count) return FLOE_EINVAL;
+    FLOE_HIP(launch_select(v, f, T, tau, idx, count, (hipStream_t)stream));
+    return FLOE_OK;
+}
+
+size_t floe_expert_workspace_bytes(const floe_shape* s, int T) {
+    if (check_shape(s) != FLOE_OK || T < 0) return 0;
+    return expert_ws(s, T).total;
+}
+
+int floe_gate_down_sparse(const floe_expert* e, const floe_half* x, int T, const float* v, const int32_t* idx,
+                          const int32_t* count, const float* out_scale, float* y_acc, void* workspace,
+                          size_t workspace_bytes, void* stream) {
+    if (!e) return FLOE_EINVAL;
+    int rc = check_shape(&e->s);
+    if (rc) return rc;
+    if ((rc = check_T(T))) return rc;
+    if (T == 0) return FLOE_OK;
+    if (!e->gd || !x || !v || !idx || !count || !y_acc || !workspace) return FLOE_EINVAL;
+    if (!aligned(e->gd, 16) || !aligned(x, 16) || !aligned(y_acc, 16) || !aligned(workspace, kAlign)) return FLOE_EINVAL;
+    if (e->gd_is_staged && (T > 1 || e->gd_rows < 0)) return FLOE_EINVAL;
+    if (!e->gd_is_staged && e->gd_rows != e->s.f) return FLOE_EINVAL;
+    const ExpertWs w = expert_ws(&e->s, T);
+    if (workspace_bytes < w.total) return FLOE_EWORKSPACE;
+    float* partial = reinterpret_cast<float*>(static_cast<char*>(workspace) + w.partial_off);
+    hipStream_t st = (hipStream_t)stream;
+    FLOE_HIP(launch_gate_down(single_map(e), e->gd_is_staged, e->gd_rows, reinterpret_cast<const h16*>(x), v, idx,
+                              count, out_scale, partial, e->s.d, e->s.f, T, w.nblk, st));
+    FLOE_HIP(launch_combine(partial, e->s.d, T, 1, w.nblk, y_acc, nullptr, st));
+    return FLOE_OK;
+}
+
+int floe_expert_ffn_sparse(const floe_expert* e, const floe_half* x, int T, const float* tau, const float* out_scale,
+                           float* y_acc, int32_t* idx, int32_t* count, void* workspace, size_t workspace_bytes,
+                           void* stream) {
+    if (!e) return FLOE_EINVAL;
+    int rc = check_shape(&e->s);
+    if (rc) return rc;
+    if ((rc = check_T(T))) return rc;
+    if (T == 0) return FLOE_OK;
+    if (!e->up_codes || !e->up_scale || !e->up_zero || !e->gd || !x || !tau || !y_acc || !idx || !count || !workspace)
+        return FLOE_EINVAL;
+    if (!aligned(e->up_codes, 16) || !aligned(e->gd, 16) || !aligned(x, 16) || !aligned(y_acc, 16) ||
+        !aligned(workspace, kAlign))
+        return FLOE_EINVAL;
+    if (e->gd_is_staged || e->gd_rows != e->s.f) return FLOE_EINVAL;
+    const ExpertWs w = expert_ws(&e->s, T);
+    if (workspace_bytes < w.total) return FLOE_EWORKSPACE;
+    float* v = reinterpret_cast<float*>(static_cast<char*>(workspace) + w.v_off);
+    float* partial = reinterpret_cast<float*>(static_cast<char*>(workspace) + w.partial_off);
+    hipStream_t st = (hipStream_t)stream;
+    const TaskMap map = single_map(e);
+    const h16* xh = reinterpret_cast<const h16*>(x);
+    FLOE_HIP(launch_up_gemv(map, xh, v, e->s.d, e->s.f, e->s.bits, e->s.group, T, st));
+    FLOE_HIP(launch_select(v, e->s.f, T, tau, idx, count, st));
+    FLOE_HIP(launch_gate_down(map, 0, e->s.f, xh, v, idx, count, out_scale, partial, e->s.d, e->s.f, T, w.nblk, st));
+    FLOE_HIP(launch_combine(partial, e->s.d, T, 1, w.nblk, y_acc, nullptr, st));
+    return FLOE_OK;
+}
+
+size_t floe_layer_table_bytes(const floe_layer* L) {
+    if (!L || L->n_experts < 0 || L->n_shared < 0) return 0;
+    return align_up((size_t)(L->n_experts + L->n_shared) * sizeof(DevExpert));
+}
+
+int floe_layer_build_table(const floe_layer* L, void* dev_table, size_t bytes, void* stream) {
+    int rc = check_layer(L);
+    if (rc) return rc;
+    if (!L->experts || !dev_table || !aligned(dev_table, kAlign)) return FLOE_EINVAL;
+    if (bytes < floe_layer_table_bytes(L)) return FLOE_EWORKSPACE;
+    const int n = L->n_experts + L->n_shared;
+    std::vector<DevExpert> host(n);
+    for (int i = 0; i < n; ++i) {
+        const floe_expert& e = L->experts[i];
+        if (e.s.d != L->s.d || e.s.f != L->s.f || e.s.bits != L->s.bits || e.s.group != L->s.group) return FLOE_ESHAPE;
+        if (!e.up_codes || !e.up_scale || !e.up_zero || !e.gd) return FLOE_EINVAL;
+        if (!aligned(e.up_codes, 16) || !aligned(e.gd, 16)) return FLOE_EINVAL;
+        if (e.gd_is_staged || e.gd_rows != e.s.f) return FLOE_EINVAL;
+        host[i].codes = e.up_codes;
+        host[i].scale = reinterpret_cast<const h16*>(e.up_scale);
+        host[i].zero = reinterpret_cast<const h16*>(e.up_zero);
+        host[i].gd = reinterpret_cast<const h16*>(e.gd);
+    }
+    hipStream_t st = (hipStream_t)stream;
+    FLOE_HIP(hipMemcpyAsync(dev_table, host.data(), (size_t)n * sizeof(DevExpert), hipMemcpyHostToDevice, st));
+    FLOE_HIP(hipStreamSynchronize(st));
+    return FLOE_OK;
+}
+
+size_t floe_layer_workspace_bytes(const floe_layer* L, int T) {
+    if (check_layer(L) != FLOE_OK || T < 0) return 0;
+    return layer_ws(L, T).total;
+}
+
+int floe_moe_layer_decode(const floe_layer* L, const floe_half* x, int T, floe_half* y, floe_slot_stat* stats,
+                          void* workspace, size_t workspace_bytes, void* stream) {
+    int rc = check_layer(L);
+    if (rc) return rc;
+    if ((rc = check_T(T))) return rc;
+    if (T == 0) return FLOE_OK;
+    if (!L->dev_table || !x || !y || !workspace) return FLOE_EINVAL;
+    if (!aligned(x, 16) || !aligned(y, 8) || !aligned(workspace, kAlign)) return FLOE_EINVAL;
+    const LayerWs w = layer_ws(L, T);
+    if (workspace_bytes < w.total) return FLOE_EWORKSPACE;
+    char* base = static_cast<char*>(workspace);
+    int32_t* task_expert = reinterpret_cast<int32_t*>(base + w.expert_off);
+    float* task_weight = reinterpret_cast<float*>(base + w.weight_off);
+    float* task_tau = reinterpret_cast<float*>(base + w.tau_off);
+    int32_t* count = reinterpret_cast<int32_t*>(base + w.count_off);
+    float* v = reinterpret_cast<float*>(base + w.v_off);
+    int32_t* idx = reinterpret_cast<int32_t*>(base + w.idx_off);
+    float* partial = reinterpret_cast<float*>(base + w.partial_off);
+    hipStream_t st = (hipStream_t)stream;
+    const h16* xh = reinterpret_cast<const h16*>(x);
+    const int slots = L->top_k + L->n_shared;
+
+    RouterArgs ra;
+    ra.router_cm = reinterpret_cast<const h16*>(L->router_cm);
+    ra.x = xh;
+    ra.tau = L->tau;
+    ra.tau_stride_t = L->tau_stride_t;
+    ra.n_experts = L->n_experts; ra.top_k = L->top_k; ra.n_shared = L->n_shared; ra.renormalize = L->renormalize;
+    ra.d = L->s.d;
+    ra.task_expert = task_expert; ra.task_weight = task_weight; ra.task_tau = task_tau;
+    FLOE_HIP(launch_router(ra, T, st));
+
+    TaskMap map{};
+    map.table = static_cast<const DevExpert*>(L->dev_table);
+    map.task_expert = task_expert;
+    map.slots = slots;
+    FLOE_HIP(launch_up_gemv(map, xh, v, L->s.d, L->s.f, L->s.bits, L->s.group, w.n_tasks, st));
+    FLOE_HIP(launch_select(v, L->s.f, w.n_tasks, task_tau, idx, count, st));
+    FLOE_HIP(launch_gate_down(map, 0, L->s.f, xh, v, idx, count, task_weight, partial, L->s.d, L->s.f, w.n_tasks,
+                              w.nblk, st));
+    FLOE_HIP(launch_combine(partial, L->s.d, T, slots, w.nblk, nullptr, reinterpret_cast<h16*>(y), st));
+    if (stats) FLOE_HIP(launch_stats(task_expert, count, task_weight, reinterpret_cast<SlotStat*>(stats), w.n_tasks, st));
+    return FLOE_OK;
+}
+
+int floe_stage_channels(const floe_half* host_gd, int d, int f, const int32_t* idx, const int32_t* count, int capacity_rows,
+                        floe_half* hbm_dst, int32_t* overflow, void* side_stream, void* done) {
+    if (!host_gd || !idx || !count || !hbm_dst) return FLOE_EINVAL;
+    if (d <= 0 || f <= 0 || capacity_rows < 0) return FLOE_EINVAL;
+    if (d % 4 != 0) return FLOE_ESHAPE;
+    if (!aligned(host_gd, 16) || !aligned(hbm_dst, 16)) return FLOE_EINVAL;
+    void* dev_view = nullptr;
+    FLOE_HIP(hipHostGetDevicePointer(&dev_view, const_cast<floe_half*>(host_gd), 0));
+    hipStream_t st = (hipStream_t)side_stream;
+    FLOE_HIP(launch_stage(static_cast<const h16*>(dev_view), d, f, idx, count, capacity_rows,
+                          reinterpret_cast<h16*>(hbm_dst), overflow, st));
+    if (done) FLOE_HIP(hipEventRecord((hipEvent_t)done, st));
+    return FLOE_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,102 @@
+// S1: router (the paper only says that a router picks the activated experts of each MoE layer, Sec. 3.3;
+// the arithmetic is the usual softmax-top-k of the models it evaluates): logits = x . W_r, softmax with the
+// maximum subtracted, top_k by probability with ties to the lower expert id, optional renormalisation.
+// One workgroup per token writes the task table the later kernels index: task q = token * slots + slot,
+// slots 0..top_k-1 routed (descending probability), then the n_shared always-on experts with weight 1.
+#include "floe_dev.h"
+#include "launch.h"
+
+namespace floe {
+
+constexpr int kMaxExperts = 1024;
+
+__global__ __launch_bounds__(256) void router_kernel(RouterArgs a) {
+    __shared__ float prob[kMaxExperts];
+    const int t = blockIdx.x;
+    const int tid = threadIdx.x;
+    const int wave = tid >> 6, lane = tid & 63;
+    const int d = a.d;
+    const int slots = a.top_k + a.n_shared;
+    const h16* xt = a.x + (size_t)t * d;
+    if (a.top_k > 0) {
+        for (int e = wave; e < a.n_experts; e += 4) {
+            const uint4* wp = reinterpret_cast<const uint4*>(a.router_cm + (size_t)e * d);
+            const uint4* xp = reinterpret_cast<const uint4*>(xt);
+            float acc = 0.0f;
+            for (int i = lane; i < d / 8; i += kWave) {
+                const uint4 w = wp[i], xv = xp[i];
+                acc = dot2(xv.x, w.x, acc);
+                acc = dot2(xv.y, w.y, acc);
+                acc = dot2(xv.z, w.z, acc);
+                acc = dot2(xv.w, w.w, acc);
+            }
+            acc = wave_allreduce_sum(acc);
+            if (lane == 0) prob[e] = acc;
+        }
+    }
+    __syncthreads();
+    if (tid == 0) {
+        if (a.top_k > 0) {
+            float mx = prob[0];
+            for (int e = 1; e < a.n_experts; ++e) mx = fmaxf(mx, prob[e]);
+            float sum = 0.0f;
+            for (int e = 0; e < a.n_experts; ++e) {
+                const float p = expf(prob[e] - mx);
+                prob[e] = p;
+                sum += p;
+            }
+            float sel = 0.0f;
+            for (int r = 0; r < a.top_k; ++r) {
+                int best = -1;
+                float bp = -1.0f;
+                for (int e = 0; e < a.n_experts; ++e) {
+                    const float p = prob[e];
+                    if (p > bp) { bp = p; best = e; }   // strict: ties keep the lower id
+                }
+                if (best < 0) best = 0;  // only reachable with NaN logits: stay in bounds
+                prob[best] = -2.0f;  // taken
+                const float pw = bp / sum;
+                a.task_expert[t * slots + r] = best;
+                a.task_weight[t * slots + r] = pw;
+                sel += pw;
+            }
+            if (a.renormalize)
+                for (int r = 0; r < a.top_k; ++r) a.task_weight[t * slots + r] /= sel;
+        }
+        for (int s = 0; s < a.n_shared; ++s) {
+            a.task_expert[t * slots + a.top_k + s] = a.n_experts + s;
+            a.task_weight[t * slots + a.top_k + s] = 1.0f;
+        }
+        for (int s = 0; s < slots; ++s) {
+            const int e = a.task_expert[t * slots + s];
+            a.task_tau[t * slots + s] = a.tau[(size_t)t * a.tau_stride_t + e];
+        }
+    }
+}
+
+hipError_t launch_router(const RouterArgs& a, int T, hipStream_t stream) {
+    if (T == 0) return hipSuccess;
+    router_kernel<<<dim3(T), dim3(256), 0, stream>>>(a);
+    return hipGetLastError();
+}
+
+__global__ void stats_kernel(const int32_t* task_expert, const int32_t* count, const float* task_weight,
+                             SlotStat* stats, int n_tasks) {
+    const int q = blockIdx.x * blockDim.x + threadIdx.x;
+    if (q >= n_tasks) return;
+    SlotStat s;
+    s.expert = task_expert[q];
+    s.count = count[q];
+    s.weight = task_weight[q];
+    s.pad = 0;
+    stats[q] = s;
+}
+
+hipError_t launch_stats(const int32_t* task_expert, const int32_t* count, const float* task_weight, SlotStat* stats,
+                        int n_tasks, hipStream_t stream) {
+    if (n_tasks == 0) return hipSuccess;
+    stats_kernel<<<dim3((n_tasks + 255) / 256), dim3(256), 0, stream>>>(task_expert, count, task_weight, stats, n_tasks);
+    return hipGetLastError();
+}
+
+}  // namespace floe

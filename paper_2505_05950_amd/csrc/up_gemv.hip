@@ -1,0 +1,204 @@
+// S2: v = x . W_up^Q over all f channels (Alg. 1 line 2 with the quantized up projection of Sec. 3.2.2).
+//
+// The zero point is hoisted out of the inner loop:
+//   sum_i x_i (q_i - z) s  =  s * ( sum_i x_i q_i  -  z * X_g ),   X_g = sum of x over the group,
+// so the per-weight work is "extract the code, multiply-accumulate with x".
+#include "floe_dev.h"
+#include "launch.h"
+
+namespace floe {
+
+// ---------------------------------------------------------------------------------------------------
+// Generic kernel: any bits in {2,3,4}, any group >= 32, any d % 32 == 0 with d <= 8192.
+// A lane owns "units" of 32 consecutive codes (BITS words); x sits in LDS as fp32, transposed to
+// [32][U] so that the 64 lanes of a wave read consecutive addresses.
+// ---------------------------------------------------------------------------------------------------
+template <int BITS>
+__device__ __forceinline__ uint32_t unit_code(const uint32_t (&w)[BITS], int m) {
+    const int bit = m * BITS;
+    const int word = bit >> 5, off = bit & 31;
+    uint64_t two = w[word];
+    if (off + BITS > 32) two |= (uint64_t)w[word + 1 < BITS ? word + 1 : word] << 32;
+    return (uint32_t)(two >> off) & ((1u << BITS) - 1u);
+}
+
+template <int BITS>
+__global__ __launch_bounds__(256) void up_gemv_generic_kernel(TaskMap map, const h16* __restrict__ x,
+                                                              float* __restrict__ v, int d, int f, int gshift) {
+    constexpr int kChPerWave = 8;
+    __shared__ float xT[32 * 256];
+    __shared__ float Xu[256];
+    const int tid = threadIdx.x;
+    const int task = blockIdx.y;
+    const int t = task / map.slots;
+    const DevExpert e = task_expert_of(map, task);
+    const int U = d >> 5;
+    const h16* xt = x + (size_t)t * d;
+    for (int i = tid; i < d; i += 256) xT[(i & 31) * U + (i >> 5)] = (float)xt[i];
+    __syncthreads();
+    for (int u = tid; u < U; u += 256) {
+        float s = 0.0f;
+#pragma unroll
+        for (int m = 0; m < 32; ++m) s += xT[m * U + u];
+        Xu[u] = s;
+    }
+    __syncthreads();
+    const int wpc = d * BITS / 32;
+    const int G = d >> gshift;
+    const int wave = tid >> 6, lane = tid & 63;
+    const int j0 = (blockIdx.x * 4 + wave) * kChPerWave;
+    for (int c = 0; c < kChPerWave; ++c) {
+        const int j = j0 + c;
+        if (j >= f) break;  // wave-uniform
+        float part = 0.0f;
+        for (int u = lane; u < U; u += kWave) {
+            const uint32_t* cw = e.codes + (size_t)j * wpc + (size_t)u * BITS;
+            uint32_t w[BITS];
+#pragma unroll
+            for (int k = 0; k < BITS; ++k) w[k] = cw[k];
+            float acc = 0.0f;
+#pragma unroll
+            for (int m = 0; m < 32; ++m) acc = fmaf(xT[m * U + u], (float)unit_code<BITS>(w, m), acc);
+            const size_t mi = (size_t)j * G + ((u << 5) >> gshift);
+            const float s = (float)e.scale[mi], z = (float)e.zero[mi];
+            part = fmaf(s, fmaf(-z, Xu[u], acc), part);
+        }
+        part = wave_allreduce_sum(part);
+        if (lane == 0) v[(size_t)task * f + j] = part;
+    }
+}
+
+// ---------------------------------------------------------------------------------------------------
+// INT2 fast kernel: group >= 64, d = 64 * UPC with UPC in {16, 32, 64}.
+// A lane owns one 64-code unit (one 128-bit load).  Codes are never converted to numbers one by one:
+// OR-ing a 2-bit field that sits at mantissa bits [p, p+2) of each 16-bit half into 0x3C00 gives the
+// fp16 pair (1 + q * 2^(p-10)); with x pre-multiplied by 2^(10-p) a packed dot product accumulates
+// c*x + x*q, and the c*x part is removed once per unit (Xoff).  Field positions used: p = 4, 6, 8
+// (c = 64, 16, 4) from the word itself, the word << 4 and the word >> 6, so 16 codes cost
+// 2 shifts + 8 and-or + 8 dot2.  Pairs are (code m, code m+8) of a word: the two halves of the register.
+// x is pre-scaled by a power of two so that 64*|x| stays finite in fp16; v is scaled back at the end.
+// ---------------------------------------------------------------------------------------------------
+template <int UPC>
+__global__ __launch_bounds__(256) void up_gemv_int2_kernel(TaskMap map, const h16* __restrict__ x,
+                                                           float* __restrict__ v, int f, int gshift) {
+    constexpr int CPW = kWave / UPC;  // channels per wave pass
+    constexpr int kPasses = 8;
+    constexpr int d = UPC * 64;
+    const int tid = threadIdx.x;
+    const int wave = tid >> 6, lane = tid & 63;
+    const int sub = lane / UPC, u = lane % UPC;
+    const int task = blockIdx.y;
+    const int t = task / map.slots;
+    const DevExpert e = task_expert_of(map, task);
+    const int G = d >> gshift;
+
+    // ---- x prologue: this lane's 64 activations -> 32 scaled fp16 pairs
+    uint32_t raw[32];
+    {
+        const uint4* xp = reinterpret_cast<const uint4*>(x + (size_t)t * d + u * 64);
+#pragma unroll
+        for (int r = 0; r < 8; ++r) {
+            uint4 q = xp[r];
+            raw[4 * r + 0] = q.x; raw[4 * r + 1] = q.y; raw[4 * r + 2] = q.z; raw[4 * r + 3] = q.w;
+        }
+    }
+    float amax = 0.0f;
+#pragma unroll
+    for (int r = 0; r < 32; ++r) {
+        h16x2 p = as_h2(raw[r]);
+        amax = fmaxf(amax, fmaxf(fabsf((float)p.x), fabsf((float)p.y)));
+    }
+#pragma unroll
+    for (int o = UPC / 2; o >= 1; o >>= 1) amax = fmaxf(amax, __shfl_xor(amax, o, kWave));
+    int down = 0;  // x' = x * 2^-down keeps 64 * |x'| below 2^15
+    if (amax >= 256.0f && amax < 3.0e38f) down = ilogbf(amax) - 7;
+    const h16 pscale = (h16)ldexpf(1.0f, -down);
+    const float inv_p = ldexpf(1.0f, down);
+    const h16x2 ones = {(h16)1.0f, (h16)1.0f};
+    const float cm[8] = {64.f, 16.f, 64.f, 16.f, 4.f, 64.f, 16.f, 4.f};
+    uint32_t xs[32];
+    float Xg = 0.0f, Xoff = 0.0f;
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+#pragma unroll
+        for (int m = 0; m < 8; ++m) {
+            const uint32_t A = raw[8 * w + m / 2], B = raw[8 * w + 4 + m / 2];
+            const uint32_t pr = (m & 1) ? ((A >> 16) | (B & 0xFFFF0000u)) : ((A & 0xFFFFu) | (B << 16));
+            h16x2 p = as_h2(pr) * (h16x2){pscale, pscale};
+            Xg = __builtin_amdgcn_fdot2(p, ones, Xg, false);
+            p = p * (h16x2){(h16)cm[m], (h16)cm[m]};
+            Xoff = __builtin_amdgcn_fdot2(p, ones, Xoff, false);
+            xs[8 * w + m] = as_u32(p);
+        }
+    }
+    uint32_t magic = 0x3C003C00u;
+    asm volatile("" : "+v"(magic));  // keep it in a VGPR: v_and_or_b32 takes one scalar operand only
+
+    // ---- main: kPasses passes of CPW channels per wave, all loads issued first
+    const int jw = (blockIdx.x * 4 + wave) * (kPasses * CPW);
+    const uint4* codes4 = reinterpret_cast<const uint4*>(e.codes);
+    uint4 cw[kPasses];
+    h16 sc[kPasses], zr[kPasses];
+#pragma unroll
+    for (int p = 0; p < kPasses; ++p) {
+        int j = jw + p * CPW + sub;
+        j = j < f ? j : f - 1;  // keep the address in bounds; the result of a clamped lane is not stored
+        cw[p] = codes4[(size_t)j * UPC + u];
+        const size_t mi = (size_t)j * G + ((u * 64) >> gshift);
+        sc[p] = e.scale[mi];
+        zr[p] = e.zero[mi];
+    }
+#pragma unroll
+    for (int p = 0; p < kPasses; ++p) {
+        const int j = jw + p * CPW + sub;
+        const uint32_t W[4] = {cw[p].x, cw[p].y, cw[p].z, cw[p].w};
+        float dot = 0.0f;
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+            const uint32_t a = W[w] << 4, b = W[w] >> 6;
+            dot = dot2(xs[8 * w + 0], and_or(a, 0x00300030u, magic), dot);
+            dot = dot2(xs[8 * w + 1], and_or(a, 0x00C000C0u, magic), dot);
+            dot = dot2(xs[8 * w + 2], and_or(W[w], 0x00300030u, magic), dot);
+            dot = dot2(xs[8 * w + 3], and_or(W[w], 0x00C000C0u, magic), dot);
+            dot = dot2(xs[8 * w + 4], and_or(W[w], 0x03000300u, magic), dot);
+            dot = dot2(xs[8 * w + 5], and_or(b, 0x00300030u, magic), dot);
+            dot = dot2(xs[8 * w + 6], and_or(b, 0x00C000C0u, magic), dot);
+            dot = dot2(xs[8 * w + 7], and_or(b, 0x03000300u, magic), dot);
+        }
+        const float s = (float)sc[p], z = (float)zr[p];
+        float part = s * fmaf(-z, Xg, dot - Xoff);
+        part = group_allreduce_sum<UPC>(part);
+        if (u == 0 && j < f) v[(size_t)task * f + j] = part * inv_p;
+    }
+}
+
+static int ilog2_exact(int g) {
+    int s = 0;
+    while ((1 << s) < g) ++s;
+    return s;
+}
+
+hipError_t launch_up_gemv(const TaskMap& map, const h16* x, float* v, int d, int f, int bits, int group, int n_tasks,
+                          hipStream_t stream) {
+    if (f == 0 || n_tasks == 0) return hipSuccess;
+    const int gshift = ilog2_exact(group);
+    dim3 block(256);
+    if (bits == 2 && group >= 64 && (d == 1024 || d == 2048 || d == 4096)) {
+        const int upc = d / 64;
+        const int ch_per_wg = 4 * 8 * (64 / upc);
+        dim3 grid((f + ch_per_wg - 1) / ch_per_wg, n_tasks);
+        if (upc == 64) up_gemv_int2_kernel<64><<<grid, block, 0, stream>>>(map, x, v, f, gshift);
+        else if (upc == 32) up_gemv_int2_kernel<32><<<grid, block, 0, stream>>>(map, x, v, f, gshift);
+        else up_gemv_int2_kernel<16><<<grid, block, 0, stream>>>(map, x, v, f, gshift);
+        return hipGetLastError();
+    }
+    dim3 grid((f + 31) / 32, n_tasks);
+    switch (bits) {
+        case 2: up_gemv_generic_kernel<2><<<grid, block, 0, stream>>>(map, x, v, d, f, gshift); break;
+        case 3: up_gemv_generic_kernel<3><<<grid, block, 0, stream>>>(map, x, v, d, f, gshift); break;
+        default: up_gemv_generic_kernel<4><<<grid, block, 0, stream>>>(map, x, v, d, f, gshift); break;
+    }
+    return hipGetLastError();
+}
+
+}  // namespace floe

@@ -1,0 +1,170 @@
+"""GPU parity of the whole MoE layer (S1..S6) through floe_moe_layer_decode, small and full-size."""
+import numpy as np
+import pytest
+import torch
+
+import floe_synth as S
+import oracle as O
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _threads():
+    O.set_threads(16)
+    yield
+    O.set_threads(1)
+
+
+def _routing_is_stable(wr, x, top_k):
+    """Harness rule: skip tokens whose k-th and (k+1)-th probabilities are within 1e-3 relative."""
+    _, _, p = O.router(wr, x, top_k, False)
+    s = np.sort(p)[::-1]
+    if top_k >= p.size:
+        return True
+    return (s[top_k - 1] - s[top_k]) > 1e-3 * s[top_k - 1]
+
+
+def _reference(experts_np, n_shared, top_k, renorm, wr, x, pct, d, f, bits, group):
+    """Oracle composition per (token, slot) with the band bookkeeping the layer-level bar needs."""
+    import gpu_common as G
+    n_all = len(experts_np)
+    n = n_all - n_shared
+    T = x.shape[0]
+    tau = np.zeros((T, n_all), np.float32)
+    y_ref = np.zeros((T, d))
+    slack = np.zeros((T, d))
+    slots_ref = []
+    for t in range(T):
+        if top_k:
+            ids, w, _ = O.router(wr, x[t], top_k, renorm)
+        else:
+            ids, w = np.zeros(0, np.int32), np.zeros(0)
+        slots = list(zip(ids.tolist(), w.tolist())) + [(n + s, 1.0) for s in range(n_shared)]
+        row = []
+        for e, we in slots:
+            ex = experts_np[e]
+            v = O.up_gemv(*ex[:3], d, bits, group, x[t])
+            tau[t, e] = O.threshold_for_sparsity(v, pct)
+            idx = O.select(v, float(tau[t, e]))
+            y_ref[t] += we * O.sparse_ffn(ex[3], x[t], v, idx)[1]
+            band = np.nonzero(G.in_band(v, float(tau[t, e])))[0].astype(np.int32)
+            if band.size:
+                hb = O.sparse_ffn(ex[3], x[t], v, band)[0]
+                slack[t] += we * (np.abs(hb)[:, None] * np.abs(ex[3][band, 1, :].astype(np.float64))).sum(axis=0)
+            row.append((e, we, idx.size, band.size))
+        slots_ref.append(row)
+    return tau, y_ref, slack, slots_ref
+
+
+def _run_layer_case(seed, cfg, d, f, bits, group, n, n_shared, top_k, renorm, T, pct, experts=None):
+    import gpu_common as G
+    import paper_2505_05950_amd as F
+    if experts is None:
+        experts = [G.make_expert(*S.expert_weights(seed, cfg, d, f, 0, e), bits, group) for e in range(n + n_shared)]
+    experts_np = [e[0] for e in experts]
+    experts_dev = [e[1] for e in experts]
+    wr = S.router_weights(seed, cfg, max(n, 1), d)
+    xs, t_try = [], 0
+    while len(xs) < T:
+        cand = S.tokens(seed, cfg, 1, d, layer=1000 + t_try)[0]
+        t_try += 1
+        if top_k == 0 or _routing_is_stable(wr, cand, top_k):
+            xs.append(cand)
+    x = np.stack(xs)
+    tau, y_ref, slack, slots_ref = _reference(experts_np, n_shared, top_k, renorm, wr, x, pct, d, f, bits, group)
+    # the oracle's own layer routine must agree with the composition above
+    res = O.moe_layer(experts_np, n_shared, top_k, renorm, wr, x, tau, bits, group)
+    np.testing.assert_allclose(res["y"], y_ref, rtol=1e-12, atol=1e-14)
+
+    L = F.Layer(experts_dev, n_shared, top_k, renorm, G.dev(wr) if top_k else None, G.dev(tau), True)
+    slots = top_k + n_shared
+    stats = torch.zeros((T, slots, 4), dtype=torch.int32, device=G.DEV)
+    y = F.floe_moe_layer_decode(L, G.dev(x), stats=stats)
+    torch.cuda.synchronize()
+    y = y.cpu().numpy()
+    st = stats.cpu().numpy().reshape(T, slots, 4).copy().view(F.SLOT_STAT_DTYPE).reshape(T, slots)
+    for t in range(T):
+        for s, (e, we, K, nband) in enumerate(slots_ref[t]):
+            assert st[t, s]["expert"] == e, (t, s)
+            assert abs(st[t, s]["weight"] - we) <= 2e-5 * max(we, 1e-3)
+            assert abs(int(st[t, s]["count"]) - K) <= nband
+        scale = np.abs(y_ref[t]).max()
+        # fp16 rounding of the output: half an ulp of the largest magnitude, relative 2^-11
+        allow = G.Y_BAR * scale + slack[t]
+        assert np.all(np.abs(y[t].astype(np.float64) - y_ref[t]) <= allow), (t, G.rel_err(y[t].astype(np.float64), y_ref[t]))
+        if slack[t].max() == 0:
+            assert G.rel_err(y[t].astype(np.float64), y_ref[t]) <= G.Y_TIGHT
+    return experts
+
+
+def test_layer_small_mixtral_like():
+    # config-3 structure at config-1 width: 8 experts, top-2 renormalised, INT2 g64, 90 % sparsity
+    _run_layer_case(10, 3, 1024, 3584, 2, 64, 8, 0, 2, True, 5, 90)
+
+
+def test_layer_shared_experts_no_renorm_int3():
+    # config-5 structure: many small experts, top-6 without renormalisation, 2 shared experts, INT3 g32, 85 %
+    _run_layer_case(11, 5, 2048, 1408, 3, 32, 16, 2, 6, False, 4, 85)
+
+
+def test_layer_only_shared_experts():
+    _run_layer_case(12, 5, 1024, 512, 4, 64, 0, 2, 0, False, 3, 70)
+
+
+def test_layer_top_k_equals_all_experts():
+    _run_layer_case(13, 3, 1024, 768, 2, 64, 4, 0, 4, True, 2, 50)
+
+
+def test_layer_broadcast_thresholds():
+    """tau_stride_t = 0: one constant per expert, as Alg. 1 takes it."""
+    import gpu_common as G
+    import paper_2505_05950_amd as F
+    d, f, bits, group, n, top_k, T = 1024, 1024, 2, 64, 4, 2, 3
+    experts = [G.make_expert(*S.expert_weights(14, 3, d, f, 0, e), bits, group) for e in range(n)]
+    experts_np = [e[0] for e in experts]
+    wr = S.router_weights(14, 3, n, d)
+    x = S.tokens(14, 3, T, d)
+    tau_e = np.array([1.0, 1.2, 0.9, 1.5], np.float32)
+    ref = O.moe_layer(experts_np, 0, top_k, True, wr, x, np.tile(tau_e, (T, 1)), bits, group)
+    L = F.Layer([e[1] for e in experts], 0, top_k, True, G.dev(wr), G.dev(tau_e), False)
+    y = F.floe_moe_layer_decode(L, G.dev(x)).cpu().numpy().astype(np.float64)
+    for t in range(T):
+        assert G.rel_err(y[t], ref["y"][t]) <= G.Y_BAR
+
+
+# ------------------------------------------------------------------------------------------- full size
+@pytest.fixture(scope="module")
+def mixtral_experts():
+    import gpu_common as G
+    return [G.make_expert(*S.expert_weights(0, 3, 4096, 14336, 0, e), 2, 64) for e in range(8)]
+
+
+@pytest.mark.parametrize("T", [1, 4, 16])
+def test_layer_config3_full_size(mixtral_experts, T):
+    """8 experts of d=4096, f=14336, INT2 g64, 90 % sparsity, top-2 renormalised (the benchmark's launch shape)."""
+    _run_layer_case(0, 3, 4096, 14336, 2, 64, 8, 0, 2, True, T, 90, experts=mixtral_experts)
+
+
+@pytest.mark.parametrize("bits,pct", [(2, 90), (2, 50), (2, 0), (3, 90), (4, 80)])
+def test_expert_config2_full_size(bits, pct):
+    import gpu_common as G
+    import paper_2505_05950_amd as F
+    d, f, group = 4096, 14336, 64
+    w_up, gd = S.expert_weights(0, 2, d, f)
+    ex_np, ex_dev = G.make_expert(w_up, gd, bits, group)
+    x = S.tokens(0, 2, 1, d)
+    v_ref = O.up_gemv(*ex_np[:3], d, bits, group, x[0])
+    tau = O.threshold_for_sparsity(v_ref, pct)
+    y = torch.zeros((1, d), dtype=torch.float32, device=G.DEV)
+    y, idx, count = F.floe_expert_ffn_sparse(ex_dev, G.dev(x), G.dev(np.array([tau], np.float32)), None, y)
+    torch.cuda.synchronize()
+    got = idx[0, : count.item()].cpu().numpy()
+    ref_idx, sym = G.check_index_set(got, v_ref, tau)
+    assert abs(got.size - (f - (-(-f * pct // 100)))) <= max(1, sym.size)
+    y_same = O.sparse_ffn(ex_np[3], x[0], v_ref, got)[1]
+    assert G.rel_err(y.cpu().numpy()[0].astype(np.float64), y_same) <= G.Y_TIGHT
+    y_ref = O.sparse_ffn(ex_np[3], x[0], v_ref, ref_idx)[1]
+    h_sym = O.sparse_ffn(ex_np[3], x[0], v_ref, sym)[0] if sym.size else np.zeros(0)
+    slack = (np.abs(h_sym)[:, None] * np.abs(ex_np[3][sym, 1, :].astype(np.float64))).sum(axis=0) if sym.size else 0.0
+    assert np.all(np.abs(y.cpu().numpy()[0] - y_ref) <= G.Y_BAR * np.abs(y_ref).max() + slack)
