@@ -62,6 +62,24 @@ int floe_last_hip_error(void);
 /* ABI version, bumped when a struct layout changes. */
 int floe_abi_version(void);
 
+/*
+ * Measurement hook (no part of the method).  After floe_profile_kernel(id, start, stop) every launch of
+ * kernel `id` made from the calling thread records hipEvent_t `start` before and `stop` after it on the
+ * launch stream, so a harness can read that kernel's duration with hipEventElapsedTime (this mirrors the
+ * per-kernel latency protocol of Sec. 4.1 / Table 1).  id 0 disarms.  The events stay owned by the caller.
+ */
+typedef enum {
+    FLOE_KERNEL_NONE = 0,
+    FLOE_KERNEL_QUANTIZE = 1,
+    FLOE_KERNEL_ROUTER = 2,
+    FLOE_KERNEL_UP_GEMV = 3,
+    FLOE_KERNEL_SELECT = 4,
+    FLOE_KERNEL_GATE_DOWN = 5,
+    FLOE_KERNEL_COMBINE = 6,
+    FLOE_KERNEL_STAGE = 7
+} floe_kernel_id;
+int floe_profile_kernel(int kernel_id, void* start_event, void* stop_event);
+
 /* ------------------------------------------------------------------------------------------------
  * S0 -- Sec. 3.2.2.  Asymmetric uniform group quantizer, bit-exact with this definition in IEEE
  * binary32 (one rounding per operation, no fused multiply-add), qmax = 2^bits - 1:

@@ -58,6 +58,7 @@ def load():
     lib.floe_status_string.argtypes = [i32]
     lib.floe_last_hip_error.restype = i32
     lib.floe_abi_version.restype = i32
+    lib.floe_profile_kernel.argtypes = [i32, vp, vp]
     lib.floe_quantize_expert.argtypes = [C.POINTER(_Shape), vp, vp, vp, vp, vp]
     lib.floe_up_gemv.argtypes = [C.POINTER(_Shape), vp, vp, vp, vp, i32, vp, vp]
     lib.floe_select_channels.argtypes = [vp, i32, i32, vp, vp, vp, vp]
@@ -78,6 +79,18 @@ def load():
 
 def floe_status_string(status: int) -> str:
     return load().floe_status_string(status).decode()
+
+
+KERNEL_IDS = {"none": 0, "quantize": 1, "router": 2, "up_gemv": 3, "select": 4, "gate_down": 5, "combine": 6, "stage": 7}
+
+
+def floe_profile_kernel(kernel: str, start_event=None, stop_event=None):
+    """Arms (or, with "none", disarms) the event bracket around one kernel; events are torch.cuda.Event
+    objects created with enable_timing=True and recorded at least once (torch creates them lazily)."""
+    kid = KERNEL_IDS[kernel]
+    a = None if start_event is None else C.c_void_p(start_event.cuda_event)
+    b = None if stop_event is None else C.c_void_p(stop_event.cuda_event)
+    _check(load().floe_profile_kernel(kid, a, b), "floe_profile_kernel")
 
 
 def words_per_channel(d: int, bits: int) -> int:

@@ -29,6 +29,31 @@ int hip_fail(hipError_t e) {
         if (e__ != hipSuccess) return hip_fail(e__); \
     } while (0)
 
+// Optional measurement hook: when armed for kernel `id`, the next launches of that kernel are bracketed
+// by the two events on the launch stream (see floe_profile_kernel in floe.h).
+struct ProfileHook {
+    int id = 0;
+    hipEvent_t start = nullptr, stop = nullptr;
+};
+thread_local ProfileHook g_hook;
+
+struct Bracket {
+    bool on;
+    hipStream_t st;
+    Bracket(int id, hipStream_t s) : on(g_hook.id == id && g_hook.start && g_hook.stop), st(s) {
+        if (on) (void)hipEventRecord(g_hook.start, st);
+    }
+    ~Bracket() {
+        if (on) (void)hipEventRecord(g_hook.stop, st);
+    }
+};
+
+#define FLOE_LAUNCH(id, stream, call) \
+    do {                              \
+        Bracket br__((id), (stream)); \
+        FLOE_HIP(call);               \
+    } while (0)
+
 constexpr size_t kAlign = 256;
 size_t align_up(size_t n) { return (n + kAlign - 1) / kAlign * kAlign; }
 bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
@@ -133,13 +158,22 @@ const char* floe_status_string(int status) {
 int floe_last_hip_error(void) { return g_last_hip_error; }
 int floe_abi_version(void) { return 1; }
 
+int floe_profile_kernel(int kernel_id, void* start_event, void* stop_event) {
+    if (kernel_id < 0 || kernel_id > FLOE_KERNEL_STAGE) return FLOE_EINVAL;
+    if (kernel_id != 0 && (!start_event || !stop_event)) return FLOE_EINVAL;
+    g_hook.id = kernel_id;
+    g_hook.start = (hipEvent_t)start_event;
+    g_hook.stop = (hipEvent_t)stop_event;
+    return FLOE_OK;
+}
+
 int floe_quantize_expert(const floe_shape* s, const floe_half* w_up_cm, uint32_t* codes, floe_half* scale,
                          floe_half* zero, void* stream) {
     int rc = check_shape(s);
     if (rc) return rc;
     if (!w_up_cm || !codes || !scale || !zero) return FLOE_EINVAL;
     if (!aligned(w_up_cm, 16) || !aligned(codes, 4) || !aligned(scale, 2) || !aligned(zero, 2)) return FLOE_EINVAL;
-    FLOE_HIP(launch_quantize(reinterpret_cast<const h16*>(w_up_cm), codes, reinterpret_cast<h16*>(scale),
+    FLOE_LAUNCH(FLOE_KERNEL_QUANTIZE, (hipStream_t)stream, launch_quantize(reinterpret_cast<const h16*>(w_up_cm), codes, reinterpret_cast<h16*>(scale),
                              reinterpret_cast<h16*>(zero), s->d, s->f, s->bits, s->group, (hipStream_t)stream));
     return FLOE_OK;
 }
@@ -154,8 +188,9 @@ int floe_up_gemv(const floe_shape* s, const uint32_t* codes, const floe_half* sc
     if (!aligned(codes, 16) || !aligned(x, 16) || !aligned(v, 4)) return FLOE_EINVAL;
     floe_expert e{};
     e.up_codes = codes; e.up_scale = scale; e.up_zero = zero;
-    FLOE_HIP(launch_up_gemv(single_map(&e), reinterpret_cast<const h16*>(x), v, s->d, s->f, s->bits, s->group, T,
-                            (hipStream_t)stream));
+    FLOE_LAUNCH(FLOE_KERNEL_UP_GEMV, (hipStream_t)stream,
+                launch_up_gemv(single_map(&e), reinterpret_cast<const h16*>(x), v, s->d, s->f, s->bits, s->group, T,
+                               (hipStream_t)stream));
     return FLOE_OK;
 }
 
@@ -166,7 +201,7 @@ int floe_select_channels(const float* v, int f, int T, const float* tau, int32_t
     if (rc) return rc;
     if (T == 0) return FLOE_OK;
     if (!v || !tau || !idx || !count) return FLOE_EINVAL;
-    FLOE_HIP(launch_select(v, f, T, tau, idx, count, (hipStream_t)stream));
+    FLOE_LAUNCH(FLOE_KERNEL_SELECT, (hipStream_t)stream, launch_select(v, f, T, tau, idx, count, (hipStream_t)stream));
     return FLOE_OK;
 }
 
@@ -191,9 +226,9 @@ int floe_gate_down_sparse(const floe_expert* e, const floe_half* x, int T, const
     if (workspace_bytes < w.total) return FLOE_EWORKSPACE;
     float* partial = reinterpret_cast<float*>(static_cast<char*>(workspace) + w.partial_off);
     hipStream_t st = (hipStream_t)stream;
-    FLOE_HIP(launch_gate_down(single_map(e), e->gd_is_staged, e->gd_rows, reinterpret_cast<const h16*>(x), v, idx,
+    FLOE_LAUNCH(FLOE_KERNEL_GATE_DOWN, st, launch_gate_down(single_map(e), e->gd_is_staged, e->gd_rows, reinterpret_cast<const h16*>(x), v, idx,
                               count, out_scale, partial, e->s.d, e->s.f, T, w.nblk, st));
-    FLOE_HIP(launch_combine(partial, e->s.d, T, 1, w.nblk, y_acc, nullptr, st));
+    FLOE_LAUNCH(FLOE_KERNEL_COMBINE, st, launch_combine(partial, e->s.d, T, 1, w.nblk, y_acc, nullptr, st));
     return FLOE_OK;
 }
 
@@ -218,10 +253,10 @@ int floe_expert_ffn_sparse(const floe_expert* e, const floe_half* x, int T, cons
     hipStream_t st = (hipStream_t)stream;
     const TaskMap map = single_map(e);
     const h16* xh = reinterpret_cast<const h16*>(x);
-    FLOE_HIP(launch_up_gemv(map, xh, v, e->s.d, e->s.f, e->s.bits, e->s.group, T, st));
-    FLOE_HIP(launch_select(v, e->s.f, T, tau, idx, count, st));
-    FLOE_HIP(launch_gate_down(map, 0, e->s.f, xh, v, idx, count, out_scale, partial, e->s.d, e->s.f, T, w.nblk, st));
-    FLOE_HIP(launch_combine(partial, e->s.d, T, 1, w.nblk, y_acc, nullptr, st));
+    FLOE_LAUNCH(FLOE_KERNEL_UP_GEMV, st, launch_up_gemv(map, xh, v, e->s.d, e->s.f, e->s.bits, e->s.group, T, st));
+    FLOE_LAUNCH(FLOE_KERNEL_SELECT, st, launch_select(v, e->s.f, T, tau, idx, count, st));
+    FLOE_LAUNCH(FLOE_KERNEL_GATE_DOWN, st, launch_gate_down(map, 0, e->s.f, xh, v, idx, count, out_scale, partial, e->s.d, e->s.f, T, w.nblk, st));
+    FLOE_LAUNCH(FLOE_KERNEL_COMBINE, st, launch_combine(partial, e->s.d, T, 1, w.nblk, y_acc, nullptr, st));
     return FLOE_OK;
 }
 
@@ -289,17 +324,17 @@ int floe_moe_layer_decode(const floe_layer* L, const floe_half* x, int T, floe_h
     ra.n_experts = L->n_experts; ra.top_k = L->top_k; ra.n_shared = L->n_shared; ra.renormalize = L->renormalize;
     ra.d = L->s.d;
     ra.task_expert = task_expert; ra.task_weight = task_weight; ra.task_tau = task_tau;
-    FLOE_HIP(launch_router(ra, T, st));
+    FLOE_LAUNCH(FLOE_KERNEL_ROUTER, st, launch_router(ra, T, st));
 
     TaskMap map{};
     map.table = static_cast<const DevExpert*>(L->dev_table);
     map.task_expert = task_expert;
     map.slots = slots;
-    FLOE_HIP(launch_up_gemv(map, xh, v, L->s.d, L->s.f, L->s.bits, L->s.group, w.n_tasks, st));
-    FLOE_HIP(launch_select(v, L->s.f, w.n_tasks, task_tau, idx, count, st));
-    FLOE_HIP(launch_gate_down(map, 0, L->s.f, xh, v, idx, count, task_weight, partial, L->s.d, L->s.f, w.n_tasks,
+    FLOE_LAUNCH(FLOE_KERNEL_UP_GEMV, st, launch_up_gemv(map, xh, v, L->s.d, L->s.f, L->s.bits, L->s.group, w.n_tasks, st));
+    FLOE_LAUNCH(FLOE_KERNEL_SELECT, st, launch_select(v, L->s.f, w.n_tasks, task_tau, idx, count, st));
+    FLOE_LAUNCH(FLOE_KERNEL_GATE_DOWN, st, launch_gate_down(map, 0, L->s.f, xh, v, idx, count, task_weight, partial, L->s.d, L->s.f, w.n_tasks,
                               w.nblk, st));
-    FLOE_HIP(launch_combine(partial, L->s.d, T, slots, w.nblk, nullptr, reinterpret_cast<h16*>(y), st));
+    FLOE_LAUNCH(FLOE_KERNEL_COMBINE, st, launch_combine(partial, L->s.d, T, slots, w.nblk, nullptr, reinterpret_cast<h16*>(y), st));
     if (stats) FLOE_HIP(launch_stats(task_expert, count, task_weight, reinterpret_cast<SlotStat*>(stats), w.n_tasks, st));
     return FLOE_OK;
 }
@@ -313,7 +348,7 @@ int floe_stage_channels(const floe_half* host_gd, int d, int f, const int32_t* i
     void* dev_view = nullptr;
     FLOE_HIP(hipHostGetDevicePointer(&dev_view, const_cast<floe_half*>(host_gd), 0));
     hipStream_t st = (hipStream_t)side_stream;
-    FLOE_HIP(launch_stage(static_cast<const h16*>(dev_view), d, f, idx, count, capacity_rows,
+    FLOE_LAUNCH(FLOE_KERNEL_STAGE, st, launch_stage(static_cast<const h16*>(dev_view), d, f, idx, count, capacity_rows,
                           reinterpret_cast<h16*>(hbm_dst), overflow, st));
     if (done) FLOE_HIP(hipEventRecord((hipEvent_t)done, st));
     return FLOE_OK;

@@ -168,3 +168,37 @@ def test_expert_config2_full_size(bits, pct):
     h_sym = O.sparse_ffn(ex_np[3], x[0], v_ref, sym)[0] if sym.size else np.zeros(0)
     slack = (np.abs(h_sym)[:, None] * np.abs(ex_np[3][sym, 1, :].astype(np.float64))).sum(axis=0) if sym.size else 0.0
     assert np.all(np.abs(y.cpu().numpy()[0] - y_ref) <= G.Y_BAR * np.abs(y_ref).max() + slack)
+
+
+def test_layer_decode_replayed_from_a_hip_graph_matches_eager():
+    """The benchmark replays the layer from a HIP graph: every replay must reproduce the eager result
+    bit for bit (the path has no atomics), with eager work and synchronisations between replays."""
+    import gpu_common as G
+    import paper_2505_05950_amd as F
+    d, f, bits, group, n, top_k, T = 1024, 2048, 2, 64, 8, 2, 2
+    experts = [G.make_expert(*S.expert_weights(15, 3, d, f, 0, e), bits, group) for e in range(n)]
+    wr = S.router_weights(15, 3, n, d)
+    tau = G.dev(np.full((n,), 1.0, np.float32))
+    L = F.Layer([e[1] for e in experts], 0, top_k, True, G.dev(wr), tau, False)
+    xs = [G.dev(S.tokens(15, 3, T, d, layer=i)) for i in range(3)]
+    eager = []
+    for x in xs:
+        eager.append(F.floe_moe_layer_decode(L, x).clone())
+    torch.cuda.synchronize()
+    x_static = xs[0].clone()
+    y_static = torch.empty((T, d), dtype=torch.float16, device=G.DEV)
+    stream = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(stream):
+        F.floe_moe_layer_decode(L, x_static, y_static)      # warm-up on the capture stream
+        stream.synchronize()
+        with torch.cuda.graph(graph, stream=stream):
+            F.floe_moe_layer_decode(L, x_static, y_static)
+    for rep in range(2):
+        for i, x in enumerate(xs):
+            x_static.copy_(x)
+            torch.cuda.synchronize()
+            graph.replay()
+            torch.cuda.synchronize()
+            assert torch.equal(y_static, eager[i]), (rep, i)
+            _ = (y_static.float() * 2).sum().item()          # eager work between replays
