@@ -172,7 +172,7 @@ def main():
     # ---------------------------------------------------------------- per-kernel durations (HIP events)
     per_kernel = {}
     with torch.cuda.stream(stream):
-        for name in ("router", "up_gemv", "select", "gate_down", "combine"):
+        for name in ("router", "up_gemv", "gate_down", "combine"):
             pairs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(K)]
             for a, b in pairs:          # torch creates the hipEvent_t on first record
                 a.record(stream)
@@ -189,13 +189,14 @@ def main():
     # ---------------------------------------------------------------- byte model (algorithmic bytes)
     codes_meta = D * F_INT * BITS // 8 + 4 * F_INT * (D // GROUP)
     k_steps = np.array([Ks[(W + i) % N_TOKENS] for i in range(K)])          # [K][TOP_K]
+    k_mean = float(np.mean(k_steps.sum(axis=1)))
     bytes_up = TOP_K * (codes_meta + 4 * F_INT) + 2 * D                       # codes+scale+zero, v write, x
-    bytes_gd = float(np.mean(k_steps.sum(axis=1) * (2 * 2 * D + 4 + 4))) + TOP_K * 4 * D + 2 * D
+    # selected gate columns and down rows, their v and index entries, the v scan of the selection, x, y
+    bytes_gd = k_mean * (2 * 2 * D + 4 + 4) + TOP_K * 4 * F_INT + 2 * D + TOP_K * 4 * D
     bytes_router = N_EXPERTS * D * 2 + 2 * D
-    bytes_select = TOP_K * (4 * F_INT) + float(np.mean(k_steps.sum(axis=1))) * 4
-    bytes_step = bytes_router + bytes_up + bytes_gd + bytes_select + 2 * D
-    kernel_bytes = {"router": bytes_router, "up_gemv": bytes_up, "select": bytes_select, "gate_down": bytes_gd,
-                    "combine": TOP_K * 4 * D + 2 * D}
+    bytes_combine = TOP_K * 4 * D + 2 * D
+    bytes_step = bytes_router + bytes_up + bytes_gd + bytes_combine
+    kernel_bytes = {"router": bytes_router, "up_gemv": bytes_up, "gate_down": bytes_gd, "combine": bytes_combine}
     dominant = max(per_kernel, key=lambda n: per_kernel[n])
     dom_gbs = kernel_bytes[dominant] / (per_kernel[dominant] * 1e-6) / 1e9
     kernels = {n: {"us": round(per_kernel[n], 3), "algorithmic_bytes": int(kernel_bytes[n]),

@@ -83,29 +83,34 @@ TaskMap single_map(const floe_expert* e) {
     m.single.scale = reinterpret_cast<const h16*>(e->up_scale);
     m.single.zero = reinterpret_cast<const h16*>(e->up_zero);
     m.single.gd = reinterpret_cast<const h16*>(e->gd);
-    m.table = nullptr;
-    m.task_expert = nullptr;
+    m.task_table = nullptr;
     m.slots = 1;
     return m;
 }
 
-// workspace of the one-expert entry points: [v: T*f floats][partial: T*nblk*d floats]
+// workspace of the one-expert entry points: [v: T*f floats][mask words][partial: T*nblk*d floats]
 struct ExpertWs {
-    size_t v_off, partial_off, total;
+    size_t v_off, mask_off, partial_off, total;
     int nblk;
 };
 ExpertWs expert_ws(const floe_shape* s, int T) {
     ExpertWs w;
     w.nblk = gd_blocks(T, s->f);
-    w.v_off = 0;
-    w.partial_off = align_up((size_t)T * s->f * sizeof(float));
-    w.total = w.partial_off + align_up((size_t)T * w.nblk * s->d * sizeof(float));
+    size_t o = 0;
+    w.v_off = o;       o += align_up((size_t)T * s->f * sizeof(float));
+    w.mask_off = o;    o += align_up((size_t)T * mask_words_per_task(s->f) * sizeof(uint32_t));
+    w.partial_off = o; o += align_up((size_t)T * w.nblk * s->d * sizeof(float));
+    w.total = o;
     return w;
 }
 
-// workspace of the layer: task table, counts, v, idx, partial
+// lists longer than this are compacted by the select kernel instead of inside the gate/down kernel
+bool mask_path_ok(int f) { return mask_words_per_task(f) <= 2048; }
+
+// workspace of the layer: per-task table, counts, mask words, prepared activations, v, idx, partial
 struct LayerWs {
-    size_t expert_off, weight_off, tau_off, count_off, v_off, idx_off, partial_off, total;
+    size_t table_off, expert_off, weight_off, tau_off, count_off, mask_off, xs_off, xoff_off, xg_off, invp_off, v_off,
+        idx_off, partial_off, total;
     int n_tasks, nblk;
 };
 LayerWs layer_ws(const floe_layer* L, int T) {
@@ -113,11 +118,18 @@ LayerWs layer_ws(const floe_layer* L, int T) {
     const int slots = L->top_k + L->n_shared;
     w.n_tasks = T * slots;
     w.nblk = gd_blocks(w.n_tasks, L->s.f);
+    const size_t upc = (size_t)L->s.d / 64;
     size_t o = 0;
+    w.table_off = o;  o += align_up((size_t)w.n_tasks * sizeof(DevExpert));
     w.expert_off = o; o += align_up((size_t)w.n_tasks * 4);
     w.weight_off = o; o += align_up((size_t)w.n_tasks * 4);
     w.tau_off = o;    o += align_up((size_t)w.n_tasks * 4);
     w.count_off = o;  o += align_up((size_t)w.n_tasks * 4);
+    w.mask_off = o;   o += align_up((size_t)w.n_tasks * mask_words_per_task(L->s.f) * 4);
+    w.xs_off = o;     o += align_up((size_t)T * L->s.d * 2);
+    w.xoff_off = o;   o += align_up((size_t)T * upc * 4);
+    w.xg_off = o;     o += align_up((size_t)T * upc * 4);
+    w.invp_off = o;   o += align_up((size_t)T * 4);
     w.v_off = o;      o += align_up((size_t)w.n_tasks * L->s.f * 4);
     w.idx_off = o;    o += align_up((size_t)w.n_tasks * L->s.f * 4);
     w.partial_off = o; o += align_up((size_t)w.n_tasks * w.nblk * L->s.d * 4);
@@ -189,8 +201,8 @@ int floe_up_gemv(const floe_shape* s, const uint32_t* codes, const floe_half* sc
     floe_expert e{};
     e.up_codes = codes; e.up_scale = scale; e.up_zero = zero;
     FLOE_LAUNCH(FLOE_KERNEL_UP_GEMV, (hipStream_t)stream,
-                launch_up_gemv(single_map(&e), reinterpret_cast<const h16*>(x), v, s->d, s->f, s->bits, s->group, T,
-                               (hipStream_t)stream));
+                launch_up_gemv(single_map(&e), reinterpret_cast<const h16*>(x), nullptr, v, nullptr, nullptr, s->d, s->f,
+                               s->bits, s->group, T, (hipStream_t)stream));
     return FLOE_OK;
 }
 
@@ -226,8 +238,8 @@ int floe_gate_down_sparse(const floe_expert* e, const floe_half* x, int T, const
     if (workspace_bytes < w.total) return FLOE_EWORKSPACE;
     float* partial = reinterpret_cast<float*>(static_cast<char*>(workspace) + w.partial_off);
     hipStream_t st = (hipStream_t)stream;
-    FLOE_LAUNCH(FLOE_KERNEL_GATE_DOWN, st, launch_gate_down(single_map(e), e->gd_is_staged, e->gd_rows, reinterpret_cast<const h16*>(x), v, idx,
-                              count, out_scale, partial, e->s.d, e->s.f, T, w.nblk, st));
+    FLOE_LAUNCH(FLOE_KERNEL_GATE_DOWN, st, launch_gate_down(single_map(e), e->gd_is_staged, e->gd_rows, reinterpret_cast<const h16*>(x), v, nullptr,
+                              const_cast<int32_t*>(idx), const_cast<int32_t*>(count), out_scale, partial, e->s.d, e->s.f, T, w.nblk, st));
     FLOE_LAUNCH(FLOE_KERNEL_COMBINE, st, launch_combine(partial, e->s.d, T, 1, w.nblk, y_acc, nullptr, st));
     return FLOE_OK;
 }
@@ -253,9 +265,22 @@ int floe_expert_ffn_sparse(const floe_expert* e, const floe_half* x, int T, cons
     hipStream_t st = (hipStream_t)stream;
     const TaskMap map = single_map(e);
     const h16* xh = reinterpret_cast<const h16*>(x);
-    FLOE_LAUNCH(FLOE_KERNEL_UP_GEMV, st, launch_up_gemv(map, xh, v, e->s.d, e->s.f, e->s.bits, e->s.group, T, st));
-    FLOE_LAUNCH(FLOE_KERNEL_SELECT, st, launch_select(v, e->s.f, T, tau, idx, count, st));
-    FLOE_LAUNCH(FLOE_KERNEL_GATE_DOWN, st, launch_gate_down(map, 0, e->s.f, xh, v, idx, count, out_scale, partial, e->s.d, e->s.f, T, w.nblk, st));
+    uint32_t* mask = reinterpret_cast<uint32_t*>(static_cast<char*>(workspace) + w.mask_off);
+    if (mask_path_ok(e->s.f)) {
+        // the GEMV leaves one mask bit per channel; the gate/down kernel compacts them and writes idx / count
+        FLOE_LAUNCH(FLOE_KERNEL_UP_GEMV, st,
+                    launch_up_gemv(map, xh, nullptr, v, tau, mask, e->s.d, e->s.f, e->s.bits, e->s.group, T, st));
+        FLOE_LAUNCH(FLOE_KERNEL_GATE_DOWN, st,
+                    launch_gate_down(map, 0, e->s.f, xh, v, mask, idx, count, out_scale, partial, e->s.d, e->s.f, T,
+                                     w.nblk, st));
+    } else {
+        FLOE_LAUNCH(FLOE_KERNEL_UP_GEMV, st,
+                    launch_up_gemv(map, xh, nullptr, v, nullptr, nullptr, e->s.d, e->s.f, e->s.bits, e->s.group, T, st));
+        FLOE_LAUNCH(FLOE_KERNEL_SELECT, st, launch_select(v, e->s.f, T, tau, idx, count, st));
+        FLOE_LAUNCH(FLOE_KERNEL_GATE_DOWN, st,
+                    launch_gate_down(map, 0, e->s.f, xh, v, nullptr, idx, count, out_scale, partial, e->s.d, e->s.f, T,
+                                     w.nblk, st));
+    }
     FLOE_LAUNCH(FLOE_KERNEL_COMBINE, st, launch_combine(partial, e->s.d, T, 1, w.nblk, y_acc, nullptr, st));
     return FLOE_OK;
 }
@@ -305,16 +330,19 @@ int floe_moe_layer_decode(const floe_layer* L, const floe_half* x, int T, floe_h
     const LayerWs w = layer_ws(L, T);
     if (workspace_bytes < w.total) return FLOE_EWORKSPACE;
     char* base = static_cast<char*>(workspace);
+    DevExpert* task_table = reinterpret_cast<DevExpert*>(base + w.table_off);
     int32_t* task_expert = reinterpret_cast<int32_t*>(base + w.expert_off);
     float* task_weight = reinterpret_cast<float*>(base + w.weight_off);
     float* task_tau = reinterpret_cast<float*>(base + w.tau_off);
     int32_t* count = reinterpret_cast<int32_t*>(base + w.count_off);
+    uint32_t* mask = reinterpret_cast<uint32_t*>(base + w.mask_off);
     float* v = reinterpret_cast<float*>(base + w.v_off);
     int32_t* idx = reinterpret_cast<int32_t*>(base + w.idx_off);
     float* partial = reinterpret_cast<float*>(base + w.partial_off);
     hipStream_t st = (hipStream_t)stream;
     const h16* xh = reinterpret_cast<const h16*>(x);
     const int slots = L->top_k + L->n_shared;
+    const bool fast_up = int2_fast_shape(L->s.d, L->s.bits, L->s.group);
 
     RouterArgs ra;
     ra.router_cm = reinterpret_cast<const h16*>(L->router_cm);
@@ -323,17 +351,37 @@ int floe_moe_layer_decode(const floe_layer* L, const floe_half* x, int T, floe_h
     ra.tau_stride_t = L->tau_stride_t;
     ra.n_experts = L->n_experts; ra.top_k = L->top_k; ra.n_shared = L->n_shared; ra.renormalize = L->renormalize;
     ra.d = L->s.d;
+    ra.table = static_cast<const DevExpert*>(L->dev_table);
+    ra.task_table = task_table;
     ra.task_expert = task_expert; ra.task_weight = task_weight; ra.task_tau = task_tau;
+    ra.xprep = XPrep{};
+    if (fast_up) {
+        ra.xprep.xs = reinterpret_cast<uint4*>(base + w.xs_off);
+        ra.xprep.xoff = reinterpret_cast<float*>(base + w.xoff_off);
+        ra.xprep.xg = reinterpret_cast<float*>(base + w.xg_off);
+        ra.xprep.inv_p = reinterpret_cast<float*>(base + w.invp_off);
+    }
     FLOE_LAUNCH(FLOE_KERNEL_ROUTER, st, launch_router(ra, T, st));
 
     TaskMap map{};
-    map.table = static_cast<const DevExpert*>(L->dev_table);
-    map.task_expert = task_expert;
+    map.task_table = task_table;
     map.slots = slots;
-    FLOE_LAUNCH(FLOE_KERNEL_UP_GEMV, st, launch_up_gemv(map, xh, v, L->s.d, L->s.f, L->s.bits, L->s.group, w.n_tasks, st));
-    FLOE_LAUNCH(FLOE_KERNEL_SELECT, st, launch_select(v, L->s.f, w.n_tasks, task_tau, idx, count, st));
-    FLOE_LAUNCH(FLOE_KERNEL_GATE_DOWN, st, launch_gate_down(map, 0, L->s.f, xh, v, idx, count, task_weight, partial, L->s.d, L->s.f, w.n_tasks,
-                              w.nblk, st));
+    if (mask_path_ok(L->s.f)) {
+        FLOE_LAUNCH(FLOE_KERNEL_UP_GEMV, st,
+                    launch_up_gemv(map, xh, fast_up ? &ra.xprep : nullptr, v, task_tau, mask, L->s.d, L->s.f, L->s.bits,
+                                   L->s.group, w.n_tasks, st));
+        FLOE_LAUNCH(FLOE_KERNEL_GATE_DOWN, st,
+                    launch_gate_down(map, 0, L->s.f, xh, v, mask, nullptr, count, task_weight, partial, L->s.d, L->s.f,
+                                     w.n_tasks, w.nblk, st));
+    } else {
+        FLOE_LAUNCH(FLOE_KERNEL_UP_GEMV, st,
+                    launch_up_gemv(map, xh, fast_up ? &ra.xprep : nullptr, v, nullptr, nullptr, L->s.d, L->s.f,
+                                   L->s.bits, L->s.group, w.n_tasks, st));
+        FLOE_LAUNCH(FLOE_KERNEL_SELECT, st, launch_select(v, L->s.f, w.n_tasks, task_tau, idx, count, st));
+        FLOE_LAUNCH(FLOE_KERNEL_GATE_DOWN, st,
+                    launch_gate_down(map, 0, L->s.f, xh, v, nullptr, idx, count, task_weight, partial, L->s.d, L->s.f,
+                                     w.n_tasks, w.nblk, st));
+    }
     FLOE_LAUNCH(FLOE_KERNEL_COMBINE, st, launch_combine(partial, L->s.d, T, slots, w.nblk, nullptr, reinterpret_cast<h16*>(y), st));
     if (stats) FLOE_HIP(launch_stats(task_expert, count, task_weight, reinterpret_cast<SlotStat*>(stats), w.n_tasks, st));
     return FLOE_OK;

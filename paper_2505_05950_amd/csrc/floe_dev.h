@@ -20,17 +20,16 @@ struct DevExpert {
 };
 
 // How a kernel finds the data of "task" q = (token, slot): either every task uses `single`
-// (one-expert entry points) or the expert id is looked up in task_expert and resolved in `table`.
+// (one-expert entry points) or the router has written one resolved entry per task into task_table.
 struct TaskMap {
     DevExpert single;
-    const DevExpert* table;     // nullptr => use `single`
-    const int32_t* task_expert; // [n_tasks] expert id per task (layer path)
-    int32_t slots;              // tasks per token; token of task q is q / slots
+    const DevExpert* task_table;  // nullptr => use `single`; else [n_tasks], written by the router kernel
+    int32_t slots;                // tasks per token; token of task q is q / slots
 };
 
 __device__ __forceinline__ DevExpert task_expert_of(const TaskMap& m, int task) {
-    if (m.table == nullptr) return m.single;
-    return m.table[m.task_expert[task]];
+    if (m.task_table == nullptr) return m.single;
+    return m.task_table[task];
 }
 
 __device__ __forceinline__ h16x2 as_h2(uint32_t u) { return __builtin_bit_cast(h16x2, u); }
@@ -48,16 +47,39 @@ __device__ __forceinline__ uint32_t and_or(uint32_t a, uint32_t mask, uint32_t m
     return r;
 }
 
-// Sum over the `width` consecutive lanes that share lane / width (width a power of two <= 64);
-// every lane of the group receives the total.
-template <int WIDTH>
-__device__ __forceinline__ float group_allreduce_sum(float x) {
-#pragma unroll
-    for (int o = WIDTH / 2; o >= 1; o >>= 1) x += __shfl_xor(x, o, kWave);
+// ---- cross-lane sums on the DPP path (no LDS traffic) -------------------------------------------
+// DPP control words of gfx9: row_ror:n = 0x120 + n, row_bcast:15 = 0x142, row_bcast:31 = 0x143.
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ float dpp_add(float x) {
+    const int y = __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), CTRL, ROW_MASK, 0xF, false);
+    return x + __builtin_bit_cast(float, y);
+}
+
+// every lane receives the sum over its row of 16 lanes
+__device__ __forceinline__ float row16_allreduce_sum(float x) {
+    x = dpp_add<0x128, 0xF>(x);
+    x = dpp_add<0x124, 0xF>(x);
+    x = dpp_add<0x122, 0xF>(x);
+    x = dpp_add<0x121, 0xF>(x);
     return x;
 }
 
-__device__ __forceinline__ float wave_allreduce_sum(float x) { return group_allreduce_sum<kWave>(x); }
+// Sum over groups of WIDTH consecutive lanes (16, 32 or 64).  The total is valid in the LAST lane of
+// each group (lane % WIDTH == WIDTH - 1); other lanes hold partial sums.
+template <int WIDTH>
+__device__ __forceinline__ float group_reduce_sum_to_last(float x) {
+    static_assert(WIDTH == 16 || WIDTH == 32 || WIDTH == 64, "group width");
+    x = row16_allreduce_sum(x);
+    if (WIDTH >= 32) x = dpp_add<0x142, 0xA>(x);  // rows 1 and 3 += last lane of rows 0 and 2
+    if (WIDTH == 64) x = dpp_add<0x143, 0xC>(x);  // rows 2 and 3 += lane 31
+    return x;
+}
+
+// sum over the 64 lanes, returned to every lane (through a scalar register)
+__device__ __forceinline__ float wave_allreduce_sum(float x) {
+    x = group_reduce_sum_to_last<64>(x);
+    return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, x), 63));
+}
 
 __device__ __forceinline__ float silu(float g) { return g / (1.0f + __expf(-g)); }
 

@@ -1,35 +1,58 @@
-// S4 + S5: gathered gate GEMV with fused SiLU and the product with v, then the gathered down GEMV
-// (Alg. 1 lines 4-5), reading only the compact [gate | down] chunks (Sec. 3.4.2) of the selected channels.
+// S3 (compaction) + S4 + S5: gathered gate GEMV with fused SiLU and the product with v, then the gathered
+// down GEMV (Alg. 1 lines 3-5), reading only the compact [gate | down] chunks (Sec. 3.4.2) of the
+// selected channels.
 //
-// Work split: a wave owns whole channels.  For channel j it streams the d fp16 numbers of the gate
-// column (128-bit loads, the whole wave covers 1 KiB per load), reduces x . gate across the wave,
-// forms h = SiLU(g) * v_j * scale, and adds h * (down row) into d/64 fp32 accumulators per lane.
-// Both rows of a channel are requested before either is used.  The waves of a workgroup then add their
-// accumulators through LDS and the workgroup stores one partial y; S6 adds the partials.
+// Everything here is bound by memory latency, not arithmetic (a Mixtral-shaped expert at 90 % sparsity
+// leaves about 11 channels of 16 KiB per compute unit), so the kernel is organised around ONE round
+// trip to HBM per batch of channels:
+//   * a workgroup takes a contiguous slice [k0, k1) of the task's ascending channel list.  With
+//     FROM_MASK the list is never materialised by a kernel of its own: the GEMV kernel left one mask
+//     bit per channel, every workgroup prefix-sums the popcounts of the task's mask words in LDS and
+//     finds its own channels by binary search (and writes them to idx for the callers that want the list);
+//   * for a batch of B channels every load is issued before anything is used: wave w requests the whole
+//     gate columns of channels w, w+4, ... and every thread requests its 16-byte pieces of all B down rows;
+//   * gate: x . column by packed dot products and a DPP wave reduction, h = SiLU(g) * v_j * scale -> LDS;
+//   * down: the four waves split the d output columns between them, so a thread adds h_c * (its pieces)
+//     into 8 fp32 accumulators per piece and no reduction between waves is needed;
+//   * the workgroup stores one partial y; S6 adds the partials of all workgroups and slots.
 #include "floe_dev.h"
 #include "launch.h"
 
 namespace floe {
 
-template <int NV>  // d = 512 * NV
+constexpr int kMaxMaskWords = 2048;  // FROM_MASK handles f <= 65536
+
+template <int NV>
+struct GdTile {
+    static constexpr int BG = NV >= 24 ? 1 : (24 / NV > 4 ? 4 : (24 / NV < 1 ? 1 : 24 / NV));  // gate channels per wave
+    static constexpr int B = 4 * BG;                                                          // channels per batch
+    static constexpr int VPR = 64 * NV;                 // uint4 per gate column / down row (d / 8)
+    static constexpr int RG = (VPR + 255) / 256;        // down pieces per thread per channel
+};
+
+template <int NV, bool FROM_MASK>  // d = 512 * NV
 __global__ __launch_bounds__(256) void gate_down_kernel(TaskMap map, int staged, int gd_rows,
                                                         const h16* __restrict__ x, const float* __restrict__ v,
-                                                        const int32_t* __restrict__ idx,
-                                                        const int32_t* __restrict__ count,
+                                                        const uint32_t* __restrict__ mask_words,
+                                                        int32_t* __restrict__ idx, int32_t* __restrict__ count,
                                                         const float* __restrict__ task_scale,
                                                         float* __restrict__ partial, int f) {
     constexpr int d = 512 * NV;
-    extern __shared__ float red[];  // [4][d]
+    using Tile = GdTile<NV>;
+    constexpr int BG = Tile::BG, B = Tile::B, VPR = Tile::VPR, RG = Tile::RG;
+    __shared__ int prefix[FROM_MASK ? kMaxMaskWords + 1 : 1];
+    __shared__ uint32_t words[FROM_MASK ? kMaxMaskWords : 1];
+    __shared__ int wave_tot[4];
+    __shared__ int jl[256];
+    __shared__ float vl[256];
+    __shared__ float hl[B];
     const int tid = threadIdx.x;
     const int wave = tid >> 6, lane = tid & 63;
     const int task = blockIdx.y;
     const int t = task / map.slots;
     const DevExpert e = task_expert_of(map, task);
     const float out_scale = task_scale ? task_scale[task] : 1.0f;
-    int K = count[task];
-    K = min(K, staged ? gd_rows : f);
     const float* vt = v + (size_t)task * f;
-    const int32_t* it = idx + (size_t)task * f;
 
     uint4 xr[NV];
     {
@@ -37,59 +60,156 @@ __global__ __launch_bounds__(256) void gate_down_kernel(TaskMap map, int staged,
 #pragma unroll
         for (int r = 0; r < NV; ++r) xr[r] = xp[r * kWave + lane];
     }
-    float acc[NV * 8];
-#pragma unroll
-    for (int i = 0; i < NV * 8; ++i) acc[i] = 0.0f;
 
-    const int nw = gridDim.x * 4;
-    for (int k = blockIdx.x * 4 + wave; k < K; k += nw) {
-        const int j = it[k];
-        if ((unsigned)j >= (unsigned)f) continue;  // a caller-supplied list may hold junk: never leave the matrix
-        const size_t row = staged ? (size_t)k : (size_t)j;
-        const uint4* gp = reinterpret_cast<const uint4*>(e.gd + row * 2 * d);
-        const uint4* dp = gp + d / 8;
-        uint4 gv[NV], dv[NV];
+    // ---- how many channels, and which slice is ours
+    int K;
+    if (FROM_MASK) {
+        const int nwords = mask_words_per_task(f);
+        const int wpt = (nwords + 255) / 256;  // consecutive words per thread (<= 8)
+        const uint32_t* mw = mask_words + (size_t)task * nwords;
+        uint32_t my[8];
+        int mine = 0;
 #pragma unroll
-        for (int r = 0; r < NV; ++r) gv[r] = gp[r * kWave + lane];
-#pragma unroll
-        for (int r = 0; r < NV; ++r) dv[r] = dp[r * kWave + lane];
-        const float vj = vt[j];
-        float g = 0.0f;
-#pragma unroll
-        for (int r = 0; r < NV; ++r) {
-            g = dot2(xr[r].x, gv[r].x, g);
-            g = dot2(xr[r].y, gv[r].y, g);
-            g = dot2(xr[r].z, gv[r].z, g);
-            g = dot2(xr[r].w, gv[r].w, g);
+        for (int i = 0; i < 8; ++i) {
+            const int w = tid * wpt + i;
+            my[i] = (i < wpt && w < nwords) ? mw[w] : 0u;
+            mine += __popc(my[i]);
         }
-        g = wave_allreduce_sum(g);
-        const float h = silu(g) * vj * out_scale;
+        // inclusive scan over the wave, then over the four waves
+        int inc = mine;
 #pragma unroll
-        for (int r = 0; r < NV; ++r) {
-            const uint32_t wds[4] = {dv[r].x, dv[r].y, dv[r].z, dv[r].w};
+        for (int o = 1; o < kWave; o <<= 1) {
+            const int up = __shfl_up(inc, o, kWave);
+            if (lane >= o) inc += up;
+        }
+        if (lane == kWave - 1) wave_tot[wave] = inc;
+        __syncthreads();
+        int base = 0;
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const h16x2 p = as_h2(wds[q]);
-                acc[r * 8 + 2 * q + 0] = fmaf(h, (float)p.x, acc[r * 8 + 2 * q + 0]);
-                acc[r * 8 + 2 * q + 1] = fmaf(h, (float)p.y, acc[r * 8 + 2 * q + 1]);
+        for (int w = 0; w < 4; ++w) base += w < wave ? wave_tot[w] : 0;
+        K = wave_tot[0] + wave_tot[1] + wave_tot[2] + wave_tot[3];
+        int run = base + inc - mine;  // exclusive prefix of this thread's first word
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const int w = tid * wpt + i;
+            if (i < wpt && w < nwords) {
+                prefix[w] = run;
+                words[w] = my[i];
+                run += __popc(my[i]);
             }
         }
+        if (tid == 0) {
+            prefix[nwords] = K;
+            if (count && blockIdx.x == 0) count[task] = K;
+        }
+        __syncthreads();
+    } else {
+        K = count[task];
+    }
+    const int Kc = min(K, staged ? gd_rows : f);
+    const int per = (Kc + (int)gridDim.x - 1) / (int)gridDim.x;
+    const int k0 = min(Kc, (int)blockIdx.x * per);
+    const int k1 = min(Kc, k0 + per);
+
+    float acc[RG * 8];
+#pragma unroll
+    for (int i = 0; i < RG * 8; ++i) acc[i] = 0.0f;
+
+    for (int kc = k0; kc < k1; kc += 256) {
+        const int n = min(256, k1 - kc);
+        if (tid < n) {
+            const int k = kc + tid;
+            int j;
+            if (FROM_MASK) {
+                int lo = 0, hi = mask_words_per_task(f);
+                while (hi - lo > 1) {
+                    const int mid = (lo + hi) >> 1;
+                    if (prefix[mid] <= k) lo = mid; else hi = mid;
+                }
+                uint32_t wbits = words[lo];
+                for (int r = k - prefix[lo]; r > 0; --r) wbits &= wbits - 1;  // drop the r lowest set bits
+                j = lo * 32 + (__ffs(wbits) - 1);
+                if (idx) idx[(size_t)task * f + k] = j;
+            } else {
+                j = idx[(size_t)task * f + k];
+                if ((unsigned)j >= (unsigned)f) j = -1;  // a caller-supplied list may hold junk: never leave the matrix
+            }
+            jl[tid] = j;
+            vl[tid] = j >= 0 ? vt[j] : 0.0f;
+        }
+        __syncthreads();
+
+        for (int b0 = 0; b0 < n; b0 += B) {
+            // ---- all loads of the batch
+            uint4 gv[BG][NV];
+            uint4 dv[B][RG];
+#pragma unroll
+            for (int i = 0; i < BG; ++i) {
+                const int c = b0 + wave + 4 * i;
+                const int j = c < n ? jl[c] : -1;
+                const size_t row = staged ? (size_t)(kc + c) : (size_t)(j < 0 ? 0 : j);
+                const uint4* gp = reinterpret_cast<const uint4*>(e.gd + row * 2 * d);
+#pragma unroll
+                for (int r = 0; r < NV; ++r) gv[i][r] = j >= 0 ? gp[r * kWave + lane] : make_uint4(0u, 0u, 0u, 0u);
+            }
+#pragma unroll
+            for (int cc = 0; cc < B; ++cc) {
+                const int c = b0 + cc;
+                const int j = c < n ? jl[c] : -1;
+                const size_t row = staged ? (size_t)(kc + c) : (size_t)(j < 0 ? 0 : j);
+                const uint4* dp = reinterpret_cast<const uint4*>(e.gd + row * 2 * d + d);
+#pragma unroll
+                for (int r = 0; r < RG; ++r) {
+                    const int piece = tid + 256 * r;
+                    dv[cc][r] = (j >= 0 && piece < VPR) ? dp[piece] : make_uint4(0u, 0u, 0u, 0u);
+                }
+            }
+            // ---- gate: h_c = SiLU(x . gate_c) * v_c * scale
+#pragma unroll
+            for (int i = 0; i < BG; ++i) {
+                const int c = b0 + wave + 4 * i;
+                float g = 0.0f;
+#pragma unroll
+                for (int r = 0; r < NV; ++r) {
+                    g = dot2(xr[r].x, gv[i][r].x, g);
+                    g = dot2(xr[r].y, gv[i][r].y, g);
+                    g = dot2(xr[r].z, gv[i][r].z, g);
+                    g = dot2(xr[r].w, gv[i][r].w, g);
+                }
+                g = wave_allreduce_sum(g);
+                if (lane == 0) hl[wave + 4 * i] = (c < n && jl[c] >= 0) ? silu(g) * vl[c] * out_scale : 0.0f;
+            }
+            __syncthreads();
+            // ---- down: acc += h_c * (this thread's pieces of row c)
+#pragma unroll
+            for (int cc = 0; cc < B; ++cc) {
+                const float h = hl[cc];
+#pragma unroll
+                for (int r = 0; r < RG; ++r) {
+                    const uint32_t wds[4] = {dv[cc][r].x, dv[cc][r].y, dv[cc][r].z, dv[cc][r].w};
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        const h16x2 p = as_h2(wds[q]);
+                        acc[r * 8 + 2 * q + 0] = fmaf(h, (float)p.x, acc[r * 8 + 2 * q + 0]);
+                        acc[r * 8 + 2 * q + 1] = fmaf(h, (float)p.y, acc[r * 8 + 2 * q + 1]);
+                    }
+                }
+            }
+            __syncthreads();  // hl is rewritten by the next batch
+        }
+        __syncthreads();  // jl / vl are rewritten by the next chunk
     }
 
-    // lane holds columns r*512 + lane*8 + e  (e < 8) of its wave's partial y
+    // thread owns output columns [8 * piece, 8 * piece + 8) for piece = tid + 256 r
+    float* out = partial + ((size_t)task * gridDim.x + blockIdx.x) * d;
 #pragma unroll
-    for (int r = 0; r < NV; ++r) {
-        float4* dst = reinterpret_cast<float4*>(red + (size_t)wave * d + r * 512 + lane * 8);
-        dst[0] = make_float4(acc[r * 8 + 0], acc[r * 8 + 1], acc[r * 8 + 2], acc[r * 8 + 3]);
-        dst[1] = make_float4(acc[r * 8 + 4], acc[r * 8 + 5], acc[r * 8 + 6], acc[r * 8 + 7]);
-    }
-    __syncthreads();
-    float4* out = reinterpret_cast<float4*>(partial + ((size_t)task * gridDim.x + blockIdx.x) * d);
-    const float4* r0 = reinterpret_cast<const float4*>(red);
-    for (int i = tid; i < d / 4; i += 256) {
-        float4 a = r0[i], b = r0[d / 4 + i], c = r0[2 * (d / 4) + i], e4 = r0[3 * (d / 4) + i];
-        out[i] = make_float4((a.x + b.x) + (c.x + e4.x), (a.y + b.y) + (c.y + e4.y), (a.z + b.z) + (c.z + e4.z),
-                             (a.w + b.w) + (c.w + e4.w));
+    for (int r = 0; r < RG; ++r) {
+        const int piece = tid + 256 * r;
+        if (piece < VPR) {
+            float4* o4 = reinterpret_cast<float4*>(out + (size_t)piece * 8);
+            o4[0] = make_float4(acc[r * 8 + 0], acc[r * 8 + 1], acc[r * 8 + 2], acc[r * 8 + 3]);
+            o4[1] = make_float4(acc[r * 8 + 4], acc[r * 8 + 5], acc[r * 8 + 6], acc[r * 8 + 7]);
+        }
     }
 }
 
@@ -97,35 +217,34 @@ int gd_blocks(int n_tasks, int f) {
     if (n_tasks <= 0) return 1;
     int nblk = kNumCU / n_tasks;
     nblk = nblk < 1 ? 1 : nblk;
-    nblk = nblk > kNumCU ? kNumCU : nblk;
-    const int by_f = (f + 3) / 4;  // never more waves than channels
+    const int by_f = (f + 3) / 4;  // a workgroup should have at least a few channels to look at
     nblk = nblk > by_f ? by_f : nblk;
     return nblk < 1 ? 1 : nblk;
 }
 
 template <int NV>
 static hipError_t launch_nv(const TaskMap& map, int staged, int gd_rows, const h16* x, const float* v,
-                            const int32_t* idx, const int32_t* count, const float* task_scale, float* partial, int f,
-                            int n_tasks, int nblk, hipStream_t stream) {
-    constexpr size_t lds = (size_t)4 * 512 * NV * sizeof(float);
-    static bool attr_set = false;
-    if (!attr_set && lds > 48 * 1024) {
-        hipError_t rc = hipFuncSetAttribute(reinterpret_cast<const void*>(&gate_down_kernel<NV>),
-                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (rc != hipSuccess) return rc;
-        attr_set = true;
-    }
-    gate_down_kernel<NV><<<dim3(nblk, n_tasks), dim3(256), lds, stream>>>(map, staged, gd_rows, x, v, idx, count,
-                                                                         task_scale, partial, f);
+                            const uint32_t* mask_words, int32_t* idx, int32_t* count, const float* task_scale,
+                            float* partial, int f, int n_tasks, int nblk, hipStream_t stream) {
+    dim3 grid(nblk, n_tasks), block(256);
+    if (mask_words)
+        gate_down_kernel<NV, true><<<grid, block, 0, stream>>>(map, staged, gd_rows, x, v, mask_words, idx, count,
+                                                              task_scale, partial, f);
+    else
+        gate_down_kernel<NV, false><<<grid, block, 0, stream>>>(map, staged, gd_rows, x, v, nullptr, idx, count,
+                                                               task_scale, partial, f);
     return hipGetLastError();
 }
 
 hipError_t launch_gate_down(const TaskMap& map, int staged, int gd_rows, const h16* x, const float* v,
-                            const int32_t* idx, const int32_t* count, const float* task_scale, float* partial, int d,
-                            int f, int n_tasks, int nblk, hipStream_t stream) {
+                            const uint32_t* mask_words, int32_t* idx, int32_t* count, const float* task_scale,
+                            float* partial, int d, int f, int n_tasks, int nblk, hipStream_t stream) {
     if (n_tasks == 0) return hipSuccess;
-#define FLOE_NV_CASE(N) \
-    case N: return launch_nv<N>(map, staged, gd_rows, x, v, idx, count, task_scale, partial, f, n_tasks, nblk, stream);
+    if (mask_words && mask_words_per_task(f) > kMaxMaskWords) return hipErrorInvalidValue;
+#define FLOE_NV_CASE(N)                                                                                            \
+    case N:                                                                                                        \
+        return launch_nv<N>(map, staged, gd_rows, x, v, mask_words, idx, count, task_scale, partial, f, n_tasks, nblk, \
+                            stream);
     switch (d / 512) {
         FLOE_NV_CASE(1) FLOE_NV_CASE(2) FLOE_NV_CASE(3) FLOE_NV_CASE(4) FLOE_NV_CASE(5) FLOE_NV_CASE(6)
         FLOE_NV_CASE(7) FLOE_NV_CASE(8) FLOE_NV_CASE(9) FLOE_NV_CASE(10) FLOE_NV_CASE(11) FLOE_NV_CASE(12)

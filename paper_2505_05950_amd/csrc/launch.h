@@ -1,49 +1,62 @@
-// Internal launcher prototypes (host side).  Every launcher validates nothing: shapes are checked once
-// in api.cpp against the limits each kernel states, before anything is enqueued.
+// Internal launcher prototypes (host side).  Launchers validate nothing: shapes are checked once in
+// api.hip against the limits each kernel states, before anything is enqueued.
 #pragma once
 
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
 #include "floe_dev.h"
+#include "xprep.h"
 
 namespace floe {
 
 constexpr int kNumCU = 256;  // MI355X
 
+// true when the packed-fp16 INT2 kernel (and its prepared activations) applies to this shape
+inline bool int2_fast_shape(int d, int bits, int group) {
+    return bits == 2 && group >= 64 && (d == 1024 || d == 2048 || d == 4096);
+}
+__host__ __device__ inline int mask_words_per_task(int f) { return (f + 31) / 32; }
+
 // S0
 hipError_t launch_quantize(const h16* w, uint32_t* codes, h16* scale, h16* zero, int d, int f, int bits, int group,
                            hipStream_t stream);
 
-// S2: v[task][j] for task in [0, n_tasks); token of a task = task / map.slots
-hipError_t launch_up_gemv(const TaskMap& map, const h16* x, float* v, int d, int f, int bits, int group, int n_tasks,
-                          hipStream_t stream);
+// S2 (+ the comparison of S3): v[task][j] for task in [0, n_tasks); token of a task = task / map.slots.
+// xprep: prepared activations or nullptr (then the kernel prepares them itself).
+// task_tau / mask_words: when both are given, bit (j % 32) of mask_words[task][j / 32] = (|v_j| > tau[task]).
+hipError_t launch_up_gemv(const TaskMap& map, const h16* x, const XPrep* xprep, float* v, const float* task_tau,
+                          uint32_t* mask_words, int d, int f, int bits, int group, int n_tasks, hipStream_t stream);
 
-// S3: per task threshold tau[task]
+// S3 as a kernel of its own: per task threshold tau[task]
 hipError_t launch_select(const float* v, int f, int n_tasks, const float* tau, int32_t* idx, int32_t* count,
                          hipStream_t stream);
 
-// S4+S5: partial[task][blk][d]; returns the number of blocks per task through gd_blocks()
+// S3 (compaction) + S4 + S5.  Index lists come either from mask_words (then idx/count are WRITTEN, both
+// may be nullptr) or, with mask_words == nullptr, from idx/count (read).  partial[task][blk][d].
 int gd_blocks(int n_tasks, int f);
 hipError_t launch_gate_down(const TaskMap& map, int staged, int gd_rows, const h16* x, const float* v,
-                            const int32_t* idx, const int32_t* count, const float* task_scale, float* partial, int d,
-                            int f, int n_tasks, int nblk, hipStream_t stream);
+                            const uint32_t* mask_words, int32_t* idx, int32_t* count, const float* task_scale,
+                            float* partial, int d, int f, int n_tasks, int nblk, hipStream_t stream);
 
 // S6 (and the "+=" of the one-expert entry points): reduce partial over blocks and slots.
 //   y_acc != nullptr: y_acc[t][i] += sum;   y_half != nullptr: y_half[t][i] = fp16(sum)
 hipError_t launch_combine(const float* partial, int d, int T, int slots, int nblk, float* y_acc, h16* y_half,
                           hipStream_t stream);
 
-// S1: router + task table (expert id, weight, tau per task) and optional stats seed
+// S1: router + per-task table (resolved expert pointers, weight, tau) + prepared activations
 struct RouterArgs {
     const h16* router_cm;
     const h16* x;
     const float* tau;
     int32_t tau_stride_t;
     int32_t n_experts, top_k, n_shared, renormalize, d;
-    int32_t* task_expert;
-    float* task_weight;
-    float* task_tau;
+    const DevExpert* table;   // all experts of the layer
+    DevExpert* task_table;    // [n_tasks] out
+    int32_t* task_expert;     // [n_tasks] out
+    float* task_weight;       // [n_tasks] out
+    float* task_tau;          // [n_tasks] out
+    XPrep xprep;              // xs == nullptr: not wanted
 };
 hipError_t launch_router(const RouterArgs& a, int T, hipStream_t stream);
 
@@ -58,7 +71,7 @@ hipError_t launch_stats(const int32_t* task_expert, const int32_t* count, const 
                         int n_tasks, hipStream_t stream);
 
 // S7
-hipError_t launch_stage(const h16* host_gd_dev, int d, int f, const int32_t* idx, const int32_t* count, int capacity_rows,
-                        h16* dst, int32_t* overflow, hipStream_t stream);
+hipError_t launch_stage(const h16* host_gd_dev, int d, int f, const int32_t* idx, const int32_t* count,
+                        int capacity_rows, h16* dst, int32_t* overflow, hipStream_t stream);
 
 }  // namespace floe

@@ -5,10 +5,42 @@
 // slots 0..top_k-1 routed (descending probability), then the n_shared always-on experts with weight 1.
 #include "floe_dev.h"
 #include "launch.h"
+#include "xprep.h"
 
 namespace floe {
 
 constexpr int kMaxExperts = 1024;
+
+// All loads of a dot product are in flight together: a lane fetches its 16-byte pieces of x once
+// (up to 16 of them, d <= 8192) and of the current expert row, then reduces with packed dot products.
+template <int UPC>
+__device__ __forceinline__ void write_xprep(const RouterArgs& a, int t, int lane) {
+    // lanes 0..UPC-1 of one wave prepare one unit each (see xprep.h)
+    const int d = UPC * 64;
+    const int u = lane < UPC ? lane : UPC - 1;
+    uint32_t raw[32];
+    const uint4* xq = reinterpret_cast<const uint4*>(a.x + (size_t)t * d + u * 64);
+#pragma unroll
+    for (int r = 0; r < 8; ++r) {
+        const uint4 q = xq[r];
+        raw[4 * r + 0] = q.x; raw[4 * r + 1] = q.y; raw[4 * r + 2] = q.z; raw[4 * r + 3] = q.w;
+    }
+    float amax = unit_amax(raw);
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) amax = fmaxf(amax, __shfl_xor(amax, o, kWave));
+    const int down = xprep_down(amax);
+    uint32_t xs[32];
+    float Xoff, Xg;
+    unit_prepare(raw, down, xs, Xoff, Xg);
+    if (lane < UPC) {
+#pragma unroll
+        for (int r = 0; r < 8; ++r)
+            a.xprep.xs[((size_t)t * 8 + r) * UPC + u] = make_uint4(xs[4 * r], xs[4 * r + 1], xs[4 * r + 2], xs[4 * r + 3]);
+        a.xprep.xoff[(size_t)t * UPC + u] = Xoff;
+        a.xprep.xg[(size_t)t * UPC + u] = Xg;
+        if (lane == 0) a.xprep.inv_p[t] = ldexpf(1.0f, down);
+    }
+}
 
 __global__ __launch_bounds__(256) void router_kernel(RouterArgs a) {
     __shared__ float prob[kMaxExperts];
@@ -18,21 +50,34 @@ __global__ __launch_bounds__(256) void router_kernel(RouterArgs a) {
     const int d = a.d;
     const int slots = a.top_k + a.n_shared;
     const h16* xt = a.x + (size_t)t * d;
+    const int nvec = d / 512;  // 16-byte pieces per lane (d % 512 == 0, d <= 8192)
     if (a.top_k > 0) {
+        uint4 xv[16];
+        const uint4* xp = reinterpret_cast<const uint4*>(xt);
+#pragma unroll
+        for (int r = 0; r < 16; ++r) xv[r] = r < nvec ? xp[r * kWave + lane] : make_uint4(0u, 0u, 0u, 0u);
         for (int e = wave; e < a.n_experts; e += 4) {
             const uint4* wp = reinterpret_cast<const uint4*>(a.router_cm + (size_t)e * d);
-            const uint4* xp = reinterpret_cast<const uint4*>(xt);
+            uint4 w[16];
+#pragma unroll
+            for (int r = 0; r < 16; ++r) w[r] = r < nvec ? wp[r * kWave + lane] : make_uint4(0u, 0u, 0u, 0u);
             float acc = 0.0f;
-            for (int i = lane; i < d / 8; i += kWave) {
-                const uint4 w = wp[i], xv = xp[i];
-                acc = dot2(xv.x, w.x, acc);
-                acc = dot2(xv.y, w.y, acc);
-                acc = dot2(xv.z, w.z, acc);
-                acc = dot2(xv.w, w.w, acc);
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                acc = dot2(xv[r].x, w[r].x, acc);
+                acc = dot2(xv[r].y, w[r].y, acc);
+                acc = dot2(xv[r].z, w[r].z, acc);
+                acc = dot2(xv[r].w, w[r].w, acc);
             }
             acc = wave_allreduce_sum(acc);
             if (lane == 0) prob[e] = acc;
         }
+    }
+    // prepared activations for the packed INT2 GEMV: the last wave does it while wave 0 routes
+    if (a.xprep.xs != nullptr && wave == 3) {
+        if (d == 4096) write_xprep<64>(a, t, lane);
+        else if (d == 2048) write_xprep<32>(a, t, lane);
+        else if (d == 1024) write_xprep<16>(a, t, lane);
     }
     __syncthreads();
     if (tid == 0) {
@@ -70,6 +115,7 @@ __global__ __launch_bounds__(256) void router_kernel(RouterArgs a) {
         for (int s = 0; s < slots; ++s) {
             const int e = a.task_expert[t * slots + s];
             a.task_tau[t * slots + s] = a.tau[(size_t)t * a.tau_stride_t + e];
+            a.task_table[t * slots + s] = a.table[e];
         }
     }
 }

@@ -5,6 +5,7 @@
 // so the per-weight work is "extract the code, multiply-accumulate with x".
 #include "floe_dev.h"
 #include "launch.h"
+#include "xprep.h"
 
 namespace floe {
 
@@ -24,16 +25,21 @@ __device__ __forceinline__ uint32_t unit_code(const uint32_t (&w)[BITS], int m) 
 
 template <int BITS>
 __global__ __launch_bounds__(256) void up_gemv_generic_kernel(TaskMap map, const h16* __restrict__ x,
-                                                              float* __restrict__ v, int d, int f, int gshift) {
+                                                              float* __restrict__ v,
+                                                              const float* __restrict__ task_tau,
+                                                              uint32_t* __restrict__ mask_words, int d, int f,
+                                                              int gshift) {
     constexpr int kChPerWave = 8;
     __shared__ float xT[32 * 256];
     __shared__ float Xu[256];
+    __shared__ uint32_t mw;
     const int tid = threadIdx.x;
     const int task = blockIdx.y;
     const int t = task / map.slots;
     const DevExpert e = task_expert_of(map, task);
     const int U = d >> 5;
     const h16* xt = x + (size_t)t * d;
+    if (tid == 0) mw = 0u;
     for (int i = tid; i < d; i += 256) xT[(i & 31) * U + (i >> 5)] = (float)xt[i];
     __syncthreads();
     for (int u = tid; u < U; u += 256) {
@@ -43,10 +49,13 @@ __global__ __launch_bounds__(256) void up_gemv_generic_kernel(TaskMap map, const
         Xu[u] = s;
     }
     __syncthreads();
+    const bool want_mask = task_tau != nullptr && mask_words != nullptr;
+    const float tau = want_mask ? task_tau[task] : 0.0f;
     const int wpc = d * BITS / 32;
     const int G = d >> gshift;
     const int wave = tid >> 6, lane = tid & 63;
     const int j0 = (blockIdx.x * 4 + wave) * kChPerWave;
+    uint32_t bits = 0u;
     for (int c = 0; c < kChPerWave; ++c) {
         const int j = j0 + c;
         if (j >= f) break;  // wave-uniform
@@ -65,6 +74,12 @@ __global__ __launch_bounds__(256) void up_gemv_generic_kernel(TaskMap map, const
         }
         part = wave_allreduce_sum(part);
         if (lane == 0) v[(size_t)task * f + j] = part;
+        if (fabsf(part) > tau) bits |= 1u << (wave * kChPerWave + c);
+    }
+    if (want_mask) {
+        if (lane == 0 && bits) atomicOr(&mw, bits);
+        __syncthreads();
+        if (tid == 0) mask_words[(size_t)task * mask_words_per_task(f) + blockIdx.x] = mw;
     }
 }
 
@@ -77,13 +92,18 @@ __global__ __launch_bounds__(256) void up_gemv_generic_kernel(TaskMap map, const
 // (c = 64, 16, 4) from the word itself, the word << 4 and the word >> 6, so 16 codes cost
 // 2 shifts + 8 and-or + 8 dot2.  Pairs are (code m, code m+8) of a word: the two halves of the register.
 // x is pre-scaled by a power of two so that 64*|x| stays finite in fp16; v is scaled back at the end.
+// The prepared activations come from HBM (written once per token by the router kernel) when PREPPED,
+// otherwise every wave prepares them itself.
 // ---------------------------------------------------------------------------------------------------
-template <int UPC>
-__global__ __launch_bounds__(256) void up_gemv_int2_kernel(TaskMap map, const h16* __restrict__ x,
-                                                           float* __restrict__ v, int f, int gshift) {
+template <int UPC, bool PREPPED>
+__global__ __launch_bounds__(256) void up_gemv_int2_kernel(TaskMap map, const h16* __restrict__ x, XPrep xp,
+                                                           float* __restrict__ v,
+                                                           const float* __restrict__ task_tau,
+                                                           uint32_t* __restrict__ mask_words, int f, int gshift) {
     constexpr int CPW = kWave / UPC;  // channels per wave pass
     constexpr int kPasses = 8;
     constexpr int d = UPC * 64;
+    __shared__ uint32_t mw[CPW];
     const int tid = threadIdx.x;
     const int wave = tid >> 6, lane = tid & 63;
     const int sub = lane / UPC, u = lane % UPC;
@@ -91,50 +111,11 @@ __global__ __launch_bounds__(256) void up_gemv_int2_kernel(TaskMap map, const h1
     const int t = task / map.slots;
     const DevExpert e = task_expert_of(map, task);
     const int G = d >> gshift;
+    const bool want_mask = task_tau != nullptr && mask_words != nullptr;
+    const float tau = want_mask ? task_tau[task] : 0.0f;
+    if (tid < CPW) mw[tid] = 0u;
 
-    // ---- x prologue: this lane's 64 activations -> 32 scaled fp16 pairs
-    uint32_t raw[32];
-    {
-        const uint4* xp = reinterpret_cast<const uint4*>(x + (size_t)t * d + u * 64);
-#pragma unroll
-        for (int r = 0; r < 8; ++r) {
-            uint4 q = xp[r];
-            raw[4 * r + 0] = q.x; raw[4 * r + 1] = q.y; raw[4 * r + 2] = q.z; raw[4 * r + 3] = q.w;
-        }
-    }
-    float amax = 0.0f;
-#pragma unroll
-    for (int r = 0; r < 32; ++r) {
-        h16x2 p = as_h2(raw[r]);
-        amax = fmaxf(amax, fmaxf(fabsf((float)p.x), fabsf((float)p.y)));
-    }
-#pragma unroll
-    for (int o = UPC / 2; o >= 1; o >>= 1) amax = fmaxf(amax, __shfl_xor(amax, o, kWave));
-    int down = 0;  // x' = x * 2^-down keeps 64 * |x'| below 2^15
-    if (amax >= 256.0f && amax < 3.0e38f) down = ilogbf(amax) - 7;
-    const h16 pscale = (h16)ldexpf(1.0f, -down);
-    const float inv_p = ldexpf(1.0f, down);
-    const h16x2 ones = {(h16)1.0f, (h16)1.0f};
-    const float cm[8] = {64.f, 16.f, 64.f, 16.f, 4.f, 64.f, 16.f, 4.f};
-    uint32_t xs[32];
-    float Xg = 0.0f, Xoff = 0.0f;
-#pragma unroll
-    for (int w = 0; w < 4; ++w) {
-#pragma unroll
-        for (int m = 0; m < 8; ++m) {
-            const uint32_t A = raw[8 * w + m / 2], B = raw[8 * w + 4 + m / 2];
-            const uint32_t pr = (m & 1) ? ((A >> 16) | (B & 0xFFFF0000u)) : ((A & 0xFFFFu) | (B << 16));
-            h16x2 p = as_h2(pr) * (h16x2){pscale, pscale};
-            Xg = __builtin_amdgcn_fdot2(p, ones, Xg, false);
-            p = p * (h16x2){(h16)cm[m], (h16)cm[m]};
-            Xoff = __builtin_amdgcn_fdot2(p, ones, Xoff, false);
-            xs[8 * w + m] = as_u32(p);
-        }
-    }
-    uint32_t magic = 0x3C003C00u;
-    asm volatile("" : "+v"(magic));  // keep it in a VGPR: v_and_or_b32 takes one scalar operand only
-
-    // ---- main: kPasses passes of CPW channels per wave, all loads issued first
+    // ---- issue the weight loads first: kPasses passes of CPW channels per wave
     const int jw = (blockIdx.x * 4 + wave) * (kPasses * CPW);
     const uint4* codes4 = reinterpret_cast<const uint4*>(e.codes);
     uint4 cw[kPasses];
@@ -148,6 +129,38 @@ __global__ __launch_bounds__(256) void up_gemv_int2_kernel(TaskMap map, const h1
         sc[p] = e.scale[mi];
         zr[p] = e.zero[mi];
     }
+
+    // ---- activations of this lane's unit: 32 scaled fp16 pairs
+    uint32_t xs[32];
+    float Xg, Xoff, inv_p;
+    if (PREPPED) {
+#pragma unroll
+        for (int r = 0; r < 8; ++r) {
+            const uint4 q = xp.xs[((size_t)t * 8 + r) * UPC + u];
+            xs[4 * r + 0] = q.x; xs[4 * r + 1] = q.y; xs[4 * r + 2] = q.z; xs[4 * r + 3] = q.w;
+        }
+        Xoff = xp.xoff[(size_t)t * UPC + u];
+        Xg = xp.xg[(size_t)t * UPC + u];
+        inv_p = xp.inv_p[t];
+    } else {
+        uint32_t raw[32];
+        const uint4* xq = reinterpret_cast<const uint4*>(x + (size_t)t * d + u * 64);
+#pragma unroll
+        for (int r = 0; r < 8; ++r) {
+            const uint4 q = xq[r];
+            raw[4 * r + 0] = q.x; raw[4 * r + 1] = q.y; raw[4 * r + 2] = q.z; raw[4 * r + 3] = q.w;
+        }
+        float amax = unit_amax(raw);
+#pragma unroll
+        for (int o = UPC / 2; o >= 1; o >>= 1) amax = fmaxf(amax, __shfl_xor(amax, o, kWave));
+        const int down = xprep_down(amax);
+        inv_p = ldexpf(1.0f, down);
+        unit_prepare(raw, down, xs, Xoff, Xg);
+    }
+    uint32_t magic = 0x3C003C00u;
+    asm volatile("" : "+v"(magic));  // keep it in a VGPR: v_and_or_b32 takes one scalar operand only
+    __syncthreads();                 // mw zeroed
+
 #pragma unroll
     for (int p = 0; p < kPasses; ++p) {
         const int j = jw + p * CPW + sub;
@@ -167,8 +180,19 @@ __global__ __launch_bounds__(256) void up_gemv_int2_kernel(TaskMap map, const h1
         }
         const float s = (float)sc[p], z = (float)zr[p];
         float part = s * fmaf(-z, Xg, dot - Xoff);
-        part = group_allreduce_sum<UPC>(part);
-        if (u == 0 && j < f) v[(size_t)task * f + j] = part * inv_p;
+        part = group_reduce_sum_to_last<UPC>(part) * inv_p;
+        if (u == UPC - 1 && j < f) {
+            v[(size_t)task * f + j] = part;
+            if (want_mask && fabsf(part) > tau) {
+                const int local = j - blockIdx.x * (32 * CPW);
+                atomicOr(&mw[local >> 5], 1u << (local & 31));
+            }
+        }
+    }
+    if (want_mask) {
+        __syncthreads();
+        const int word = blockIdx.x * CPW + tid;
+        if (tid < CPW && word < mask_words_per_task(f)) mask_words[(size_t)task * mask_words_per_task(f) + word] = mw[tid];
     }
 }
 
@@ -178,25 +202,37 @@ static int ilog2_exact(int g) {
     return s;
 }
 
-hipError_t launch_up_gemv(const TaskMap& map, const h16* x, float* v, int d, int f, int bits, int group, int n_tasks,
-                          hipStream_t stream) {
+template <int UPC>
+static void launch_int2(bool prepped, dim3 grid, hipStream_t stream, const TaskMap& map, const h16* x, const XPrep& xp,
+                        float* v, const float* task_tau, uint32_t* mask_words, int f, int gshift) {
+    if (prepped)
+        up_gemv_int2_kernel<UPC, true><<<grid, dim3(256), 0, stream>>>(map, x, xp, v, task_tau, mask_words, f, gshift);
+    else
+        up_gemv_int2_kernel<UPC, false><<<grid, dim3(256), 0, stream>>>(map, x, xp, v, task_tau, mask_words, f, gshift);
+}
+
+hipError_t launch_up_gemv(const TaskMap& map, const h16* x, const XPrep* xprep, float* v, const float* task_tau,
+                          uint32_t* mask_words, int d, int f, int bits, int group, int n_tasks, hipStream_t stream) {
     if (f == 0 || n_tasks == 0) return hipSuccess;
     const int gshift = ilog2_exact(group);
     dim3 block(256);
-    if (bits == 2 && group >= 64 && (d == 1024 || d == 2048 || d == 4096)) {
+    if (int2_fast_shape(d, bits, group)) {
         const int upc = d / 64;
         const int ch_per_wg = 4 * 8 * (64 / upc);
         dim3 grid((f + ch_per_wg - 1) / ch_per_wg, n_tasks);
-        if (upc == 64) up_gemv_int2_kernel<64><<<grid, block, 0, stream>>>(map, x, v, f, gshift);
-        else if (upc == 32) up_gemv_int2_kernel<32><<<grid, block, 0, stream>>>(map, x, v, f, gshift);
-        else up_gemv_int2_kernel<16><<<grid, block, 0, stream>>>(map, x, v, f, gshift);
+        const bool prepped = xprep != nullptr && xprep->xs != nullptr;
+        XPrep xp{};
+        if (prepped) xp = *xprep;
+        if (upc == 64) launch_int2<64>(prepped, grid, stream, map, x, xp, v, task_tau, mask_words, f, gshift);
+        else if (upc == 32) launch_int2<32>(prepped, grid, stream, map, x, xp, v, task_tau, mask_words, f, gshift);
+        else launch_int2<16>(prepped, grid, stream, map, x, xp, v, task_tau, mask_words, f, gshift);
         return hipGetLastError();
     }
     dim3 grid((f + 31) / 32, n_tasks);
     switch (bits) {
-        case 2: up_gemv_generic_kernel<2><<<grid, block, 0, stream>>>(map, x, v, d, f, gshift); break;
-        case 3: up_gemv_generic_kernel<3><<<grid, block, 0, stream>>>(map, x, v, d, f, gshift); break;
-        default: up_gemv_generic_kernel<4><<<grid, block, 0, stream>>>(map, x, v, d, f, gshift); break;
+        case 2: up_gemv_generic_kernel<2><<<grid, block, 0, stream>>>(map, x, v, task_tau, mask_words, d, f, gshift); break;
+        case 3: up_gemv_generic_kernel<3><<<grid, block, 0, stream>>>(map, x, v, task_tau, mask_words, d, f, gshift); break;
+        default: up_gemv_generic_kernel<4><<<grid, block, 0, stream>>>(map, x, v, task_tau, mask_words, d, f, gshift); break;
     }
     return hipGetLastError();
 }
