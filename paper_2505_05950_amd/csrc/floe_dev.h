@@ -81,6 +81,21 @@ __device__ __forceinline__ float wave_allreduce_sum(float x) {
     return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, x), 63));
 }
 
+// Optional phase timeline for tuning builds (-DFLOE_TIMELINE): thread 0 of each workgroup stamps the
+// constant 100 MHz clock into g_timeline[wg * 16 + slot].  Compiled out of the product library.
+#ifdef FLOE_TIMELINE
+static __device__ unsigned long long* g_timeline = nullptr;  // one copy per translation unit
+#define FLOE_TL(slot)                                                                                      \
+    do {                                                                                                   \
+        if (g_timeline && threadIdx.x == 0)                                                                \
+            g_timeline[((size_t)blockIdx.y * gridDim.x + blockIdx.x) * 16 + (slot)] = wall_clock64();      \
+    } while (0)
+#else
+#define FLOE_TL(slot) \
+    do {              \
+    } while (0)
+#endif
+
 __device__ __forceinline__ float silu(float g) { return g / (1.0f + __expf(-g)); }
 
 }  // namespace floe

@@ -44,7 +44,6 @@ __global__ __launch_bounds__(256) void gate_down_kernel(TaskMap map, int staged,
     __shared__ uint32_t words[FROM_MASK ? kMaxMaskWords : 1];
     __shared__ int wave_tot[4];
     __shared__ int jl[256];
-    __shared__ float vl[256];
     __shared__ float hl[B];
     const int tid = threadIdx.x;
     const int wave = tid >> 6, lane = tid & 63;
@@ -54,6 +53,7 @@ __global__ __launch_bounds__(256) void gate_down_kernel(TaskMap map, int staged,
     const float out_scale = task_scale ? task_scale[task] : 1.0f;
     const float* vt = v + (size_t)task * f;
 
+    FLOE_TL(0);
     uint4 xr[NV];
     {
         const uint4* xp = reinterpret_cast<const uint4*>(x + (size_t)t * d);
@@ -106,6 +106,7 @@ __global__ __launch_bounds__(256) void gate_down_kernel(TaskMap map, int staged,
     } else {
         K = count[task];
     }
+    FLOE_TL(1);
     const int Kc = min(K, staged ? gd_rows : f);
     const int per = (Kc + (int)gridDim.x - 1) / (int)gridDim.x;
     const int k0 = min(Kc, (int)blockIdx.x * per);
@@ -135,18 +136,20 @@ __global__ __launch_bounds__(256) void gate_down_kernel(TaskMap map, int staged,
                 if ((unsigned)j >= (unsigned)f) j = -1;  // a caller-supplied list may hold junk: never leave the matrix
             }
             jl[tid] = j;
-            vl[tid] = j >= 0 ? vt[j] : 0.0f;
         }
         __syncthreads();
+        FLOE_TL(2);
 
         for (int b0 = 0; b0 < n; b0 += B) {
             // ---- all loads of the batch
             uint4 gv[BG][NV];
             uint4 dv[B][RG];
+            float vj[BG];
 #pragma unroll
             for (int i = 0; i < BG; ++i) {
                 const int c = b0 + wave + 4 * i;
                 const int j = c < n ? jl[c] : -1;
+                vj[i] = j >= 0 ? vt[j] : 0.0f;  // same address in every lane; needed only after the dot product
                 const size_t row = staged ? (size_t)(kc + c) : (size_t)(j < 0 ? 0 : j);
                 const uint4* gp = reinterpret_cast<const uint4*>(e.gd + row * 2 * d);
 #pragma unroll
@@ -164,6 +167,7 @@ __global__ __launch_bounds__(256) void gate_down_kernel(TaskMap map, int staged,
                     dv[cc][r] = (j >= 0 && piece < VPR) ? dp[piece] : make_uint4(0u, 0u, 0u, 0u);
                 }
             }
+            FLOE_TL(3);
             // ---- gate: h_c = SiLU(x . gate_c) * v_c * scale
 #pragma unroll
             for (int i = 0; i < BG; ++i) {
@@ -177,9 +181,11 @@ __global__ __launch_bounds__(256) void gate_down_kernel(TaskMap map, int staged,
                     g = dot2(xr[r].w, gv[i][r].w, g);
                 }
                 g = wave_allreduce_sum(g);
-                if (lane == 0) hl[wave + 4 * i] = (c < n && jl[c] >= 0) ? silu(g) * vl[c] * out_scale : 0.0f;
+                if (lane == 0) hl[wave + 4 * i] = (c < n && jl[c] >= 0) ? silu(g) * vj[i] * out_scale : 0.0f;
             }
+            FLOE_TL(4);
             __syncthreads();
+            FLOE_TL(5);
             // ---- down: acc += h_c * (this thread's pieces of row c)
 #pragma unroll
             for (int cc = 0; cc < B; ++cc) {
@@ -195,9 +201,10 @@ __global__ __launch_bounds__(256) void gate_down_kernel(TaskMap map, int staged,
                     }
                 }
             }
+            FLOE_TL(6);
             __syncthreads();  // hl is rewritten by the next batch
         }
-        __syncthreads();  // jl / vl are rewritten by the next chunk
+        __syncthreads();  // jl is rewritten by the next chunk
     }
 
     // thread owns output columns [8 * piece, 8 * piece + 8) for piece = tid + 256 r
@@ -211,7 +218,14 @@ __global__ __launch_bounds__(256) void gate_down_kernel(TaskMap map, int staged,
             o4[1] = make_float4(acc[r * 8 + 4], acc[r * 8 + 5], acc[r * 8 + 6], acc[r * 8 + 7]);
         }
     }
+    FLOE_TL(7);
 }
+
+#ifdef FLOE_TIMELINE
+extern "C" int floe_debug_set_timeline_gate_down(unsigned long long* p) {
+    return (int)hipMemcpyToSymbol(HIP_SYMBOL(g_timeline), &p, sizeof(p));
+}
+#endif
 
 int gd_blocks(int n_tasks, int f) {
     if (n_tasks <= 0) return 1;
@@ -256,26 +270,32 @@ hipError_t launch_gate_down(const TaskMap& map, int staged, int gd_rows, const h
 
 // ---------------------------------------------------------------------------------------------------
 // S6: sum the partial results of every (slot, block) of a token, fold into y_acc and / or round to fp16.
-// A workgroup owns 64 output columns of one token: 16 threads (one float4 each) cover the columns,
-// the 16 thread rows split the partials between them and meet in LDS.
+// A workgroup owns 32 output columns of one token: 8 threads (one float4 each) cover the columns,
+// the 32 thread rows split the partials between them (eight loads in flight each) and meet in LDS.
 // ---------------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void combine_kernel(const float* __restrict__ partial, int d, int per_token,
                                                       float* __restrict__ y_acc, h16* __restrict__ y_half) {
-    __shared__ float4 red[16][16];
+    __shared__ float4 red[32][8];
     const int t = blockIdx.y;
-    const int cg = threadIdx.x & 15, pg = threadIdx.x >> 4;
-    const int c4 = blockIdx.x * 16 + cg;  // column / 4   (d % 64 == 0)
+    const int cg = threadIdx.x & 7, pg = threadIdx.x >> 3;
+    const int c4 = blockIdx.x * 8 + cg;  // column / 4   (d % 32 == 0)
     const float4* p = reinterpret_cast<const float4*>(partial + (size_t)t * per_token * d) + c4;
     float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
-    for (int b = pg; b < per_token; b += 16) {
-        const float4 a = p[(size_t)b * (d / 4)];
-        s.x += a.x; s.y += a.y; s.z += a.z; s.w += a.w;
+    for (int b0 = pg; b0 < per_token; b0 += 32 * 8) {
+        float4 a[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {  // eight independent loads in flight
+            const int b = b0 + 32 * i;
+            a[i] = b < per_token ? p[(size_t)b * (d / 4)] : make_float4(0.f, 0.f, 0.f, 0.f);
+        }
+#pragma unroll
+        for (int i = 0; i < 8; ++i) { s.x += a[i].x; s.y += a[i].y; s.z += a[i].z; s.w += a[i].w; }
     }
     red[pg][cg] = s;
     __syncthreads();
     if (pg != 0) return;
 #pragma unroll
-    for (int r = 1; r < 16; ++r) {
+    for (int r = 1; r < 32; ++r) {
         const float4 a = red[r][cg];
         s.x += a.x; s.y += a.y; s.z += a.z; s.w += a.w;
     }
@@ -295,7 +315,7 @@ __global__ __launch_bounds__(256) void combine_kernel(const float* __restrict__ 
 hipError_t launch_combine(const float* partial, int d, int T, int slots, int nblk, float* y_acc, h16* y_half,
                           hipStream_t stream) {
     if (T == 0) return hipSuccess;
-    dim3 grid(d / 64, T);
+    dim3 grid(d / 32, T);
     combine_kernel<<<grid, dim3(256), 0, stream>>>(partial, d, slots * nblk, y_acc, y_half);
     return hipGetLastError();
 }

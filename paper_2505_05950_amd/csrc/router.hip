@@ -44,6 +44,8 @@ __device__ __forceinline__ void write_xprep(const RouterArgs& a, int t, int lane
 
 __global__ __launch_bounds__(256) void router_kernel(RouterArgs a) {
     __shared__ float prob[kMaxExperts];
+    __shared__ int sel_id[64];
+    __shared__ float sel_w[64];
     const int t = blockIdx.x;
     const int tid = threadIdx.x;
     const int wave = tid >> 6, lane = tid & 63;
@@ -99,24 +101,29 @@ __global__ __launch_bounds__(256) void router_kernel(RouterArgs a) {
                     if (p > bp) { bp = p; best = e; }   // strict: ties keep the lower id
                 }
                 if (best < 0) best = 0;  // only reachable with NaN logits: stay in bounds
-                prob[best] = -2.0f;  // taken
+                prob[best] = -2.0f;      // taken
                 const float pw = bp / sum;
-                a.task_expert[t * slots + r] = best;
-                a.task_weight[t * slots + r] = pw;
+                sel_id[r] = best;
+                sel_w[r] = pw;
                 sel += pw;
             }
             if (a.renormalize)
-                for (int r = 0; r < a.top_k; ++r) a.task_weight[t * slots + r] /= sel;
+                for (int r = 0; r < a.top_k; ++r) sel_w[r] /= sel;
         }
         for (int s = 0; s < a.n_shared; ++s) {
-            a.task_expert[t * slots + a.top_k + s] = a.n_experts + s;
-            a.task_weight[t * slots + a.top_k + s] = 1.0f;
+            sel_id[a.top_k + s] = a.n_experts + s;
+            sel_w[a.top_k + s] = 1.0f;
         }
-        for (int s = 0; s < slots; ++s) {
-            const int e = a.task_expert[t * slots + s];
-            a.task_tau[t * slots + s] = a.tau[(size_t)t * a.tau_stride_t + e];
-            a.task_table[t * slots + s] = a.table[e];
-        }
+    }
+    __syncthreads();
+    // one thread per slot resolves the expert: its pointers, weight and threshold go to the task table
+    if (tid < slots) {
+        const int e = sel_id[tid];
+        const int q = t * slots + tid;
+        a.task_expert[q] = e;
+        a.task_weight[q] = sel_w[tid];
+        a.task_tau[q] = a.tau[(size_t)t * a.tau_stride_t + e];
+        a.task_table[q] = a.table[e];
     }
 }
 
