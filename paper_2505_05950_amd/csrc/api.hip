@@ -201,7 +201,7 @@ int floe_up_gemv(const floe_shape* s, const uint32_t* codes, const floe_half* sc
     floe_expert e{};
     e.up_codes = codes; e.up_scale = scale; e.up_zero = zero;
     FLOE_LAUNCH(FLOE_KERNEL_UP_GEMV, (hipStream_t)stream,
-                launch_up_gemv(single_map(&e), reinterpret_cast<const h16*>(x), nullptr, v, nullptr, nullptr, s->d, s->f,
+                launch_up_gemv(single_map(&e), reinterpret_cast<const h16*>(x), nullptr, nullptr, v, nullptr, nullptr, s->d, s->f,
                                s->bits, s->group, T, (hipStream_t)stream));
     return FLOE_OK;
 }
@@ -269,13 +269,13 @@ int floe_expert_ffn_sparse(const floe_expert* e, const floe_half* x, int T, cons
     if (mask_path_ok(e->s.f)) {
         // the GEMV leaves one mask bit per channel; the gate/down kernel compacts them and writes idx / count
         FLOE_LAUNCH(FLOE_KERNEL_UP_GEMV, st,
-                    launch_up_gemv(map, xh, nullptr, v, tau, mask, e->s.d, e->s.f, e->s.bits, e->s.group, T, st));
+                    launch_up_gemv(map, xh, nullptr, nullptr, v, tau, mask, e->s.d, e->s.f, e->s.bits, e->s.group, T, st));
         FLOE_LAUNCH(FLOE_KERNEL_GATE_DOWN, st,
                     launch_gate_down(map, 0, e->s.f, xh, v, mask, idx, count, out_scale, partial, e->s.d, e->s.f, T,
                                      w.nblk, st));
     } else {
         FLOE_LAUNCH(FLOE_KERNEL_UP_GEMV, st,
-                    launch_up_gemv(map, xh, nullptr, v, nullptr, nullptr, e->s.d, e->s.f, e->s.bits, e->s.group, T, st));
+                    launch_up_gemv(map, xh, nullptr, nullptr, v, nullptr, nullptr, e->s.d, e->s.f, e->s.bits, e->s.group, T, st));
         FLOE_LAUNCH(FLOE_KERNEL_SELECT, st, launch_select(v, e->s.f, T, tau, idx, count, st));
         FLOE_LAUNCH(FLOE_KERNEL_GATE_DOWN, st,
                     launch_gate_down(map, 0, e->s.f, xh, v, nullptr, idx, count, out_scale, partial, e->s.d, e->s.f, T,
@@ -344,43 +344,62 @@ int floe_moe_layer_decode(const floe_layer* L, const floe_half* x, int T, floe_h
     const int slots = L->top_k + L->n_shared;
     const bool fast_up = int2_fast_shape(L->s.d, L->s.bits, L->s.group);
 
-    RouterArgs ra;
-    ra.router_cm = reinterpret_cast<const h16*>(L->router_cm);
-    ra.x = xh;
-    ra.tau = L->tau;
-    ra.tau_stride_t = L->tau_stride_t;
-    ra.n_experts = L->n_experts; ra.top_k = L->top_k; ra.n_shared = L->n_shared; ra.renormalize = L->renormalize;
-    ra.d = L->s.d;
-    ra.table = static_cast<const DevExpert*>(L->dev_table);
-    ra.task_table = task_table;
-    ra.task_expert = task_expert; ra.task_weight = task_weight; ra.task_tau = task_tau;
-    ra.xprep = XPrep{};
-    if (fast_up) {
-        ra.xprep.xs = reinterpret_cast<uint4*>(base + w.xs_off);
-        ra.xprep.xoff = reinterpret_cast<float*>(base + w.xoff_off);
-        ra.xprep.xg = reinterpret_cast<float*>(base + w.xg_off);
-        ra.xprep.inv_p = reinterpret_cast<float*>(base + w.invp_off);
-    }
-    FLOE_LAUNCH(FLOE_KERNEL_ROUTER, st, launch_router(ra, T, st));
-
     TaskMap map{};
     map.task_table = task_table;
     map.slots = slots;
-    if (mask_path_ok(L->s.f)) {
+    const bool mask_ok = mask_path_ok(L->s.f);
+    if (mask_ok && route_in_place_ok(L->s.d, L->s.bits, L->s.group, L->n_experts, L->top_k, L->n_shared)) {
+        // three kernels: [router + up GEMV + mask] -> [compaction + gate/down] -> [combine]
+        RouteArgs ro;
+        ro.router_cm = reinterpret_cast<const h16*>(L->router_cm);
+        ro.tau = L->tau;
+        ro.tau_stride_t = L->tau_stride_t;
+        ro.n_experts = L->n_experts; ro.top_k = L->top_k; ro.n_shared = L->n_shared; ro.renormalize = L->renormalize;
+        ro.table = static_cast<const DevExpert*>(L->dev_table);
+        ro.task_table = task_table;
+        ro.task_expert = task_expert; ro.task_weight = task_weight; ro.task_tau = task_tau;
         FLOE_LAUNCH(FLOE_KERNEL_UP_GEMV, st,
-                    launch_up_gemv(map, xh, fast_up ? &ra.xprep : nullptr, v, task_tau, mask, L->s.d, L->s.f, L->s.bits,
-                                   L->s.group, w.n_tasks, st));
+                    launch_up_gemv(map, xh, nullptr, &ro, v, nullptr, mask, L->s.d, L->s.f, L->s.bits, L->s.group,
+                                   w.n_tasks, st));
         FLOE_LAUNCH(FLOE_KERNEL_GATE_DOWN, st,
                     launch_gate_down(map, 0, L->s.f, xh, v, mask, nullptr, count, task_weight, partial, L->s.d, L->s.f,
                                      w.n_tasks, w.nblk, st));
     } else {
-        FLOE_LAUNCH(FLOE_KERNEL_UP_GEMV, st,
-                    launch_up_gemv(map, xh, fast_up ? &ra.xprep : nullptr, v, nullptr, nullptr, L->s.d, L->s.f,
-                                   L->s.bits, L->s.group, w.n_tasks, st));
-        FLOE_LAUNCH(FLOE_KERNEL_SELECT, st, launch_select(v, L->s.f, w.n_tasks, task_tau, idx, count, st));
-        FLOE_LAUNCH(FLOE_KERNEL_GATE_DOWN, st,
-                    launch_gate_down(map, 0, L->s.f, xh, v, nullptr, idx, count, task_weight, partial, L->s.d, L->s.f,
-                                     w.n_tasks, w.nblk, st));
+        RouterArgs ra;
+        ra.router_cm = reinterpret_cast<const h16*>(L->router_cm);
+        ra.x = xh;
+        ra.tau = L->tau;
+        ra.tau_stride_t = L->tau_stride_t;
+        ra.n_experts = L->n_experts; ra.top_k = L->top_k; ra.n_shared = L->n_shared; ra.renormalize = L->renormalize;
+        ra.d = L->s.d;
+        ra.table = static_cast<const DevExpert*>(L->dev_table);
+        ra.task_table = task_table;
+        ra.task_expert = task_expert; ra.task_weight = task_weight; ra.task_tau = task_tau;
+        ra.xprep = XPrep{};
+        if (fast_up) {
+            ra.xprep.xs = reinterpret_cast<uint4*>(base + w.xs_off);
+            ra.xprep.xoff = reinterpret_cast<float*>(base + w.xoff_off);
+            ra.xprep.xg = reinterpret_cast<float*>(base + w.xg_off);
+            ra.xprep.inv_p = reinterpret_cast<float*>(base + w.invp_off);
+        }
+        FLOE_LAUNCH(FLOE_KERNEL_ROUTER, st, launch_router(ra, T, st));
+        const XPrep* xpp = fast_up ? &ra.xprep : nullptr;
+        if (mask_ok) {
+            FLOE_LAUNCH(FLOE_KERNEL_UP_GEMV, st,
+                        launch_up_gemv(map, xh, xpp, nullptr, v, task_tau, mask, L->s.d, L->s.f, L->s.bits, L->s.group,
+                                       w.n_tasks, st));
+            FLOE_LAUNCH(FLOE_KERNEL_GATE_DOWN, st,
+                        launch_gate_down(map, 0, L->s.f, xh, v, mask, nullptr, count, task_weight, partial, L->s.d,
+                                         L->s.f, w.n_tasks, w.nblk, st));
+        } else {
+            FLOE_LAUNCH(FLOE_KERNEL_UP_GEMV, st,
+                        launch_up_gemv(map, xh, xpp, nullptr, v, nullptr, nullptr, L->s.d, L->s.f, L->s.bits,
+                                       L->s.group, w.n_tasks, st));
+            FLOE_LAUNCH(FLOE_KERNEL_SELECT, st, launch_select(v, L->s.f, w.n_tasks, task_tau, idx, count, st));
+            FLOE_LAUNCH(FLOE_KERNEL_GATE_DOWN, st,
+                        launch_gate_down(map, 0, L->s.f, xh, v, nullptr, idx, count, task_weight, partial, L->s.d,
+                                         L->s.f, w.n_tasks, w.nblk, st));
+        }
     }
     FLOE_LAUNCH(FLOE_KERNEL_COMBINE, st, launch_combine(partial, L->s.d, T, slots, w.nblk, nullptr, reinterpret_cast<h16*>(y), st));
     if (stats) FLOE_HIP(launch_stats(task_expert, count, task_weight, reinterpret_cast<SlotStat*>(stats), w.n_tasks, st));

@@ -81,6 +81,34 @@ __device__ __forceinline__ float wave_allreduce_sum(float x) {
     return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, x), 63));
 }
 
+// value of lane (lane rotated right by N inside its row of 16) -- a pure register move, no LDS
+template <int CTRL>
+__device__ __forceinline__ float dpp_movf(float x) {
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), CTRL, 0xF, 0xF, false));
+}
+template <int CTRL>
+__device__ __forceinline__ int dpp_movi(int x) {
+    return __builtin_amdgcn_update_dpp(0, x, CTRL, 0xF, 0xF, false);
+}
+
+// max over the row of 16 lanes, delivered to every lane of the row
+__device__ __forceinline__ float row16_allreduce_max(float x) {
+    x = fmaxf(x, dpp_movf<0x128>(x));
+    x = fmaxf(x, dpp_movf<0x124>(x));
+    x = fmaxf(x, dpp_movf<0x122>(x));
+    x = fmaxf(x, dpp_movf<0x121>(x));
+    return x;
+}
+
+// max over the 64 lanes (x >= 0 everywhere), returned to every lane
+__device__ __forceinline__ float wave_allreduce_max_nonneg(float x) {
+    x = row16_allreduce_max(x);
+    // lanes that a row_bcast does not write receive 0, which is neutral for non-negative inputs
+    x = fmaxf(x, __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0x142, 0xA, 0xF, false)));
+    x = fmaxf(x, __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0x143, 0xC, 0xF, false)));
+    return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, x), 63));
+}
+
 // Optional phase timeline for tuning builds (-DFLOE_TIMELINE): thread 0 of each workgroup stamps the
 // constant 100 MHz clock into g_timeline[wg * 16 + slot].  Compiled out of the product library.
 #ifdef FLOE_TIMELINE

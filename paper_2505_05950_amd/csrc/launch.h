@@ -6,6 +6,7 @@
 #include <stdint.h>
 
 #include "floe_dev.h"
+#include "route.h"
 #include "xprep.h"
 
 namespace floe {
@@ -25,8 +26,14 @@ hipError_t launch_quantize(const h16* w, uint32_t* codes, h16* scale, h16* zero,
 // S2 (+ the comparison of S3): v[task][j] for task in [0, n_tasks); token of a task = task / map.slots.
 // xprep: prepared activations or nullptr (then the kernel prepares them itself).
 // task_tau / mask_words: when both are given, bit (j % 32) of mask_words[task][j / 32] = (|v_j| > tau[task]).
-hipError_t launch_up_gemv(const TaskMap& map, const h16* x, const XPrep* xprep, float* v, const float* task_tau,
-                          uint32_t* mask_words, int d, int f, int bits, int group, int n_tasks, hipStream_t stream);
+// route: when given (INT2 fast shapes, n_experts <= 16 only) the kernel routes in place and fills the
+// task table itself; map.task_table, xprep and task_tau are then ignored.
+hipError_t launch_up_gemv(const TaskMap& map, const h16* x, const XPrep* xprep, const RouteArgs* route, float* v,
+                          const float* task_tau, uint32_t* mask_words, int d, int f, int bits, int group, int n_tasks,
+                          hipStream_t stream);
+inline bool route_in_place_ok(int d, int bits, int group, int n_experts, int top_k, int n_shared) {
+    return int2_fast_shape(d, bits, group) && top_k >= 1 && n_experts <= 16 && top_k + n_shared <= 16;
+}
 
 // S3 as a kernel of its own: per task threshold tau[task]
 hipError_t launch_select(const float* v, int f, int n_tasks, const float* tau, int32_t* idx, int32_t* count,

@@ -1,0 +1,110 @@
+// Softmax + top-k of the router (S1), shared by the stand-alone router kernel and by the GEMV kernel
+// that routes in place.  Run by ONE thread on logits held in LDS; n_experts is small (<= 1024).
+#pragma once
+
+#include "floe_dev.h"
+
+namespace floe {
+
+// prob[0..n) holds the logits on entry and is destroyed.  sel_id / sel_w receive the top_k experts by
+// descending probability (ties keep the lower id) with weight p_e, or p_e / sum of the selected p when
+// renormalize is set.  The n_shared always-on experts follow with ids n, n+1, ... and weight 1.
+__device__ __forceinline__ void route_select(float* prob, int n, int top_k, int n_shared, int renormalize, int* sel_id,
+                                             float* sel_w) {
+    if (top_k > 0) {
+        float mx = prob[0];
+        for (int e = 1; e < n; ++e) mx = fmaxf(mx, prob[e]);
+        float sum = 0.0f;
+        for (int e = 0; e < n; ++e) {
+            const float p = expf(prob[e] - mx);
+            prob[e] = p;
+            sum += p;
+        }
+        float sel = 0.0f;
+        for (int r = 0; r < top_k; ++r) {
+            int best = -1;
+            float bp = -1.0f;
+            for (int e = 0; e < n; ++e) {
+                const float p = prob[e];
+                if (p > bp) { bp = p; best = e; }  // strict: ties keep the lower id
+            }
+            if (best < 0) best = 0;  // only reachable with NaN logits: stay in bounds
+            prob[best] = -2.0f;      // taken
+            const float pw = bp / sum;
+            sel_id[r] = best;
+            sel_w[r] = pw;
+            sel += pw;
+        }
+        if (renormalize)
+            for (int r = 0; r < top_k; ++r) sel_w[r] /= sel;
+    }
+    for (int s = 0; s < n_shared; ++s) {
+        sel_id[top_k + s] = n + s;
+        sel_w[top_k + s] = 1.0f;
+    }
+}
+
+// The same selection for n <= 16 experts, done by the first 16 lanes of one wave with the logits in
+// registers (no serial LDS round trips).  Every lane of the wave must call it; `logit` is the lane's
+// own logit for lane < n (ignored otherwise).  Results land in sel_id / sel_w (LDS or global) as above.
+// Bit-identical to route_select: same expf, same left-to-right sums, same tie rule.
+__device__ __forceinline__ void route_select_wave16(float logit, int lane, int n, int top_k, int n_shared,
+                                                    int renormalize, int* sel_id, float* sel_w) {
+    if (top_k > 0) {
+        const int l16 = lane & 15;
+        const bool live = l16 < n;
+        const float mx = row16_allreduce_max(live ? logit : -INFINITY);
+        const float p = live ? expf(logit - mx) : 0.0f;
+        // sum in ascending expert order, exactly like the serial loop (lane e of row 0 holds p_e)
+        float sum = 0.0f;
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+            const float pe = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, p), e));
+            if (e < n) sum += pe;
+        }
+        float cur = live ? p : -3.0f;
+        float sel = 0.0f;
+        float my_w = 0.0f;
+        int my_id = 0;
+        for (int r = 0; r < top_k; ++r) {
+            // arg-max with ties to the lower id: (value, id) pairs rotate around the row of 16
+            float bv = cur;
+            int bi = l16;
+#define FLOE_ARGMAX_STEP(CTRL)                                               \
+    {                                                                        \
+        const float ov = dpp_movf<CTRL>(bv);                                 \
+        const int oi = dpp_movi<CTRL>(bi);                                   \
+        if (ov > bv || (ov == bv && oi < bi)) { bv = ov; bi = oi; }          \
+    }
+            FLOE_ARGMAX_STEP(0x128) FLOE_ARGMAX_STEP(0x124) FLOE_ARGMAX_STEP(0x122) FLOE_ARGMAX_STEP(0x121)
+#undef FLOE_ARGMAX_STEP
+            const float pw = bv / sum;
+            if (l16 == r) { my_w = pw; my_id = bi; }
+            sel += pw;
+            if (l16 == bi) cur = -2.0f;  // taken
+        }
+        if (lane < top_k) {
+            sel_id[lane] = my_id;
+            sel_w[lane] = renormalize ? my_w / sel : my_w;
+        }
+    }
+    if (lane < n_shared) {
+        sel_id[top_k + lane] = n + lane;
+        sel_w[top_k + lane] = 1.0f;
+    }
+}
+
+// What a kernel that routes in place needs (layer path).
+struct RouteArgs {
+    const h16* router_cm;     // [n_experts][d]
+    const float* tau;         // threshold of (token t, expert e) at tau[t * tau_stride_t + e]
+    int32_t tau_stride_t;
+    int32_t n_experts, top_k, n_shared, renormalize;
+    const DevExpert* table;   // all experts of the layer
+    DevExpert* task_table;    // [n_tasks] out (written by the first workgroup of each task)
+    int32_t* task_expert;     // [n_tasks] out
+    float* task_weight;       // [n_tasks] out
+    float* task_tau;          // [n_tasks] out
+};
+
+}  // namespace floe

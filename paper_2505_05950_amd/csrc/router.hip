@@ -5,6 +5,7 @@
 // slots 0..top_k-1 routed (descending probability), then the n_shared always-on experts with weight 1.
 #include "floe_dev.h"
 #include "launch.h"
+#include "route.h"
 #include "xprep.h"
 
 namespace floe {
@@ -25,9 +26,7 @@ __device__ __forceinline__ void write_xprep(const RouterArgs& a, int t, int lane
         const uint4 q = xq[r];
         raw[4 * r + 0] = q.x; raw[4 * r + 1] = q.y; raw[4 * r + 2] = q.z; raw[4 * r + 3] = q.w;
     }
-    float amax = unit_amax(raw);
-#pragma unroll
-    for (int o = 32; o >= 1; o >>= 1) amax = fmaxf(amax, __shfl_xor(amax, o, kWave));
+    const float amax = wave_allreduce_max_nonneg(unit_amax(raw));
     const int down = xprep_down(amax);
     uint32_t xs[32];
     float Xoff, Xg;
@@ -82,39 +81,7 @@ __global__ __launch_bounds__(256) void router_kernel(RouterArgs a) {
         else if (d == 1024) write_xprep<16>(a, t, lane);
     }
     __syncthreads();
-    if (tid == 0) {
-        if (a.top_k > 0) {
-            float mx = prob[0];
-            for (int e = 1; e < a.n_experts; ++e) mx = fmaxf(mx, prob[e]);
-            float sum = 0.0f;
-            for (int e = 0; e < a.n_experts; ++e) {
-                const float p = expf(prob[e] - mx);
-                prob[e] = p;
-                sum += p;
-            }
-            float sel = 0.0f;
-            for (int r = 0; r < a.top_k; ++r) {
-                int best = -1;
-                float bp = -1.0f;
-                for (int e = 0; e < a.n_experts; ++e) {
-                    const float p = prob[e];
-                    if (p > bp) { bp = p; best = e; }   // strict: ties keep the lower id
-                }
-                if (best < 0) best = 0;  // only reachable with NaN logits: stay in bounds
-                prob[best] = -2.0f;      // taken
-                const float pw = bp / sum;
-                sel_id[r] = best;
-                sel_w[r] = pw;
-                sel += pw;
-            }
-            if (a.renormalize)
-                for (int r = 0; r < a.top_k; ++r) sel_w[r] /= sel;
-        }
-        for (int s = 0; s < a.n_shared; ++s) {
-            sel_id[a.top_k + s] = a.n_experts + s;
-            sel_w[a.top_k + s] = 1.0f;
-        }
-    }
+    if (tid == 0) route_select(prob, a.n_experts, a.top_k, a.n_shared, a.renormalize, sel_id, sel_w);
     __syncthreads();
     // one thread per slot resolves the expert: its pointers, weight and threshold go to the task table
     if (tid < slots) {

@@ -5,6 +5,7 @@
 // so the per-weight work is "extract the code, multiply-accumulate with x".
 #include "floe_dev.h"
 #include "launch.h"
+#include "route.h"
 #include "xprep.h"
 
 namespace floe {
@@ -95,27 +96,107 @@ __global__ __launch_bounds__(256) void up_gemv_generic_kernel(TaskMap map, const
 // The prepared activations come from HBM (written once per token by the router kernel) when PREPPED,
 // otherwise every wave prepares them itself.
 // ---------------------------------------------------------------------------------------------------
-template <int UPC, bool PREPPED>
+enum { kModeRaw = 0, kModePrepped = 1, kModeRouted = 2 };
+
+template <int UPC, int MODE, int kPasses>
 __global__ __launch_bounds__(256) void up_gemv_int2_kernel(TaskMap map, const h16* __restrict__ x, XPrep xp,
-                                                           float* __restrict__ v,
+                                                           RouteArgs ro, float* __restrict__ v,
                                                            const float* __restrict__ task_tau,
                                                            uint32_t* __restrict__ mask_words, int f, int gshift) {
     constexpr int CPW = kWave / UPC;  // channels per wave pass
-    constexpr int kPasses = 8;
     constexpr int d = UPC * 64;
-    __shared__ uint32_t mw[CPW];
+    constexpr int kWords = (kPasses * CPW * 4 + 31) / 32;  // mask words per workgroup
+    __shared__ uint32_t mw[kWords];
+    __shared__ float prob[16];
+    __shared__ int sel_id[16];
+    __shared__ float sel_w[16];
+    __shared__ DevExpert tab[32];
+    __shared__ float taus[32];
     const int tid = threadIdx.x;
     const int wave = tid >> 6, lane = tid & 63;
     const int sub = lane / UPC, u = lane % UPC;
     const int task = blockIdx.y;
     const int t = task / map.slots;
-    const DevExpert e = task_expert_of(map, task);
     const int G = d >> gshift;
-    const bool want_mask = task_tau != nullptr && mask_words != nullptr;
-    const float tau = want_mask ? task_tau[task] : 0.0f;
-    if (tid < CPW) mw[tid] = 0u;
+    if (tid < kWords) mw[tid] = 0u;
+    FLOE_TL(0);
 
-    // ---- issue the weight loads first: kPasses passes of CPW channels per wave
+    DevExpert e;
+    float tau = 0.0f;
+    bool want_mask = mask_words != nullptr;
+    uint32_t raw[32];  // this lane's 64 activations (kModeRaw / kModeRouted)
+    if (MODE != kModePrepped) {
+        const uint4* xq = reinterpret_cast<const uint4*>(x + (size_t)t * d + u * 64);
+#pragma unroll
+        for (int r = 0; r < 8; ++r) {
+            const uint4 q = xq[r];
+            raw[4 * r + 0] = q.x; raw[4 * r + 1] = q.y; raw[4 * r + 2] = q.z; raw[4 * r + 3] = q.w;
+        }
+    }
+    if (MODE == kModeRouted) {
+        // ---- S1 in place: every workgroup of the layer computes the same few dot products (n_experts <= 16,
+        // the router matrix sits in L2), so no kernel of its own and no global hand-off is needed
+        // a whole wave per expert, two experts in flight per wave, fully coalesced 16-byte pieces
+        // every expert's table entry and threshold is fetched now, so that nothing has to be loaded from
+        // global memory between knowing the routed expert and requesting its codes
+        if (tid < ro.n_experts + ro.n_shared) {
+            tab[tid] = ro.table[tid];
+            taus[tid] = ro.tau[(size_t)t * ro.tau_stride_t + tid];
+        }
+        constexpr int NVR = d / 512;
+        uint4 xl[NVR];
+        {
+            const uint4* xp4 = reinterpret_cast<const uint4*>(x + (size_t)t * d);
+#pragma unroll
+            for (int r = 0; r < NVR; ++r) xl[r] = xp4[r * kWave + lane];
+        }
+        for (int e0 = wave * 2; e0 < ro.n_experts; e0 += 8) {
+            uint4 w[2][NVR];
+#pragma unroll
+            for (int q = 0; q < 2; ++q) {
+                const int ex = e0 + q < ro.n_experts ? e0 + q : e0;
+                const uint4* wq = reinterpret_cast<const uint4*>(ro.router_cm + (size_t)ex * d);
+#pragma unroll
+                for (int r = 0; r < NVR; ++r) w[q][r] = wq[r * kWave + lane];
+            }
+#pragma unroll
+            for (int q = 0; q < 2; ++q) {
+                float acc = 0.0f;
+#pragma unroll
+                for (int r = 0; r < NVR; ++r) {
+                    acc = dot2(xl[r].x, w[q][r].x, acc);
+                    acc = dot2(xl[r].y, w[q][r].y, acc);
+                    acc = dot2(xl[r].z, w[q][r].z, acc);
+                    acc = dot2(xl[r].w, w[q][r].w, acc);
+                }
+                acc = group_reduce_sum_to_last<64>(acc);
+                if (lane == kWave - 1 && e0 + q < ro.n_experts) prob[e0 + q] = acc;
+            }
+        }
+        FLOE_TL(1);
+        __syncthreads();
+        if (wave == 0)
+            route_select_wave16(prob[lane & 15], lane, ro.n_experts, ro.top_k, ro.n_shared, ro.renormalize, sel_id, sel_w);
+        __syncthreads();
+        FLOE_TL(2);
+        const int slot = task - t * map.slots;
+        const int ex = sel_id[slot];
+        e = tab[ex];
+        tau = taus[ex];
+        if (blockIdx.x == 0 && tid == 0) {
+            ro.task_table[task] = e;
+            ro.task_expert[task] = ex;
+            ro.task_weight[task] = sel_w[slot];
+            ro.task_tau[task] = tau;
+        }
+    } else {
+        e = task_expert_of(map, task);
+        want_mask = want_mask && task_tau != nullptr;
+        if (want_mask) tau = task_tau[task];
+    }
+
+    FLOE_TL(3);
+    // ---- issue the weight loads: kPasses passes of CPW channels per wave
     const int jw = (blockIdx.x * 4 + wave) * (kPasses * CPW);
     const uint4* codes4 = reinterpret_cast<const uint4*>(e.codes);
     uint4 cw[kPasses];
@@ -133,7 +214,7 @@ __global__ __launch_bounds__(256) void up_gemv_int2_kernel(TaskMap map, const h1
     // ---- activations of this lane's unit: 32 scaled fp16 pairs
     uint32_t xs[32];
     float Xg, Xoff, inv_p;
-    if (PREPPED) {
+    if (MODE == kModePrepped) {
 #pragma unroll
         for (int r = 0; r < 8; ++r) {
             const uint4 q = xp.xs[((size_t)t * 8 + r) * UPC + u];
@@ -143,16 +224,8 @@ __global__ __launch_bounds__(256) void up_gemv_int2_kernel(TaskMap map, const h1
         Xg = xp.xg[(size_t)t * UPC + u];
         inv_p = xp.inv_p[t];
     } else {
-        uint32_t raw[32];
-        const uint4* xq = reinterpret_cast<const uint4*>(x + (size_t)t * d + u * 64);
-#pragma unroll
-        for (int r = 0; r < 8; ++r) {
-            const uint4 q = xq[r];
-            raw[4 * r + 0] = q.x; raw[4 * r + 1] = q.y; raw[4 * r + 2] = q.z; raw[4 * r + 3] = q.w;
-        }
-        float amax = unit_amax(raw);
-#pragma unroll
-        for (int o = UPC / 2; o >= 1; o >>= 1) amax = fmaxf(amax, __shfl_xor(amax, o, kWave));
+        // every group of UPC lanes holds the whole token, so the wave-wide maximum is the token's
+        const float amax = wave_allreduce_max_nonneg(unit_amax(raw));
         const int down = xprep_down(amax);
         inv_p = ldexpf(1.0f, down);
         unit_prepare(raw, down, xs, Xoff, Xg);
@@ -160,6 +233,7 @@ __global__ __launch_bounds__(256) void up_gemv_int2_kernel(TaskMap map, const h1
     uint32_t magic = 0x3C003C00u;
     asm volatile("" : "+v"(magic));  // keep it in a VGPR: v_and_or_b32 takes one scalar operand only
     __syncthreads();                 // mw zeroed
+    FLOE_TL(4);
 
 #pragma unroll
     for (int p = 0; p < kPasses; ++p) {
@@ -181,20 +255,28 @@ __global__ __launch_bounds__(256) void up_gemv_int2_kernel(TaskMap map, const h1
         const float s = (float)sc[p], z = (float)zr[p];
         float part = s * fmaf(-z, Xg, dot - Xoff);
         part = group_reduce_sum_to_last<UPC>(part) * inv_p;
+        if (p == 0) FLOE_TL(5);
         if (u == UPC - 1 && j < f) {
             v[(size_t)task * f + j] = part;
             if (want_mask && fabsf(part) > tau) {
-                const int local = j - blockIdx.x * (32 * CPW);
+                const int local = j - blockIdx.x * (4 * kPasses * CPW);
                 atomicOr(&mw[local >> 5], 1u << (local & 31));
             }
         }
     }
+    FLOE_TL(6);
     if (want_mask) {
         __syncthreads();
-        const int word = blockIdx.x * CPW + tid;
-        if (tid < CPW && word < mask_words_per_task(f)) mask_words[(size_t)task * mask_words_per_task(f) + word] = mw[tid];
+        const int word = blockIdx.x * kWords + tid;
+        if (tid < kWords && word < mask_words_per_task(f)) mask_words[(size_t)task * mask_words_per_task(f) + word] = mw[tid];
     }
 }
+
+#ifdef FLOE_TIMELINE
+extern "C" int floe_debug_set_timeline_up_gemv(unsigned long long* p) {
+    return (int)hipMemcpyToSymbol(HIP_SYMBOL(g_timeline), &p, sizeof(p));
+}
+#endif
 
 static int ilog2_exact(int g) {
     int s = 0;
@@ -202,32 +284,48 @@ static int ilog2_exact(int g) {
     return s;
 }
 
+constexpr int kPassesPlain = 8, kPassesRouted = 16;
+
 template <int UPC>
-static void launch_int2(bool prepped, dim3 grid, hipStream_t stream, const TaskMap& map, const h16* x, const XPrep& xp,
-                        float* v, const float* task_tau, uint32_t* mask_words, int f, int gshift) {
-    if (prepped)
-        up_gemv_int2_kernel<UPC, true><<<grid, dim3(256), 0, stream>>>(map, x, xp, v, task_tau, mask_words, f, gshift);
+static void launch_int2(int mode, int f, int n_tasks, hipStream_t stream, const TaskMap& map, const h16* x,
+                        const XPrep& xp, const RouteArgs& ro, float* v, const float* task_tau, uint32_t* mask_words,
+                        int gshift) {
+    const dim3 block(256);
+    const int passes = mode == kModeRouted ? kPassesRouted : kPassesPlain;
+    const int ch_per_wg = 4 * passes * (64 / UPC);
+    const dim3 grid((f + ch_per_wg - 1) / ch_per_wg, n_tasks);
+    if (mode == kModeRouted)
+        up_gemv_int2_kernel<UPC, kModeRouted, kPassesRouted><<<grid, block, 0, stream>>>(map, x, xp, ro, v, task_tau, mask_words, f, gshift);
+    else if (mode == kModePrepped)
+        up_gemv_int2_kernel<UPC, kModePrepped, kPassesPlain><<<grid, block, 0, stream>>>(map, x, xp, ro, v, task_tau, mask_words, f, gshift);
     else
-        up_gemv_int2_kernel<UPC, false><<<grid, dim3(256), 0, stream>>>(map, x, xp, v, task_tau, mask_words, f, gshift);
+        up_gemv_int2_kernel<UPC, kModeRaw, kPassesPlain><<<grid, block, 0, stream>>>(map, x, xp, ro, v, task_tau, mask_words, f, gshift);
 }
 
-hipError_t launch_up_gemv(const TaskMap& map, const h16* x, const XPrep* xprep, float* v, const float* task_tau,
-                          uint32_t* mask_words, int d, int f, int bits, int group, int n_tasks, hipStream_t stream) {
+hipError_t launch_up_gemv(const TaskMap& map, const h16* x, const XPrep* xprep, const RouteArgs* route, float* v,
+                          const float* task_tau, uint32_t* mask_words, int d, int f, int bits, int group, int n_tasks,
+                          hipStream_t stream) {
     if (f == 0 || n_tasks == 0) return hipSuccess;
     const int gshift = ilog2_exact(group);
     dim3 block(256);
     if (int2_fast_shape(d, bits, group)) {
         const int upc = d / 64;
-        const int ch_per_wg = 4 * 8 * (64 / upc);
-        dim3 grid((f + ch_per_wg - 1) / ch_per_wg, n_tasks);
-        const bool prepped = xprep != nullptr && xprep->xs != nullptr;
+        int mode = kModeRaw;
         XPrep xp{};
-        if (prepped) xp = *xprep;
-        if (upc == 64) launch_int2<64>(prepped, grid, stream, map, x, xp, v, task_tau, mask_words, f, gshift);
-        else if (upc == 32) launch_int2<32>(prepped, grid, stream, map, x, xp, v, task_tau, mask_words, f, gshift);
-        else launch_int2<16>(prepped, grid, stream, map, x, xp, v, task_tau, mask_words, f, gshift);
+        RouteArgs ro{};
+        if (route != nullptr) {
+            mode = kModeRouted;
+            ro = *route;
+        } else if (xprep != nullptr && xprep->xs != nullptr) {
+            mode = kModePrepped;
+            xp = *xprep;
+        }
+        if (upc == 64) launch_int2<64>(mode, f, n_tasks, stream, map, x, xp, ro, v, task_tau, mask_words, gshift);
+        else if (upc == 32) launch_int2<32>(mode, f, n_tasks, stream, map, x, xp, ro, v, task_tau, mask_words, gshift);
+        else launch_int2<16>(mode, f, n_tasks, stream, map, x, xp, ro, v, task_tau, mask_words, gshift);
         return hipGetLastError();
     }
+    if (route != nullptr) return hipErrorInvalidValue;  // in-place routing exists only in the INT2 kernel
     dim3 grid((f + 31) / 32, n_tasks);
     switch (bits) {
         case 2: up_gemv_generic_kernel<2><<<grid, block, 0, stream>>>(map, x, v, task_tau, mask_words, d, f, gshift); break;
