@@ -158,6 +158,9 @@ typedef struct {
     int32_t tau_stride_t;       /* n_experts + n_shared for per-token thresholds, 0 to broadcast the
                                    per-expert constant t_ij that Alg. 1 takes as input */
     const void* dev_table;      /* dev, written by floe_layer_build_table: the experts' pointers in HBM */
+    int32_t gd_on_host;         /* 0: every expert's gd is in HBM.  1: every expert's gd is PINNED HOST memory
+                                   (the offloaded setting of Sec. 3.1 / 3.4.2); only
+                                   floe_moe_layer_decode_offloaded accepts such a layer */
 } floe_layer;
 
 /* Per (token, slot) record written by floe_moe_layer_decode when `stats` is not NULL;
@@ -183,6 +186,30 @@ size_t floe_layer_workspace_bytes(const floe_layer* L, int T);
  */
 int floe_moe_layer_decode(const floe_layer* L, const floe_half* x, int T, floe_half* y, floe_slot_stat* stats,
                           void* workspace, size_t workspace_bytes, void* stream);
+
+/* ------------------------------------------------------------------------------------------------
+ * One MoE layer in the offloaded setting (Sec. 3.1, Fig. 1(c); Sec. 3.4.2): the quantized up projections
+ * and the router are resident in HBM, the gate/down matrices stay in pinned host memory and only the
+ * selected channels of the routed experts cross the bus.  Sequence:
+ *   on `stream`:      router, up GEMV, selection (index lists)           -> ev_lists_ready
+ *   on side_stream:   wait ev_lists_ready; copy the selected chunks of every (token, slot) into its slab of
+ *                     `staging` (S7)                                     -> ev_staged
+ *   on `stream`:      wait ev_staged; gathered gate/down on the staged rows, combine.
+ * staging: dev [T * (top_k + n_shared)][capacity_rows][2][d]; a list longer than capacity_rows is truncated
+ * and overflow[task] (dev, optional) is set to 1.  The two events are hipEvent_t owned by the caller.
+ * L->gd_on_host must be 1 and L->dev_table built by floe_layer_build_table.
+ */
+typedef struct {
+    floe_half* staging;
+    int32_t capacity_rows;
+    int32_t* overflow;
+    void* side_stream;
+    void* ev_lists_ready;
+    void* ev_staged;
+} floe_offload;
+
+int floe_moe_layer_decode_offloaded(const floe_layer* L, const floe_offload* o, const floe_half* x, int T, floe_half* y,
+                                    floe_slot_stat* stats, void* workspace, size_t workspace_bytes, void* stream);
 
 /* ------------------------------------------------------------------------------------------------
  * S7 -- Sec. 3.4.2 (compact asynchronous transfer), done the MI355X way: a copy kernel on a side

@@ -36,7 +36,12 @@ class _Expert(C.Structure):
 class _Layer(C.Structure):
     _fields_ = [("n_experts", C.c_int32), ("top_k", C.c_int32), ("n_shared", C.c_int32), ("renormalize", C.c_int32),
                 ("s", _Shape), ("router_cm", C.c_void_p), ("experts", C.POINTER(_Expert)), ("tau", C.c_void_p),
-                ("tau_stride_t", C.c_int32), ("dev_table", C.c_void_p)]
+                ("tau_stride_t", C.c_int32), ("dev_table", C.c_void_p), ("gd_on_host", C.c_int32)]
+
+
+class _Offload(C.Structure):
+    _fields_ = [("staging", C.c_void_p), ("capacity_rows", C.c_int32), ("overflow", C.c_void_p),
+                ("side_stream", C.c_void_p), ("ev_lists_ready", C.c_void_p), ("ev_staged", C.c_void_p)]
 
 
 def lib_path() -> str:
@@ -72,6 +77,7 @@ def load():
     lib.floe_layer_workspace_bytes.restype = sz
     lib.floe_layer_workspace_bytes.argtypes = [C.POINTER(_Layer), i32]
     lib.floe_moe_layer_decode.argtypes = [C.POINTER(_Layer), vp, i32, vp, vp, vp, sz, vp]
+    lib.floe_moe_layer_decode_offloaded.argtypes = [C.POINTER(_Layer), C.POINTER(_Offload), vp, i32, vp, vp, vp, sz, vp]
     lib.floe_stage_channels.argtypes = [vp, i32, i32, vp, vp, i32, vp, vp, vp, vp]
     _lib = lib
     return lib
@@ -212,7 +218,8 @@ def floe_expert_ffn_sparse(e: Expert, x, tau, out_scale, y_acc, idx=None, count=
 class Layer:
     """One MoE layer: routed experts first, shared experts last; builds the HBM pointer table once."""
 
-    def __init__(self, experts, n_shared, top_k, renormalize, router_cm, tau, tau_per_token: bool, stream=None):
+    def __init__(self, experts, n_shared, top_k, renormalize, router_cm, tau, tau_per_token: bool, stream=None,
+                 gd_on_host: bool = False):
         self.experts = list(experts)
         e0 = self.experts[0]
         self.d, self.f, self.bits, self.group = e0.d, e0.f, e0.bits, e0.group
@@ -224,7 +231,8 @@ class Layer:
         self._c = _Layer(self.n_experts, self.top_k, self.n_shared, int(self.renormalize),
                          _shape(self.d, self.f, self.bits, self.group),
                          None if router_cm is None else router_cm.data_ptr(), self._arr, tau.data_ptr(),
-                         self.tau_stride, None)
+                         self.tau_stride, None, int(gd_on_host))
+        self.gd_on_host = bool(gd_on_host)
         nbytes = floe_layer_table_bytes(self)
         self.table = torch.empty((nbytes + 256,), dtype=torch.uint8, device=tau.device)
         tp, tn = _aligned_ptr(self.table)
@@ -267,6 +275,26 @@ def floe_moe_layer_decode(L: Layer, x: torch.Tensor, y: torch.Tensor = None, sta
     wp, wn = _aligned_ptr(workspace)
     _check(load().floe_moe_layer_decode(C.byref(L._c), _ptr(x), T, _ptr(y), _ptr(stats), wp, wn, _stream(stream)),
            "floe_moe_layer_decode")
+    return y
+
+
+def floe_moe_layer_decode_offloaded(L: Layer, x, staging, capacity_rows, side_stream, ev_lists_ready, ev_staged,
+                                    y=None, stats=None, overflow=None, workspace=None, stream=None):
+    """Offloaded layer: experts' gd are pinned host tensors; staging dev [T*slots][capacity_rows][2][d]."""
+    T = x.shape[0]
+    if y is None:
+        y = torch.empty((T, L.d), dtype=torch.float16, device=x.device)
+    if workspace is None:
+        workspace = L.workspace(T)
+    wp, wn = _aligned_ptr(workspace)
+    cur = stream if stream is not None else torch.cuda.current_stream()
+    # torch creates the hipEvent_t lazily on the first record(); the library records both again
+    ev_lists_ready.record(cur)
+    ev_staged.record(side_stream)
+    off = _Offload(staging.data_ptr(), int(capacity_rows), None if overflow is None else overflow.data_ptr(),
+                   side_stream.cuda_stream, ev_lists_ready.cuda_event, ev_staged.cuda_event)
+    _check(load().floe_moe_layer_decode_offloaded(C.byref(L._c), C.byref(off), _ptr(x), T, _ptr(y), _ptr(stats), wp, wn,
+                                                  _stream(stream)), "floe_moe_layer_decode_offloaded")
     return y
 
 

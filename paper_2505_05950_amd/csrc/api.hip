@@ -168,7 +168,7 @@ const char* floe_status_string(int status) {
 }
 
 int floe_last_hip_error(void) { return g_last_hip_error; }
-int floe_abi_version(void) { return 1; }
+int floe_abi_version(void) { return 2; }
 
 int floe_profile_kernel(int kernel_id, void* start_event, void* stop_event) {
     if (kernel_id < 0 || kernel_id > FLOE_KERNEL_STAGE) return FLOE_EINVAL;
@@ -238,7 +238,8 @@ int floe_gate_down_sparse(const floe_expert* e, const floe_half* x, int T, const
     if (workspace_bytes < w.total) return FLOE_EWORKSPACE;
     float* partial = reinterpret_cast<float*>(static_cast<char*>(workspace) + w.partial_off);
     hipStream_t st = (hipStream_t)stream;
-    FLOE_LAUNCH(FLOE_KERNEL_GATE_DOWN, st, launch_gate_down(single_map(e), e->gd_is_staged, e->gd_rows, reinterpret_cast<const h16*>(x), v, nullptr,
+    FLOE_LAUNCH(FLOE_KERNEL_GATE_DOWN, st, launch_gate_down(single_map(e), e->gd_is_staged ? reinterpret_cast<const h16*>(e->gd) : nullptr, e->gd_rows,
+                              reinterpret_cast<const h16*>(x), v, nullptr,
                               const_cast<int32_t*>(idx), const_cast<int32_t*>(count), out_scale, partial, e->s.d, e->s.f, T, w.nblk, st));
     FLOE_LAUNCH(FLOE_KERNEL_COMBINE, st, launch_combine(partial, e->s.d, T, 1, w.nblk, y_acc, nullptr, st));
     return FLOE_OK;
@@ -271,14 +272,14 @@ int floe_expert_ffn_sparse(const floe_expert* e, const floe_half* x, int T, cons
         FLOE_LAUNCH(FLOE_KERNEL_UP_GEMV, st,
                     launch_up_gemv(map, xh, nullptr, nullptr, v, tau, mask, e->s.d, e->s.f, e->s.bits, e->s.group, T, st));
         FLOE_LAUNCH(FLOE_KERNEL_GATE_DOWN, st,
-                    launch_gate_down(map, 0, e->s.f, xh, v, mask, idx, count, out_scale, partial, e->s.d, e->s.f, T,
+                    launch_gate_down(map, nullptr, e->s.f, xh, v, mask, idx, count, out_scale, partial, e->s.d, e->s.f, T,
                                      w.nblk, st));
     } else {
         FLOE_LAUNCH(FLOE_KERNEL_UP_GEMV, st,
                     launch_up_gemv(map, xh, nullptr, nullptr, v, nullptr, nullptr, e->s.d, e->s.f, e->s.bits, e->s.group, T, st));
         FLOE_LAUNCH(FLOE_KERNEL_SELECT, st, launch_select(v, e->s.f, T, tau, idx, count, st));
         FLOE_LAUNCH(FLOE_KERNEL_GATE_DOWN, st,
-                    launch_gate_down(map, 0, e->s.f, xh, v, nullptr, idx, count, out_scale, partial, e->s.d, e->s.f, T,
+                    launch_gate_down(map, nullptr, e->s.f, xh, v, nullptr, idx, count, out_scale, partial, e->s.d, e->s.f, T,
                                      w.nblk, st));
     }
     FLOE_LAUNCH(FLOE_KERNEL_COMBINE, st, launch_combine(partial, e->s.d, T, 1, w.nblk, y_acc, nullptr, st));
@@ -307,6 +308,11 @@ int floe_layer_build_table(const floe_layer* L, void* dev_table, size_t bytes, v
         host[i].scale = reinterpret_cast<const h16*>(e.up_scale);
         host[i].zero = reinterpret_cast<const h16*>(e.up_zero);
         host[i].gd = reinterpret_cast<const h16*>(e.gd);
+        if (L->gd_on_host) {  // the kernels read pinned host memory through its device-side address
+            void* dev_view = nullptr;
+            FLOE_HIP(hipHostGetDevicePointer(&dev_view, const_cast<floe_half*>(e.gd), 0));
+            host[i].gd = static_cast<const h16*>(dev_view);
+        }
     }
     hipStream_t st = (hipStream_t)stream;
     FLOE_HIP(hipMemcpyAsync(dev_table, host.data(), (size_t)n * sizeof(DevExpert), hipMemcpyHostToDevice, st));
@@ -326,6 +332,7 @@ int floe_moe_layer_decode(const floe_layer* L, const floe_half* x, int T, floe_h
     if ((rc = check_T(T))) return rc;
     if (T == 0) return FLOE_OK;
     if (!L->dev_table || !x || !y || !workspace) return FLOE_EINVAL;
+    if (L->gd_on_host) return FLOE_EINVAL;  // host-resident gate/down: use floe_moe_layer_decode_offloaded
     if (!aligned(x, 16) || !aligned(y, 8) || !aligned(workspace, kAlign)) return FLOE_EINVAL;
     const LayerWs w = layer_ws(L, T);
     if (workspace_bytes < w.total) return FLOE_EWORKSPACE;
@@ -362,7 +369,7 @@ int floe_moe_layer_decode(const floe_layer* L, const floe_half* x, int T, floe_h
                     launch_up_gemv(map, xh, nullptr, &ro, v, nullptr, mask, L->s.d, L->s.f, L->s.bits, L->s.group,
                                    w.n_tasks, st));
         FLOE_LAUNCH(FLOE_KERNEL_GATE_DOWN, st,
-                    launch_gate_down(map, 0, L->s.f, xh, v, mask, nullptr, count, task_weight, partial, L->s.d, L->s.f,
+                    launch_gate_down(map, nullptr, L->s.f, xh, v, mask, nullptr, count, task_weight, partial, L->s.d, L->s.f,
                                      w.n_tasks, w.nblk, st));
     } else {
         RouterArgs ra;
@@ -389,7 +396,7 @@ int floe_moe_layer_decode(const floe_layer* L, const floe_half* x, int T, floe_h
                         launch_up_gemv(map, xh, xpp, nullptr, v, task_tau, mask, L->s.d, L->s.f, L->s.bits, L->s.group,
                                        w.n_tasks, st));
             FLOE_LAUNCH(FLOE_KERNEL_GATE_DOWN, st,
-                        launch_gate_down(map, 0, L->s.f, xh, v, mask, nullptr, count, task_weight, partial, L->s.d,
+                        launch_gate_down(map, nullptr, L->s.f, xh, v, mask, nullptr, count, task_weight, partial, L->s.d,
                                          L->s.f, w.n_tasks, w.nblk, st));
         } else {
             FLOE_LAUNCH(FLOE_KERNEL_UP_GEMV, st,
@@ -397,11 +404,84 @@ int floe_moe_layer_decode(const floe_layer* L, const floe_half* x, int T, floe_h
                                        L->s.group, w.n_tasks, st));
             FLOE_LAUNCH(FLOE_KERNEL_SELECT, st, launch_select(v, L->s.f, w.n_tasks, task_tau, idx, count, st));
             FLOE_LAUNCH(FLOE_KERNEL_GATE_DOWN, st,
-                        launch_gate_down(map, 0, L->s.f, xh, v, nullptr, idx, count, task_weight, partial, L->s.d,
+                        launch_gate_down(map, nullptr, L->s.f, xh, v, nullptr, idx, count, task_weight, partial, L->s.d,
                                          L->s.f, w.n_tasks, w.nblk, st));
         }
     }
     FLOE_LAUNCH(FLOE_KERNEL_COMBINE, st, launch_combine(partial, L->s.d, T, slots, w.nblk, nullptr, reinterpret_cast<h16*>(y), st));
+    if (stats) FLOE_HIP(launch_stats(task_expert, count, task_weight, reinterpret_cast<SlotStat*>(stats), w.n_tasks, st));
+    return FLOE_OK;
+}
+
+int floe_moe_layer_decode_offloaded(const floe_layer* L, const floe_offload* o, const floe_half* x, int T, floe_half* y,
+                                    floe_slot_stat* stats, void* workspace, size_t workspace_bytes, void* stream) {
+    int rc = check_layer(L);
+    if (rc) return rc;
+    if ((rc = check_T(T))) return rc;
+    if (T == 0) return FLOE_OK;
+    if (!o || !o->staging || !o->ev_lists_ready || !o->ev_staged || o->capacity_rows <= 0) return FLOE_EINVAL;
+    if (!L->dev_table || !L->gd_on_host || !x || !y || !workspace) return FLOE_EINVAL;
+    if (!aligned(x, 16) || !aligned(y, 8) || !aligned(workspace, kAlign) || !aligned(o->staging, 16)) return FLOE_EINVAL;
+    const LayerWs w = layer_ws(L, T);
+    if (workspace_bytes < w.total) return FLOE_EWORKSPACE;
+    char* base = static_cast<char*>(workspace);
+    DevExpert* task_table = reinterpret_cast<DevExpert*>(base + w.table_off);
+    int32_t* task_expert = reinterpret_cast<int32_t*>(base + w.expert_off);
+    float* task_weight = reinterpret_cast<float*>(base + w.weight_off);
+    float* task_tau = reinterpret_cast<float*>(base + w.tau_off);
+    int32_t* count = reinterpret_cast<int32_t*>(base + w.count_off);
+    float* v = reinterpret_cast<float*>(base + w.v_off);
+    int32_t* idx = reinterpret_cast<int32_t*>(base + w.idx_off);
+    float* partial = reinterpret_cast<float*>(base + w.partial_off);
+    hipStream_t st = (hipStream_t)stream, side = (hipStream_t)o->side_stream;
+    const h16* xh = reinterpret_cast<const h16*>(x);
+    const int slots = L->top_k + L->n_shared;
+
+    TaskMap map{};
+    map.task_table = task_table;
+    map.slots = slots;
+    if (route_in_place_ok(L->s.d, L->s.bits, L->s.group, L->n_experts, L->top_k, L->n_shared)) {
+        RouteArgs ro;
+        ro.router_cm = reinterpret_cast<const h16*>(L->router_cm);
+        ro.tau = L->tau;
+        ro.tau_stride_t = L->tau_stride_t;
+        ro.n_experts = L->n_experts; ro.top_k = L->top_k; ro.n_shared = L->n_shared; ro.renormalize = L->renormalize;
+        ro.table = static_cast<const DevExpert*>(L->dev_table);
+        ro.task_table = task_table;
+        ro.task_expert = task_expert; ro.task_weight = task_weight; ro.task_tau = task_tau;
+        FLOE_LAUNCH(FLOE_KERNEL_UP_GEMV, st,
+                    launch_up_gemv(map, xh, nullptr, &ro, v, nullptr, nullptr, L->s.d, L->s.f, L->s.bits, L->s.group,
+                                   w.n_tasks, st));
+    } else {
+        RouterArgs ra;
+        ra.router_cm = reinterpret_cast<const h16*>(L->router_cm);
+        ra.x = xh;
+        ra.tau = L->tau;
+        ra.tau_stride_t = L->tau_stride_t;
+        ra.n_experts = L->n_experts; ra.top_k = L->top_k; ra.n_shared = L->n_shared; ra.renormalize = L->renormalize;
+        ra.d = L->s.d;
+        ra.table = static_cast<const DevExpert*>(L->dev_table);
+        ra.task_table = task_table;
+        ra.task_expert = task_expert; ra.task_weight = task_weight; ra.task_tau = task_tau;
+        ra.xprep = XPrep{};
+        FLOE_LAUNCH(FLOE_KERNEL_ROUTER, st, launch_router(ra, T, st));
+        FLOE_LAUNCH(FLOE_KERNEL_UP_GEMV, st,
+                    launch_up_gemv(map, xh, nullptr, nullptr, v, nullptr, nullptr, L->s.d, L->s.f, L->s.bits, L->s.group,
+                                   w.n_tasks, st));
+    }
+    FLOE_LAUNCH(FLOE_KERNEL_SELECT, st, launch_select(v, L->s.f, w.n_tasks, task_tau, idx, count, st));
+    FLOE_HIP(hipEventRecord((hipEvent_t)o->ev_lists_ready, st));
+    FLOE_HIP(hipStreamWaitEvent(side, (hipEvent_t)o->ev_lists_ready, 0));
+    FLOE_LAUNCH(FLOE_KERNEL_STAGE, side,
+                launch_stage_tasks(task_table, L->s.d, L->s.f, idx, count, o->capacity_rows,
+                                   reinterpret_cast<h16*>(o->staging), o->overflow, w.n_tasks, side));
+    FLOE_HIP(hipEventRecord((hipEvent_t)o->ev_staged, side));
+    FLOE_HIP(hipStreamWaitEvent(st, (hipEvent_t)o->ev_staged, 0));
+    FLOE_LAUNCH(FLOE_KERNEL_GATE_DOWN, st,
+                launch_gate_down(map, reinterpret_cast<const h16*>(o->staging), o->capacity_rows, xh, v, nullptr, idx,
+                                 count, task_weight, partial, L->s.d, L->s.f, w.n_tasks, w.nblk, st));
+    FLOE_LAUNCH(FLOE_KERNEL_COMBINE, st,
+                launch_combine(partial, L->s.d, T, slots, w.nblk, nullptr, reinterpret_cast<h16*>(y), st));
     if (stats) FLOE_HIP(launch_stats(task_expert, count, task_weight, reinterpret_cast<SlotStat*>(stats), w.n_tasks, st));
     return FLOE_OK;
 }

@@ -31,7 +31,7 @@ struct GdTile {
 };
 
 template <int NV, bool FROM_MASK>  // d = 512 * NV
-__global__ __launch_bounds__(256) void gate_down_kernel(TaskMap map, int staged, int gd_rows,
+__global__ __launch_bounds__(256) void gate_down_kernel(TaskMap map, const h16* __restrict__ staged_base, int gd_rows,
                                                         const h16* __restrict__ x, const float* __restrict__ v,
                                                         const uint32_t* __restrict__ mask_words,
                                                         int32_t* __restrict__ idx, int32_t* __restrict__ count,
@@ -52,6 +52,9 @@ __global__ __launch_bounds__(256) void gate_down_kernel(TaskMap map, int staged,
     const DevExpert e = task_expert_of(map, task);
     const float out_scale = task_scale ? task_scale[task] : 1.0f;
     const float* vt = v + (size_t)task * f;
+    // staged: the task's selected chunks sit in rows 0..K-1 of its own slab of the staging buffer
+    const bool staged = staged_base != nullptr;
+    const h16* gdp = staged ? staged_base + (size_t)task * gd_rows * 2 * d : e.gd;
 
     FLOE_TL(0);
     uint4 xr[NV];
@@ -151,7 +154,7 @@ __global__ __launch_bounds__(256) void gate_down_kernel(TaskMap map, int staged,
                 const int j = c < n ? jl[c] : -1;
                 vj[i] = j >= 0 ? vt[j] : 0.0f;  // same address in every lane; needed only after the dot product
                 const size_t row = staged ? (size_t)(kc + c) : (size_t)(j < 0 ? 0 : j);
-                const uint4* gp = reinterpret_cast<const uint4*>(e.gd + row * 2 * d);
+                const uint4* gp = reinterpret_cast<const uint4*>(gdp + row * 2 * d);
 #pragma unroll
                 for (int r = 0; r < NV; ++r) gv[i][r] = j >= 0 ? gp[r * kWave + lane] : make_uint4(0u, 0u, 0u, 0u);
             }
@@ -160,7 +163,7 @@ __global__ __launch_bounds__(256) void gate_down_kernel(TaskMap map, int staged,
                 const int c = b0 + cc;
                 const int j = c < n ? jl[c] : -1;
                 const size_t row = staged ? (size_t)(kc + c) : (size_t)(j < 0 ? 0 : j);
-                const uint4* dp = reinterpret_cast<const uint4*>(e.gd + row * 2 * d + d);
+                const uint4* dp = reinterpret_cast<const uint4*>(gdp + row * 2 * d + d);
 #pragma unroll
                 for (int r = 0; r < RG; ++r) {
                     const int piece = tid + 256 * r;
@@ -237,7 +240,7 @@ int gd_blocks(int n_tasks, int f) {
 }
 
 template <int NV>
-static hipError_t launch_nv(const TaskMap& map, int staged, int gd_rows, const h16* x, const float* v,
+static hipError_t launch_nv(const TaskMap& map, const h16* staged, int gd_rows, const h16* x, const float* v,
                             const uint32_t* mask_words, int32_t* idx, int32_t* count, const float* task_scale,
                             float* partial, int f, int n_tasks, int nblk, hipStream_t stream) {
     dim3 grid(nblk, n_tasks), block(256);
@@ -250,7 +253,7 @@ static hipError_t launch_nv(const TaskMap& map, int staged, int gd_rows, const h
     return hipGetLastError();
 }
 
-hipError_t launch_gate_down(const TaskMap& map, int staged, int gd_rows, const h16* x, const float* v,
+hipError_t launch_gate_down(const TaskMap& map, const h16* staged, int gd_rows, const h16* x, const float* v,
                             const uint32_t* mask_words, int32_t* idx, int32_t* count, const float* task_scale,
                             float* partial, int d, int f, int n_tasks, int nblk, hipStream_t stream) {
     if (n_tasks == 0) return hipSuccess;

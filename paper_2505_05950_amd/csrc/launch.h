@@ -42,7 +42,8 @@ hipError_t launch_select(const float* v, int f, int n_tasks, const float* tau, i
 // S3 (compaction) + S4 + S5.  Index lists come either from mask_words (then idx/count are WRITTEN, both
 // may be nullptr) or, with mask_words == nullptr, from idx/count (read).  partial[task][blk][d].
 int gd_blocks(int n_tasks, int f);
-hipError_t launch_gate_down(const TaskMap& map, int staged, int gd_rows, const h16* x, const float* v,
+// staged: nullptr, or the staging buffer [n_tasks][gd_rows][2][d] whose row k of task q holds channel idx[q][k]
+hipError_t launch_gate_down(const TaskMap& map, const h16* staged, int gd_rows, const h16* x, const float* v,
                             const uint32_t* mask_words, int32_t* idx, int32_t* count, const float* task_scale,
                             float* partial, int d, int f, int n_tasks, int nblk, hipStream_t stream);
 
@@ -80,5 +81,9 @@ hipError_t launch_stats(const int32_t* task_expert, const int32_t* count, const 
 // S7
 hipError_t launch_stage(const h16* host_gd_dev, int d, int f, const int32_t* idx, const int32_t* count,
                         int capacity_rows, h16* dst, int32_t* overflow, hipStream_t stream);
+// all tasks of a layer at once: source matrix of task q = task_table[q].gd (device view of pinned host memory),
+// list idx[q][0..count[q]), destination dst[q][capacity_rows][2][d], overflow[q]
+hipError_t launch_stage_tasks(const DevExpert* task_table, int d, int f, const int32_t* idx, const int32_t* count,
+                              int capacity_rows, h16* dst, int32_t* overflow, int n_tasks, hipStream_t stream);
 
 }  // namespace floe

@@ -37,6 +37,48 @@ __global__ __launch_bounds__(256) void stage_kernel(const uint4* __restrict__ sr
     }
 }
 
+// Layer form: blockIdx.y = task; the source matrix, list and destination slab are the task's own.
+__global__ __launch_bounds__(256) void stage_tasks_kernel(const DevExpert* __restrict__ task_table, int vec_per_chunk,
+                                                          int f, const int32_t* __restrict__ idx,
+                                                          const int32_t* __restrict__ count, int capacity_rows,
+                                                          uint4* __restrict__ dst, int32_t* __restrict__ overflow) {
+    const int task = blockIdx.y;
+    const uint4* src = reinterpret_cast<const uint4*>(task_table[task].gd);
+    const int32_t* it = idx + (size_t)task * f;
+    uint4* out = dst + (size_t)task * capacity_rows * vec_per_chunk;
+    const int n = count[task];
+    const int K = min(n, capacity_rows);
+    if (overflow && blockIdx.x == 0 && threadIdx.x == 0) overflow[task] = n > capacity_rows ? 1 : 0;
+    const int lane = threadIdx.x & 63;
+    const int gw = blockIdx.x * 4 + (threadIdx.x >> 6);
+    const int nw = gridDim.x * 4;
+    for (int k = gw; k < K; k += nw) {
+        const int j = it[k];
+        if ((unsigned)j >= (unsigned)f) continue;
+        const uint4* s = src + (size_t)j * vec_per_chunk;
+        uint4* o = out + (size_t)k * vec_per_chunk;
+        for (int i = lane; i < vec_per_chunk; i += 4 * kWave) {
+            uint4 a = s[i];
+            uint4 b = i + kWave < vec_per_chunk ? s[i + kWave] : a;
+            uint4 c = i + 2 * kWave < vec_per_chunk ? s[i + 2 * kWave] : a;
+            uint4 e = i + 3 * kWave < vec_per_chunk ? s[i + 3 * kWave] : a;
+            o[i] = a;
+            if (i + kWave < vec_per_chunk) o[i + kWave] = b;
+            if (i + 2 * kWave < vec_per_chunk) o[i + 2 * kWave] = c;
+            if (i + 3 * kWave < vec_per_chunk) o[i + 3 * kWave] = e;
+        }
+    }
+}
+
+hipError_t launch_stage_tasks(const DevExpert* task_table, int d, int f, const int32_t* idx, const int32_t* count,
+                              int capacity_rows, h16* dst, int32_t* overflow, int n_tasks, hipStream_t stream) {
+    if (n_tasks == 0) return hipSuccess;
+    const int nblk = kNumCU / n_tasks > 0 ? kNumCU / n_tasks : 1;
+    stage_tasks_kernel<<<dim3(nblk, n_tasks), dim3(256), 0, stream>>>(task_table, d / 4, f, idx, count, capacity_rows,
+                                                                     reinterpret_cast<uint4*>(dst), overflow);
+    return hipGetLastError();
+}
+
 hipError_t launch_stage(const h16* host_gd_dev, int d, int f, const int32_t* idx, const int32_t* count, int capacity_rows,
                         h16* dst, int32_t* overflow, hipStream_t stream) {
     const int vec_per_chunk = d / 4;  // 2 * d halves = 4 * d bytes = d / 4 uint4

@@ -202,3 +202,63 @@ def test_layer_decode_replayed_from_a_hip_graph_matches_eager():
             torch.cuda.synchronize()
             assert torch.equal(y_static, eager[i]), (rep, i)
             _ = (y_static.float() * 2).sum().item()          # eager work between replays
+
+
+def test_offloaded_layer_matches_resident_layer_and_oracle():
+    """Gate/down matrices in pinned host memory, selected chunks staged on a side stream (Sec. 3.4.2)."""
+    import gpu_common as G
+    import paper_2505_05950_amd as F
+    d, f, bits, group, n, top_k, T, pct = 1024, 2048, 2, 64, 4, 2, 2, 80
+    experts = [G.make_expert(*S.expert_weights(16, 4, d, f, 0, e), bits, group) for e in range(n)]
+    experts_np = [e[0] for e in experts]
+    wr = S.router_weights(16, 4, n, d)
+    x = S.tokens(16, 4, T, d)
+    tau = np.zeros((T, n), np.float32)
+    for t in range(T):
+        for e in range(n):
+            tau[t, e] = O.threshold_for_sparsity(O.up_gemv(*experts_np[e][:3], d, bits, group, x[t]), pct)
+    # nudge the thresholds off the order statistic so that no channel sits exactly on them
+    tau *= np.float32(1.0 + 2e-3)
+    ref = O.moe_layer(experts_np, 0, top_k, True, wr, x, tau, bits, group)
+    L_res = F.Layer([e[1] for e in experts], 0, top_k, True, G.dev(wr), G.dev(tau), True)
+    y_res = F.floe_moe_layer_decode(L_res, G.dev(x)).clone()
+    pinned = [torch.from_numpy(e[3]).pin_memory() for e in experts_np]
+    ex_host = [F.Expert(d, f, bits, group, e[1].up_codes, e[1].up_scale, e[1].up_zero, pinned[i]) for i, e in enumerate(experts)]
+    L_off = F.Layer(ex_host, 0, top_k, True, G.dev(wr), G.dev(tau), True, gd_on_host=True)
+    with pytest.raises(F.FloeError):
+        F.floe_moe_layer_decode(L_off, G.dev(x))                    # resident entry point refuses host matrices
+    slots = top_k
+    side = torch.cuda.Stream()
+    ev_a, ev_b = torch.cuda.Event(), torch.cuda.Event()
+    for cap in (f, 256):
+        staging = torch.zeros((T * slots, cap, 2, d), dtype=torch.float16, device=G.DEV)
+        overflow = torch.full((T * slots,), 7, dtype=torch.int32, device=G.DEV)
+        stats = torch.zeros((T, slots, 4), dtype=torch.int32, device=G.DEV)
+        y = F.floe_moe_layer_decode_offloaded(L_off, G.dev(x), staging, cap, side, ev_a, ev_b, stats=stats, overflow=overflow)
+        torch.cuda.synchronize()
+        counts = stats.cpu().numpy().reshape(T, slots, 4)[:, :, 1]
+        assert np.array_equal(counts, ref["counts"])
+        if cap == f:
+            assert overflow.cpu().numpy().tolist() == [0] * (T * slots)
+            assert torch.equal(y, y_res)                            # same lists, same summation order
+            for t in range(T):
+                assert G.rel_err(y[t].cpu().numpy().astype(np.float64), ref["y"][t]) <= G.Y_TIGHT
+            # staged rows are byte copies of the host rows of the selected channels
+            st = staging.cpu().numpy()
+            for t in range(T):
+                for s_ in range(slots):
+                    e = int(ref["ids"][t, s_])
+                    v = O.up_gemv(*experts_np[e][:3], d, bits, group, x[t])
+                    sel = O.select(v, float(tau[t, e]))
+                    assert st[t * slots + s_, : sel.size].tobytes() == experts_np[e][3][sel].tobytes()
+        else:
+            assert np.all(counts > cap) and overflow.cpu().numpy().tolist() == [1] * (T * slots)
+            # truncated lists: the result is the oracle's FFN over the first `cap` channels of each list
+            for t in range(T):
+                acc = np.zeros(d)
+                for s_ in range(slots):
+                    e = int(ref["ids"][t, s_])
+                    v = O.up_gemv(*experts_np[e][:3], d, bits, group, x[t])
+                    sel = O.select(v, float(tau[t, e]))[:cap]
+                    acc += ref["weights"][t, s_] * O.sparse_ffn(experts_np[e][3], x[t], v, sel)[1]
+                assert G.rel_err(y[t].cpu().numpy().astype(np.float64), acc) <= G.Y_TIGHT
