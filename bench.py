@@ -29,6 +29,9 @@ HBM_PEAK_GBS = 8000.0
 D, F_INT, BITS, GROUP, N_EXPERTS, TOP_K, PCT = 4096, 14336, 2, 64, 8, 2, 90
 CONFIG_ID, SEED = 3, 0
 N_TOKENS = 16          # distinct decode tokens the steps cycle through
+# HBM bytes per launch of each kernel for THIS workload, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs scaled by
+# a plain 256 MiB copy (profiles/layer_decode_config3_T1_hbm_traffic.md); hardware counters cannot be read from here
+MEASURED_TRAFFIC_BYTES = {"up_gemv": 37.73e6, "gate_down": 51.56e6, "combine": 4.24e6}
 
 
 def log(*a):
@@ -63,6 +66,8 @@ def main():
                     help="layer: the headline metric (default); expert: single-expert sweep over bit widths and "
                          "sparsity levels (Table 1 protocol); stage: host->HBM transfer of selected channels; "
                          "stack: 32 offloaded layers per token, gate/down matrices in pinned host memory")
+    ap.add_argument("--calib-copy", action="store_true",
+                    help="also run a plain 256 MiB device copy five times (reference for hardware-counter runs)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0)
     args = ap.parse_args()
@@ -212,11 +217,18 @@ def main():
     kernels = {n: {"us": round(per_kernel[n], 3), "algorithmic_bytes": int(kernel_bytes[n]),
                    "GBps": round(kernel_bytes[n] / (per_kernel[n] * 1e-6) / 1e9, 1)} for n in per_kernel}
     roofline = {"bound": "hbm", "kernel": dominant, "achieved": round(dom_gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                "frac": round(dom_gbs / HBM_PEAK_GBS, 4), "traffic": None,
+                "frac": round(dom_gbs / HBM_PEAK_GBS, 4), "traffic": MEASURED_TRAFFIC_BYTES.get(dominant),
                 "kernel_us": round(per_kernel[dominant], 3), "kernels": kernels,
                 "layer_bytes": int(bytes_step),
                 "layer_frac": round(bytes_step / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
                 "timing": "hipEvent pair recorded around each launch of the kernel, second pass over the same K steps"}
+
+    if args.calib_copy:
+        src = torch.ones((64 << 20,), dtype=torch.float32, device=dev)     # 256 MiB read + 256 MiB written per copy
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
 
     # ---------------------------------------------------------------- CPU oracle on a bounded sample
     cpu = None
