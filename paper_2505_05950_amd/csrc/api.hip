@@ -107,10 +107,9 @@ ExpertWs expert_ws(const floe_shape* s, int T) {
 // lists longer than this are compacted by the select kernel instead of inside the gate/down kernel
 bool mask_path_ok(int f) { return mask_words_per_task(f) <= 2048; }
 
-// workspace of the layer: per-task table, counts, mask words, prepared activations, v, idx, partial
+// workspace of the layer: per-task table, counts, mask words, v, idx, partial
 struct LayerWs {
-    size_t table_off, expert_off, weight_off, tau_off, count_off, mask_off, xs_off, xoff_off, xg_off, invp_off, v_off,
-        idx_off, partial_off, total;
+    size_t table_off, expert_off, weight_off, tau_off, count_off, mask_off, v_off, idx_off, partial_off, total;
     int n_tasks, nblk;
 };
 LayerWs layer_ws(const floe_layer* L, int T) {
@@ -118,7 +117,6 @@ LayerWs layer_ws(const floe_layer* L, int T) {
     const int slots = L->top_k + L->n_shared;
     w.n_tasks = T * slots;
     w.nblk = gd_blocks(w.n_tasks, L->s.f);
-    const size_t upc = (size_t)L->s.d / 64;
     size_t o = 0;
     w.table_off = o;  o += align_up((size_t)w.n_tasks * sizeof(DevExpert));
     w.expert_off = o; o += align_up((size_t)w.n_tasks * 4);
@@ -126,10 +124,6 @@ LayerWs layer_ws(const floe_layer* L, int T) {
     w.tau_off = o;    o += align_up((size_t)w.n_tasks * 4);
     w.count_off = o;  o += align_up((size_t)w.n_tasks * 4);
     w.mask_off = o;   o += align_up((size_t)w.n_tasks * mask_words_per_task(L->s.f) * 4);
-    w.xs_off = o;     o += align_up((size_t)T * L->s.d * 2);
-    w.xoff_off = o;   o += align_up((size_t)T * upc * 4);
-    w.xg_off = o;     o += align_up((size_t)T * upc * 4);
-    w.invp_off = o;   o += align_up((size_t)T * 4);
     w.v_off = o;      o += align_up((size_t)w.n_tasks * L->s.f * 4);
     w.idx_off = o;    o += align_up((size_t)w.n_tasks * L->s.f * 4);
     w.partial_off = o; o += align_up((size_t)w.n_tasks * w.nblk * L->s.d * 4);
@@ -201,7 +195,7 @@ int floe_up_gemv(const floe_shape* s, const uint32_t* codes, const floe_half* sc
     floe_expert e{};
     e.up_codes = codes; e.up_scale = scale; e.up_zero = zero;
     FLOE_LAUNCH(FLOE_KERNEL_UP_GEMV, (hipStream_t)stream,
-                launch_up_gemv(single_map(&e), reinterpret_cast<const h16*>(x), nullptr, nullptr, v, nullptr, nullptr, s->d, s->f,
+                launch_up_gemv(single_map(&e), reinterpret_cast<const h16*>(x), nullptr, v, nullptr, nullptr, s->d, s->f,
                                s->bits, s->group, T, (hipStream_t)stream));
     return FLOE_OK;
 }
@@ -270,13 +264,13 @@ int floe_expert_ffn_sparse(const floe_expert* e, const floe_half* x, int T, cons
     if (mask_path_ok(e->s.f)) {
         // the GEMV leaves one mask bit per channel; the gate/down kernel compacts them and writes idx / count
         FLOE_LAUNCH(FLOE_KERNEL_UP_GEMV, st,
-                    launch_up_gemv(map, xh, nullptr, nullptr, v, tau, mask, e->s.d, e->s.f, e->s.bits, e->s.group, T, st));
+                    launch_up_gemv(map, xh, nullptr, v, tau, mask, e->s.d, e->s.f, e->s.bits, e->s.group, T, st));
         FLOE_LAUNCH(FLOE_KERNEL_GATE_DOWN, st,
                     launch_gate_down(map, nullptr, e->s.f, xh, v, mask, idx, count, out_scale, partial, e->s.d, e->s.f, T,
                                      w.nblk, st));
     } else {
         FLOE_LAUNCH(FLOE_KERNEL_UP_GEMV, st,
-                    launch_up_gemv(map, xh, nullptr, nullptr, v, nullptr, nullptr, e->s.d, e->s.f, e->s.bits, e->s.group, T, st));
+                    launch_up_gemv(map, xh, nullptr, v, nullptr, nullptr, e->s.d, e->s.f, e->s.bits, e->s.group, T, st));
         FLOE_LAUNCH(FLOE_KERNEL_SELECT, st, launch_select(v, e->s.f, T, tau, idx, count, st));
         FLOE_LAUNCH(FLOE_KERNEL_GATE_DOWN, st,
                     launch_gate_down(map, nullptr, e->s.f, xh, v, nullptr, idx, count, out_scale, partial, e->s.d, e->s.f, T,
@@ -349,7 +343,6 @@ int floe_moe_layer_decode(const floe_layer* L, const floe_half* x, int T, floe_h
     hipStream_t st = (hipStream_t)stream;
     const h16* xh = reinterpret_cast<const h16*>(x);
     const int slots = L->top_k + L->n_shared;
-    const bool fast_up = int2_fast_shape(L->s.d, L->s.bits, L->s.group);
 
     TaskMap map{};
     map.task_table = task_table;
@@ -366,7 +359,7 @@ int floe_moe_layer_decode(const floe_layer* L, const floe_half* x, int T, floe_h
         ro.task_table = task_table;
         ro.task_expert = task_expert; ro.task_weight = task_weight; ro.task_tau = task_tau;
         FLOE_LAUNCH(FLOE_KERNEL_UP_GEMV, st,
-                    launch_up_gemv(map, xh, nullptr, &ro, v, nullptr, mask, L->s.d, L->s.f, L->s.bits, L->s.group,
+                    launch_up_gemv(map, xh, &ro, v, nullptr, mask, L->s.d, L->s.f, L->s.bits, L->s.group,
                                    w.n_tasks, st));
         FLOE_LAUNCH(FLOE_KERNEL_GATE_DOWN, st,
                     launch_gate_down(map, nullptr, L->s.f, xh, v, mask, nullptr, count, task_weight, partial, L->s.d, L->s.f,
@@ -382,25 +375,17 @@ int floe_moe_layer_decode(const floe_layer* L, const floe_half* x, int T, floe_h
         ra.table = static_cast<const DevExpert*>(L->dev_table);
         ra.task_table = task_table;
         ra.task_expert = task_expert; ra.task_weight = task_weight; ra.task_tau = task_tau;
-        ra.xprep = XPrep{};
-        if (fast_up) {
-            ra.xprep.xs = reinterpret_cast<uint4*>(base + w.xs_off);
-            ra.xprep.xoff = reinterpret_cast<float*>(base + w.xoff_off);
-            ra.xprep.xg = reinterpret_cast<float*>(base + w.xg_off);
-            ra.xprep.inv_p = reinterpret_cast<float*>(base + w.invp_off);
-        }
         FLOE_LAUNCH(FLOE_KERNEL_ROUTER, st, launch_router(ra, T, st));
-        const XPrep* xpp = fast_up ? &ra.xprep : nullptr;
         if (mask_ok) {
             FLOE_LAUNCH(FLOE_KERNEL_UP_GEMV, st,
-                        launch_up_gemv(map, xh, xpp, nullptr, v, task_tau, mask, L->s.d, L->s.f, L->s.bits, L->s.group,
+                        launch_up_gemv(map, xh, nullptr, v, task_tau, mask, L->s.d, L->s.f, L->s.bits, L->s.group,
                                        w.n_tasks, st));
             FLOE_LAUNCH(FLOE_KERNEL_GATE_DOWN, st,
                         launch_gate_down(map, nullptr, L->s.f, xh, v, mask, nullptr, count, task_weight, partial, L->s.d,
                                          L->s.f, w.n_tasks, w.nblk, st));
         } else {
             FLOE_LAUNCH(FLOE_KERNEL_UP_GEMV, st,
-                        launch_up_gemv(map, xh, xpp, nullptr, v, nullptr, nullptr, L->s.d, L->s.f, L->s.bits,
+                        launch_up_gemv(map, xh, nullptr, v, nullptr, nullptr, L->s.d, L->s.f, L->s.bits,
                                        L->s.group, w.n_tasks, st));
             FLOE_LAUNCH(FLOE_KERNEL_SELECT, st, launch_select(v, L->s.f, w.n_tasks, task_tau, idx, count, st));
             FLOE_LAUNCH(FLOE_KERNEL_GATE_DOWN, st,
@@ -450,7 +435,7 @@ int floe_moe_layer_decode_offloaded(const floe_layer* L, const floe_offload* o, 
         ro.task_table = task_table;
         ro.task_expert = task_expert; ro.task_weight = task_weight; ro.task_tau = task_tau;
         FLOE_LAUNCH(FLOE_KERNEL_UP_GEMV, st,
-                    launch_up_gemv(map, xh, nullptr, &ro, v, nullptr, nullptr, L->s.d, L->s.f, L->s.bits, L->s.group,
+                    launch_up_gemv(map, xh, &ro, v, nullptr, nullptr, L->s.d, L->s.f, L->s.bits, L->s.group,
                                    w.n_tasks, st));
     } else {
         RouterArgs ra;
@@ -463,10 +448,9 @@ int floe_moe_layer_decode_offloaded(const floe_layer* L, const floe_offload* o, 
         ra.table = static_cast<const DevExpert*>(L->dev_table);
         ra.task_table = task_table;
         ra.task_expert = task_expert; ra.task_weight = task_weight; ra.task_tau = task_tau;
-        ra.xprep = XPrep{};
         FLOE_LAUNCH(FLOE_KERNEL_ROUTER, st, launch_router(ra, T, st));
         FLOE_LAUNCH(FLOE_KERNEL_UP_GEMV, st,
-                    launch_up_gemv(map, xh, nullptr, nullptr, v, nullptr, nullptr, L->s.d, L->s.f, L->s.bits, L->s.group,
+                    launch_up_gemv(map, xh, nullptr, v, nullptr, nullptr, L->s.d, L->s.f, L->s.bits, L->s.group,
                                    w.n_tasks, st));
     }
     FLOE_LAUNCH(FLOE_KERNEL_SELECT, st, launch_select(v, L->s.f, w.n_tasks, task_tau, idx, count, st));

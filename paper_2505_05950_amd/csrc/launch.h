@@ -13,9 +13,9 @@ namespace floe {
 
 constexpr int kNumCU = 256;  // MI355X
 
-// true when the packed-fp16 INT2 kernel (and its prepared activations) applies to this shape
-inline bool int2_fast_shape(int d, int bits, int group) {
-    return bits == 2 && group >= 64 && (d == 1024 || d == 2048 || d == 4096);
+// true when the packed-fp16 kernel applies to this shape (otherwise the generic kernel runs)
+inline bool packed_fast_shape(int d, int bits, int group) {
+    return (bits == 2 || bits == 3 || bits == 4) && group >= 32 && (d == 1024 || d == 2048 || d == 4096);
 }
 __host__ __device__ inline int mask_words_per_task(int f) { return (f + 31) / 32; }
 
@@ -24,15 +24,14 @@ hipError_t launch_quantize(const h16* w, uint32_t* codes, h16* scale, h16* zero,
                            hipStream_t stream);
 
 // S2 (+ the comparison of S3): v[task][j] for task in [0, n_tasks); token of a task = task / map.slots.
-// xprep: prepared activations or nullptr (then the kernel prepares them itself).
 // task_tau / mask_words: when both are given, bit (j % 32) of mask_words[task][j / 32] = (|v_j| > tau[task]).
-// route: when given (INT2 fast shapes, n_experts <= 16 only) the kernel routes in place and fills the
-// task table itself; map.task_table, xprep and task_tau are then ignored.
-hipError_t launch_up_gemv(const TaskMap& map, const h16* x, const XPrep* xprep, const RouteArgs* route, float* v,
-                          const float* task_tau, uint32_t* mask_words, int d, int f, int bits, int group, int n_tasks,
-                          hipStream_t stream);
+// route: when given (INT2, group >= 64, packed shapes, n_experts <= 16 only) the kernel routes in place and
+// fills the task table itself; map.task_table and task_tau are then ignored.
+hipError_t launch_up_gemv(const TaskMap& map, const h16* x, const RouteArgs* route, float* v, const float* task_tau,
+                          uint32_t* mask_words, int d, int f, int bits, int group, int n_tasks, hipStream_t stream);
 inline bool route_in_place_ok(int d, int bits, int group, int n_experts, int top_k, int n_shared) {
-    return int2_fast_shape(d, bits, group) && top_k >= 1 && n_experts <= 16 && top_k + n_shared <= 16;
+    return bits == 2 && group >= 64 && packed_fast_shape(d, bits, group) && top_k >= 1 && n_experts <= 16 &&
+           top_k + n_shared <= 16;
 }
 
 // S3 as a kernel of its own: per task threshold tau[task]
@@ -52,7 +51,7 @@ hipError_t launch_gate_down(const TaskMap& map, const h16* staged, int gd_rows, 
 hipError_t launch_combine(const float* partial, int d, int T, int slots, int nblk, float* y_acc, h16* y_half,
                           hipStream_t stream);
 
-// S1: router + per-task table (resolved expert pointers, weight, tau) + prepared activations
+// S1: router + per-task table (resolved expert pointers, weight, tau)
 struct RouterArgs {
     const h16* router_cm;
     const h16* x;
@@ -64,7 +63,6 @@ struct RouterArgs {
     int32_t* task_expert;     // [n_tasks] out
     float* task_weight;       // [n_tasks] out
     float* task_tau;          // [n_tasks] out
-    XPrep xprep;              // xs == nullptr: not wanted
 };
 hipError_t launch_router(const RouterArgs& a, int T, hipStream_t stream);
 

@@ -6,7 +6,6 @@
 #include "floe_dev.h"
 #include "launch.h"
 #include "route.h"
-#include "xprep.h"
 
 namespace floe {
 
@@ -14,33 +13,6 @@ constexpr int kMaxExperts = 1024;
 
 // All loads of a dot product are in flight together: a lane fetches its 16-byte pieces of x once
 // (up to 16 of them, d <= 8192) and of the current expert row, then reduces with packed dot products.
-template <int UPC>
-__device__ __forceinline__ void write_xprep(const RouterArgs& a, int t, int lane) {
-    // lanes 0..UPC-1 of one wave prepare one unit each (see xprep.h)
-    const int d = UPC * 64;
-    const int u = lane < UPC ? lane : UPC - 1;
-    uint32_t raw[32];
-    const uint4* xq = reinterpret_cast<const uint4*>(a.x + (size_t)t * d + u * 64);
-#pragma unroll
-    for (int r = 0; r < 8; ++r) {
-        const uint4 q = xq[r];
-        raw[4 * r + 0] = q.x; raw[4 * r + 1] = q.y; raw[4 * r + 2] = q.z; raw[4 * r + 3] = q.w;
-    }
-    const float amax = wave_allreduce_max_nonneg(unit_amax(raw));
-    const int down = xprep_down(amax);
-    uint32_t xs[32];
-    float Xoff, Xg;
-    unit_prepare(raw, down, xs, Xoff, Xg);
-    if (lane < UPC) {
-#pragma unroll
-        for (int r = 0; r < 8; ++r)
-            a.xprep.xs[((size_t)t * 8 + r) * UPC + u] = make_uint4(xs[4 * r], xs[4 * r + 1], xs[4 * r + 2], xs[4 * r + 3]);
-        a.xprep.xoff[(size_t)t * UPC + u] = Xoff;
-        a.xprep.xg[(size_t)t * UPC + u] = Xg;
-        if (lane == 0) a.xprep.inv_p[t] = ldexpf(1.0f, down);
-    }
-}
-
 __global__ __launch_bounds__(256) void router_kernel(RouterArgs a) {
     __shared__ float prob[kMaxExperts];
     __shared__ int sel_id[64];
@@ -73,12 +45,6 @@ __global__ __launch_bounds__(256) void router_kernel(RouterArgs a) {
             acc = wave_allreduce_sum(acc);
             if (lane == 0) prob[e] = acc;
         }
-    }
-    // prepared activations for the packed INT2 GEMV: the last wave does it while wave 0 routes
-    if (a.xprep.xs != nullptr && wave == 3) {
-        if (d == 4096) write_xprep<64>(a, t, lane);
-        else if (d == 2048) write_xprep<32>(a, t, lane);
-        else if (d == 1024) write_xprep<16>(a, t, lane);
     }
     __syncthreads();
     if (tid == 0) route_select(prob, a.n_experts, a.top_k, a.n_shared, a.renormalize, sel_id, sel_w);

@@ -85,27 +85,44 @@ __global__ __launch_bounds__(256) void up_gemv_generic_kernel(TaskMap map, const
 }
 
 // ---------------------------------------------------------------------------------------------------
-// INT2 fast kernel: group >= 64, d = 64 * UPC with UPC in {16, 32, 64}.
-// A lane owns one 64-code unit (one 128-bit load).  Codes are never converted to numbers one by one:
-// OR-ing a 2-bit field that sits at mantissa bits [p, p+2) of each 16-bit half into 0x3C00 gives the
-// fp16 pair (1 + q * 2^(p-10)); with x pre-multiplied by 2^(10-p) a packed dot product accumulates
-// c*x + x*q, and the c*x part is removed once per unit (Xoff).  Field positions used: p = 4, 6, 8
-// (c = 64, 16, 4) from the word itself, the word << 4 and the word >> 6, so 16 codes cost
-// 2 shifts + 8 and-or + 8 dot2.  Pairs are (code m, code m+8) of a word: the two halves of the register.
-// x is pre-scaled by a power of two so that 64*|x| stays finite in fp16; v is scaled back at the end.
-// The prepared activations come from HBM (written once per token by the router kernel) when PREPPED,
-// otherwise every wave prepares them itself.
+// Packed-fp16 fast kernel: bits 2, 3 or 4; d = 64 * UPC with UPC in {16, 32, 64}; any group >= 32.
+// A lane owns one 64-code unit of a channel (4 / 6 / 8 code words, loaded with 128-bit or 64-bit loads
+// that the wave issues fully coalesced) and the 64 activations that meet it, prepared once per wave
+// as 32 fp16 pairs (xprep.h).  A 64-lane wave therefore covers 64 / UPC channels per pass.
+// Per half unit (32 codes) the lane gets sum x'q as a packed dot product, applies the group's scale and
+// zero point as s * (dot - Xoff - z * Xg), and the UPC lanes of a channel are summed on the DPP path.
+// Groups of 32 use one (scale, zero) per half unit, larger groups one per unit.
+// All weight loads of the kPasses passes are issued before the first one is used.
+// ROUTED (INT2 layer path, <= 16 experts): the workgroup first computes the router itself.
 // ---------------------------------------------------------------------------------------------------
-enum { kModeRaw = 0, kModePrepped = 1, kModeRouted = 2 };
+template <int BITS>
+__device__ __forceinline__ void load_unit(const uint32_t* __restrict__ codes, size_t unit_index, uint32_t* cw) {
+    constexpr int W = PackedTraits<BITS>::kWords;
+    const uint32_t* p = codes + unit_index * W;
+    if (BITS == 2) {
+        const uint4 q = *reinterpret_cast<const uint4*>(p);
+        cw[0] = q.x; cw[1] = q.y; cw[2] = q.z; cw[3] = q.w;
+    } else if (BITS == 4) {
+        const uint4 q0 = reinterpret_cast<const uint4*>(p)[0], q1 = reinterpret_cast<const uint4*>(p)[1];
+        cw[0] = q0.x; cw[1] = q0.y; cw[2] = q0.z; cw[3] = q0.w;
+        cw[4] = q1.x; cw[5] = q1.y; cw[6] = q1.z; cw[7] = q1.w;
+    } else {  // 24 bytes, 8-byte aligned
+        const uint2 q0 = reinterpret_cast<const uint2*>(p)[0], q1 = reinterpret_cast<const uint2*>(p)[1],
+                    q2 = reinterpret_cast<const uint2*>(p)[2];
+        cw[0] = q0.x; cw[1] = q0.y; cw[2] = q1.x; cw[3] = q1.y; cw[4] = q2.x; cw[5] = q2.y;
+    }
+}
 
-template <int UPC, int MODE, int kPasses>
-__global__ __launch_bounds__(256) void up_gemv_int2_kernel(TaskMap map, const h16* __restrict__ x, XPrep xp,
-                                                           RouteArgs ro, float* __restrict__ v,
-                                                           const float* __restrict__ task_tau,
-                                                           uint32_t* __restrict__ mask_words, int f, int gshift) {
+template <int BITS, int UPC, bool ROUTED, int kPasses, bool G32>
+__global__ __launch_bounds__(256) void up_gemv_packed_kernel(TaskMap map, const h16* __restrict__ x, RouteArgs ro,
+                                                             float* __restrict__ v,
+                                                             const float* __restrict__ task_tau,
+                                                             uint32_t* __restrict__ mask_words, int f, int gshift) {
     constexpr int CPW = kWave / UPC;  // channels per wave pass
     constexpr int d = UPC * 64;
+    constexpr int kCw = PackedTraits<BITS>::kWords;
     constexpr int kWords = (kPasses * CPW * 4 + 31) / 32;  // mask words per workgroup
+    static_assert((kPasses * CPW * 4) % 32 == 0, "a workgroup covers whole mask words");
     __shared__ uint32_t mw[kWords];
     __shared__ float prob[16];
     __shared__ int sel_id[16];
@@ -124,8 +141,8 @@ __global__ __launch_bounds__(256) void up_gemv_int2_kernel(TaskMap map, const h1
     DevExpert e;
     float tau = 0.0f;
     bool want_mask = mask_words != nullptr;
-    uint32_t raw[32];  // this lane's 64 activations (kModeRaw / kModeRouted)
-    if (MODE != kModePrepped) {
+    uint32_t raw[32];  // this lane's 64 activations
+    {
         const uint4* xq = reinterpret_cast<const uint4*>(x + (size_t)t * d + u * 64);
 #pragma unroll
         for (int r = 0; r < 8; ++r) {
@@ -133,16 +150,16 @@ __global__ __launch_bounds__(256) void up_gemv_int2_kernel(TaskMap map, const h1
             raw[4 * r + 0] = q.x; raw[4 * r + 1] = q.y; raw[4 * r + 2] = q.z; raw[4 * r + 3] = q.w;
         }
     }
-    if (MODE == kModeRouted) {
+    if (ROUTED) {
         // ---- S1 in place: every workgroup of the layer computes the same few dot products (n_experts <= 16,
-        // the router matrix sits in L2), so no kernel of its own and no global hand-off is needed
-        // a whole wave per expert, two experts in flight per wave, fully coalesced 16-byte pieces
-        // every expert's table entry and threshold is fetched now, so that nothing has to be loaded from
-        // global memory between knowing the routed expert and requesting its codes
+        // the router matrix sits in L2), so no kernel of its own and no global hand-off is needed.
+        // Every expert's table entry and threshold is fetched now, so that nothing has to be loaded from
+        // global memory between knowing the routed expert and requesting its codes.
         if (tid < ro.n_experts + ro.n_shared) {
             tab[tid] = ro.table[tid];
             taus[tid] = ro.tau[(size_t)t * ro.tau_stride_t + tid];
         }
+        // a whole wave per expert, two experts in flight per wave, fully coalesced 16-byte pieces
         constexpr int NVR = d / 512;
         uint4 xl[NVR];
         {
@@ -198,38 +215,32 @@ __global__ __launch_bounds__(256) void up_gemv_int2_kernel(TaskMap map, const h1
     FLOE_TL(3);
     // ---- issue the weight loads: kPasses passes of CPW channels per wave
     const int jw = (blockIdx.x * 4 + wave) * (kPasses * CPW);
-    const uint4* codes4 = reinterpret_cast<const uint4*>(e.codes);
-    uint4 cw[kPasses];
-    h16 sc[kPasses], zr[kPasses];
+    uint32_t cw[kPasses][kCw];
+    uint32_t meta_s[kPasses], meta_z[kPasses];  // one fp16 (groups >= 64) or two (groups of 32) per unit
 #pragma unroll
     for (int p = 0; p < kPasses; ++p) {
         int j = jw + p * CPW + sub;
         j = j < f ? j : f - 1;  // keep the address in bounds; the result of a clamped lane is not stored
-        cw[p] = codes4[(size_t)j * UPC + u];
-        const size_t mi = (size_t)j * G + ((u * 64) >> gshift);
-        sc[p] = e.scale[mi];
-        zr[p] = e.zero[mi];
+        load_unit<BITS>(e.codes, (size_t)j * UPC + u, cw[p]);
+        if (G32) {
+            const size_t mi = (size_t)j * G + 2 * u;  // even index: 4-byte aligned
+            meta_s[p] = *reinterpret_cast<const uint32_t*>(e.scale + mi);
+            meta_z[p] = *reinterpret_cast<const uint32_t*>(e.zero + mi);
+        } else {
+            const size_t mi = (size_t)j * G + ((u * 64) >> gshift);
+            meta_s[p] = *reinterpret_cast<const uint16_t*>(e.scale + mi);
+            meta_z[p] = *reinterpret_cast<const uint16_t*>(e.zero + mi);
+        }
     }
 
     // ---- activations of this lane's unit: 32 scaled fp16 pairs
     uint32_t xs[32];
-    float Xg, Xoff, inv_p;
-    if (MODE == kModePrepped) {
-#pragma unroll
-        for (int r = 0; r < 8; ++r) {
-            const uint4 q = xp.xs[((size_t)t * 8 + r) * UPC + u];
-            xs[4 * r + 0] = q.x; xs[4 * r + 1] = q.y; xs[4 * r + 2] = q.z; xs[4 * r + 3] = q.w;
-        }
-        Xoff = xp.xoff[(size_t)t * UPC + u];
-        Xg = xp.xg[(size_t)t * UPC + u];
-        inv_p = xp.inv_p[t];
-    } else {
-        // every group of UPC lanes holds the whole token, so the wave-wide maximum is the token's
-        const float amax = wave_allreduce_max_nonneg(unit_amax(raw));
-        const int down = xprep_down(amax);
-        inv_p = ldexpf(1.0f, down);
-        unit_prepare(raw, down, xs, Xoff, Xg);
-    }
+    float Xg[2], Xoff[2];
+    // every group of UPC lanes holds the whole token, so the wave-wide maximum is the token's
+    const float amax = wave_allreduce_max_nonneg(unit_amax(raw));
+    const int down = xprep_down<BITS>(amax);
+    const float inv_p = ldexpf(1.0f, down);
+    unit_prepare<BITS>(raw, down, xs, Xoff, Xg);
     uint32_t magic = 0x3C003C00u;
     asm volatile("" : "+v"(magic));  // keep it in a VGPR: v_and_or_b32 takes one scalar operand only
     __syncthreads();                 // mw zeroed
@@ -238,22 +249,17 @@ __global__ __launch_bounds__(256) void up_gemv_int2_kernel(TaskMap map, const h1
 #pragma unroll
     for (int p = 0; p < kPasses; ++p) {
         const int j = jw + p * CPW + sub;
-        const uint32_t W[4] = {cw[p].x, cw[p].y, cw[p].z, cw[p].w};
-        float dot = 0.0f;
-#pragma unroll
-        for (int w = 0; w < 4; ++w) {
-            const uint32_t a = W[w] << 4, b = W[w] >> 6;
-            dot = dot2(xs[8 * w + 0], and_or(a, 0x00300030u, magic), dot);
-            dot = dot2(xs[8 * w + 1], and_or(a, 0x00C000C0u, magic), dot);
-            dot = dot2(xs[8 * w + 2], and_or(W[w], 0x00300030u, magic), dot);
-            dot = dot2(xs[8 * w + 3], and_or(W[w], 0x00C000C0u, magic), dot);
-            dot = dot2(xs[8 * w + 4], and_or(W[w], 0x03000300u, magic), dot);
-            dot = dot2(xs[8 * w + 5], and_or(b, 0x00300030u, magic), dot);
-            dot = dot2(xs[8 * w + 6], and_or(b, 0x00C000C0u, magic), dot);
-            dot = dot2(xs[8 * w + 7], and_or(b, 0x03000300u, magic), dot);
+        const float dot0 = half_unit_dot<BITS>(cw[p], xs, 0, magic);
+        const float dot1 = half_unit_dot<BITS>(cw[p], xs, 1, magic);
+        float part;
+        if (G32) {
+            const h16x2 s2 = as_h2(meta_s[p]), z2 = as_h2(meta_z[p]);
+            part = (float)s2.x * fmaf(-(float)z2.x, Xg[0], dot0 - Xoff[0]) +
+                   (float)s2.y * fmaf(-(float)z2.y, Xg[1], dot1 - Xoff[1]);
+        } else {
+            const float s = (float)as_h2(meta_s[p]).x, z = (float)as_h2(meta_z[p]).x;
+            part = s * fmaf(-z, Xg[0] + Xg[1], (dot0 + dot1) - (Xoff[0] + Xoff[1]));
         }
-        const float s = (float)sc[p], z = (float)zr[p];
-        float part = s * fmaf(-z, Xg, dot - Xoff);
         part = group_reduce_sum_to_last<UPC>(part) * inv_p;
         if (p == 0) FLOE_TL(5);
         if (u == UPC - 1 && j < f) {
@@ -286,46 +292,51 @@ static int ilog2_exact(int g) {
 
 constexpr int kPassesPlain = 8, kPassesRouted = 16;
 
-template <int UPC>
-static void launch_int2(int mode, int f, int n_tasks, hipStream_t stream, const TaskMap& map, const h16* x,
-                        const XPrep& xp, const RouteArgs& ro, float* v, const float* task_tau, uint32_t* mask_words,
-                        int gshift) {
+template <int BITS, int UPC>
+static void launch_packed(bool routed, bool g32, int f, int n_tasks, hipStream_t stream, const TaskMap& map,
+                          const h16* x, const RouteArgs& ro, float* v, const float* task_tau, uint32_t* mask_words,
+                          int gshift) {
     const dim3 block(256);
-    const int passes = mode == kModeRouted ? kPassesRouted : kPassesPlain;
+    const int passes = routed ? kPassesRouted : kPassesPlain;
     const int ch_per_wg = 4 * passes * (64 / UPC);
     const dim3 grid((f + ch_per_wg - 1) / ch_per_wg, n_tasks);
-    if (mode == kModeRouted)
-        up_gemv_int2_kernel<UPC, kModeRouted, kPassesRouted><<<grid, block, 0, stream>>>(map, x, xp, ro, v, task_tau, mask_words, f, gshift);
-    else if (mode == kModePrepped)
-        up_gemv_int2_kernel<UPC, kModePrepped, kPassesPlain><<<grid, block, 0, stream>>>(map, x, xp, ro, v, task_tau, mask_words, f, gshift);
-    else
-        up_gemv_int2_kernel<UPC, kModeRaw, kPassesPlain><<<grid, block, 0, stream>>>(map, x, xp, ro, v, task_tau, mask_words, f, gshift);
+    if (routed) {
+        if (BITS == 2 && !g32)
+            up_gemv_packed_kernel<2, UPC, true, kPassesRouted, false><<<grid, block, 0, stream>>>(map, x, ro, v, task_tau, mask_words, f, gshift);
+    } else if (g32) {
+        up_gemv_packed_kernel<BITS, UPC, false, kPassesPlain, true><<<grid, block, 0, stream>>>(map, x, ro, v, task_tau, mask_words, f, gshift);
+    } else {
+        up_gemv_packed_kernel<BITS, UPC, false, kPassesPlain, false><<<grid, block, 0, stream>>>(map, x, ro, v, task_tau, mask_words, f, gshift);
+    }
 }
 
-hipError_t launch_up_gemv(const TaskMap& map, const h16* x, const XPrep* xprep, const RouteArgs* route, float* v,
-                          const float* task_tau, uint32_t* mask_words, int d, int f, int bits, int group, int n_tasks,
-                          hipStream_t stream) {
+template <int BITS>
+static void launch_packed_upc(int upc, bool routed, bool g32, int f, int n_tasks, hipStream_t stream, const TaskMap& map,
+                              const h16* x, const RouteArgs& ro, float* v, const float* task_tau, uint32_t* mask_words,
+                              int gshift) {
+    if (upc == 64) launch_packed<BITS, 64>(routed, g32, f, n_tasks, stream, map, x, ro, v, task_tau, mask_words, gshift);
+    else if (upc == 32) launch_packed<BITS, 32>(routed, g32, f, n_tasks, stream, map, x, ro, v, task_tau, mask_words, gshift);
+    else launch_packed<BITS, 16>(routed, g32, f, n_tasks, stream, map, x, ro, v, task_tau, mask_words, gshift);
+}
+
+hipError_t launch_up_gemv(const TaskMap& map, const h16* x, const RouteArgs* route, float* v, const float* task_tau,
+                          uint32_t* mask_words, int d, int f, int bits, int group, int n_tasks, hipStream_t stream) {
     if (f == 0 || n_tasks == 0) return hipSuccess;
     const int gshift = ilog2_exact(group);
     dim3 block(256);
-    if (int2_fast_shape(d, bits, group)) {
+    if (packed_fast_shape(d, bits, group)) {
         const int upc = d / 64;
-        int mode = kModeRaw;
-        XPrep xp{};
+        const bool routed = route != nullptr;
+        const bool g32 = group == 32;
+        if (routed && !(bits == 2 && !g32)) return hipErrorInvalidValue;
         RouteArgs ro{};
-        if (route != nullptr) {
-            mode = kModeRouted;
-            ro = *route;
-        } else if (xprep != nullptr && xprep->xs != nullptr) {
-            mode = kModePrepped;
-            xp = *xprep;
-        }
-        if (upc == 64) launch_int2<64>(mode, f, n_tasks, stream, map, x, xp, ro, v, task_tau, mask_words, gshift);
-        else if (upc == 32) launch_int2<32>(mode, f, n_tasks, stream, map, x, xp, ro, v, task_tau, mask_words, gshift);
-        else launch_int2<16>(mode, f, n_tasks, stream, map, x, xp, ro, v, task_tau, mask_words, gshift);
+        if (routed) ro = *route;
+        if (bits == 2) launch_packed_upc<2>(upc, routed, g32, f, n_tasks, stream, map, x, ro, v, task_tau, mask_words, gshift);
+        else if (bits == 3) launch_packed_upc<3>(upc, false, g32, f, n_tasks, stream, map, x, ro, v, task_tau, mask_words, gshift);
+        else launch_packed_upc<4>(upc, false, g32, f, n_tasks, stream, map, x, ro, v, task_tau, mask_words, gshift);
         return hipGetLastError();
     }
-    if (route != nullptr) return hipErrorInvalidValue;  // in-place routing exists only in the INT2 kernel
+    if (route != nullptr) return hipErrorInvalidValue;  // in-place routing exists only in the packed INT2 kernel
     dim3 grid((f + 31) / 32, n_tasks);
     switch (bits) {
         case 2: up_gemv_generic_kernel<2><<<grid, block, 0, stream>>>(map, x, v, task_tau, mask_words, d, f, gshift); break;

@@ -57,12 +57,16 @@ def test_quantize_config1_shape_bit_exact():
     (2, 64, 1024, 3584, 1),     # config 1 shape, packed-fp16 fast path (16 lanes per channel)
     (2, 64, 4096, 1000, 3),     # fast path, ragged f (not a multiple of the 32 channels per workgroup)
     (2, 128, 2048, 515, 2),     # fast path with a group that spans two lanes
-    (2, 32, 1024, 130, 1),      # generic path (group 32)
+    (2, 32, 1024, 130, 1),      # packed path, two (scale, zero) pairs per 64-code unit
     (2, 64, 1536, 77, 2),       # generic path (d not a power of two)
-    (3, 32, 2048, 1408, 2),     # config 5 shape
-    (3, 64, 4096, 300, 1),
-    (4, 64, 4096, 300, 1),
-    (4, 32, 512, 64, 5),
+    (3, 32, 2048, 1408, 2),     # config 5 shape: packed INT3 (96-bit half units), group 32
+    (3, 64, 4096, 300, 1),      # packed INT3
+    (3, 128, 1024, 70, 3),
+    (4, 64, 4096, 300, 1),      # packed INT4
+    (4, 128, 2048, 99, 2),
+    (4, 32, 1024, 65, 2),
+    (4, 32, 512, 64, 5),        # generic path (d = 512)
+    (3, 64, 2560, 41, 1),       # generic path
 ])
 def test_up_gemv_matches_oracle(bits, group, d, f, T):
     G = _gc()
