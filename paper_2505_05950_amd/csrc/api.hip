@@ -109,7 +109,8 @@ bool mask_path_ok(int f) { return mask_words_per_task(f) <= 2048; }
 
 // workspace of the layer: per-task table, counts, mask words, v, idx, partial
 struct LayerWs {
-    size_t table_off, expert_off, weight_off, tau_off, count_off, mask_off, v_off, idx_off, partial_off, total;
+    size_t table_off, expert_off, weight_off, tau_off, count_off, mask_off, groups_off, ngroups_off, v_off, idx_off,
+        partial_off, total;
     int n_tasks, nblk;
 };
 LayerWs layer_ws(const floe_layer* L, int T) {
@@ -124,6 +125,8 @@ LayerWs layer_ws(const floe_layer* L, int T) {
     w.tau_off = o;    o += align_up((size_t)w.n_tasks * 4);
     w.count_off = o;  o += align_up((size_t)w.n_tasks * 4);
     w.mask_off = o;   o += align_up((size_t)w.n_tasks * mask_words_per_task(L->s.f) * 4);
+    w.groups_off = o; o += align_up((size_t)mfma_max_groups(L->n_experts + L->n_shared, w.n_tasks) * sizeof(TokenGroup));
+    w.ngroups_off = o; o += align_up(4);
     w.v_off = o;      o += align_up((size_t)w.n_tasks * L->s.f * 4);
     w.idx_off = o;    o += align_up((size_t)w.n_tasks * L->s.f * 4);
     w.partial_off = o; o += align_up((size_t)w.n_tasks * w.nblk * L->s.d * 4);
@@ -348,7 +351,11 @@ int floe_moe_layer_decode(const floe_layer* L, const floe_half* x, int T, floe_h
     map.task_table = task_table;
     map.slots = slots;
     const bool mask_ok = mask_path_ok(L->s.f);
-    if (mask_ok && route_in_place_ok(L->s.d, L->s.bits, L->s.group, L->n_experts, L->top_k, L->n_shared)) {
+    const bool batch_mfma = T >= 2 && mfma_grouped_shape(L->s.d, L->s.bits, L->s.group) &&
+                            mfma_batch_pays(L->n_experts + L->n_shared, w.n_tasks) &&
+                            aligned(L->experts ? L->experts[0].up_scale : nullptr, 16);
+    if (mask_ok && !batch_mfma &&
+        route_in_place_ok(L->s.d, L->s.bits, L->s.group, L->n_experts, L->top_k, L->n_shared)) {
         // three kernels: [router + up GEMV + mask] -> [compaction + gate/down] -> [combine]
         RouteArgs ro;
         ro.router_cm = reinterpret_cast<const h16*>(L->router_cm);
@@ -376,7 +383,21 @@ int floe_moe_layer_decode(const floe_layer* L, const floe_half* x, int T, floe_h
         ra.task_table = task_table;
         ra.task_expert = task_expert; ra.task_weight = task_weight; ra.task_tau = task_tau;
         FLOE_LAUNCH(FLOE_KERNEL_ROUTER, st, launch_router(ra, T, st));
-        if (mask_ok) {
+        if (mask_ok && batch_mfma) {
+            // decode batch: tokens routed to the same expert share one pass over its codes (matrix cores)
+            TokenGroup* groups = reinterpret_cast<TokenGroup*>(base + w.groups_off);
+            int32_t* n_groups = reinterpret_cast<int32_t*>(base + w.ngroups_off);
+            const int n_all = L->n_experts + L->n_shared;
+            const int chunk = mfma_chunk(n_all, w.n_tasks);
+            FLOE_HIP(launch_group_tokens(task_expert, w.n_tasks, n_all, chunk, groups, n_groups, st));
+            FLOE_LAUNCH(FLOE_KERNEL_UP_GEMV, st,
+                        launch_up_gemv_grouped(static_cast<const DevExpert*>(L->dev_table), groups, n_groups,
+                                               mfma_max_groups(n_all, w.n_tasks), chunk, xh, slots, v, task_tau,
+                                               mask, L->s.d, L->s.f, L->s.bits, L->s.group, st));
+            FLOE_LAUNCH(FLOE_KERNEL_GATE_DOWN, st,
+                        launch_gate_down(map, nullptr, L->s.f, xh, v, mask, nullptr, count, task_weight, partial, L->s.d,
+                                         L->s.f, w.n_tasks, w.nblk, st));
+        } else if (mask_ok) {
             FLOE_LAUNCH(FLOE_KERNEL_UP_GEMV, st,
                         launch_up_gemv(map, xh, nullptr, v, task_tau, mask, L->s.d, L->s.f, L->s.bits, L->s.group,
                                        w.n_tasks, st));

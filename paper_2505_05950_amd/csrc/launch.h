@@ -34,6 +34,29 @@ inline bool route_in_place_ok(int d, int bits, int group, int n_experts, int top
            top_k + n_shared <= 16;
 }
 
+// S2 for decode batches on the matrix cores: tokens routed to the same expert share one pass over its codes.
+struct TokenGroup {
+    int32_t expert;    // index into the layer's expert table
+    int32_t n;         // tasks in this chunk (<= chunk size)
+    int32_t task[16];  // ascending task ids (token * slots + slot)
+};
+inline bool mfma_grouped_shape(int d, int bits, int group) {
+    return ((bits == 2 && group == 64) || (bits == 4 && (group == 32 || group == 64))) &&
+           (d == 1024 || d == 2048 || d == 4096);
+}
+// tasks per group (token rows of the MFMA tile that are used): 8 while experts see few tokens each, else 16
+inline int mfma_chunk(int n_all, int n_tasks) { return n_tasks <= 8 * n_all ? 8 : 16; }
+inline int mfma_max_groups(int n_all, int n_tasks) {
+    return (n_all < n_tasks ? n_all : n_tasks) + n_tasks / mfma_chunk(n_all, n_tasks) + 1;
+}
+// grouping pays once experts see about two tokens each; below that the per-token kernels read the same bytes
+inline bool mfma_batch_pays(int n_all, int n_tasks) { return n_tasks >= 2 * n_all; }
+hipError_t launch_group_tokens(const int32_t* task_expert, int n_tasks, int n_all, int chunk, TokenGroup* groups,
+                               int32_t* n_groups, hipStream_t stream);
+hipError_t launch_up_gemv_grouped(const DevExpert* table, const TokenGroup* groups, const int32_t* n_groups,
+                                  int max_groups, int chunk, const h16* x, int slots, float* v, const float* task_tau,
+                                  uint32_t* mask_words, int d, int f, int bits, int group, hipStream_t stream);
+
 // S3 as a kernel of its own: per task threshold tau[task]
 hipError_t launch_select(const float* v, int f, int n_tasks, const float* tau, int32_t* idx, int32_t* count,
                          hipStream_t stream);

@@ -1,0 +1,490 @@
+// S2 for several tokens at once (decode batches): V = X . W_up^Q with the tokens that were routed to the
+// same expert sharing ONE pass over that expert's codes (Alg. 1 line 2; the paper itself is batch-1, each
+// token keeps its own threshold, mask and result).  Here the contraction is dense and tall-skinny
+// (up to 16 tokens x d) x (d x f), so it goes to the matrix cores:
+//
+//   v_mfma_f32_16x16x32_f16:  C[16 tokens][16 channels] += A[16 tokens][32 k] * B[32 k][16 channels]
+//
+// * B (weights) never becomes a number on the vector ALU.  A lane (channel c = lane % 16, quarter
+//   g = lane / 16) loads the 16 codes of its quarter of a 64-code unit (one dword for INT2, two for INT4).
+//   A code field that sits at bits [p, p+b) of a 16-bit half, ANDed out and left in place, IS the fp16
+//   subnormal q * 2^(p-24) (the matrix cores honour fp16 subnormals), so one AND per register builds
+//   two weights, with no offset to remove afterwards.
+// * A (activations) is prepared once per workgroup in LDS in exactly the slot order the extraction
+//   produces, pre-multiplied by 2^(pmax - p) so that every product carries the same 2^(pmax-24), and by a
+//   per-token power of two that keeps it finite in fp16.
+// * Two MFMAs cover the 64 codes of a unit.  The result tile is scaled per quantization group,
+//   acc += s * (2^k C - z * Xg), with the channel's (s, z) in the lane and the tokens' group sums Xg in
+//   LDS.  A lane ends up holding v for one channel and four tokens; the comparison with each token's
+//   threshold is a wave ballot whose 16-bit pieces are the mask bits the gate/down kernel compacts.
+#include "floe_dev.h"
+#include "launch.h"
+
+namespace floe {
+
+typedef _Float16 h16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int kMfmaThreads = 512;              // 8 waves
+
+// How the 64 codes of a unit are dealt to the four lane quarters g and the two MFMAs j.
+//  kLaneWords           code words a lane loads per unit
+//  word(k, g)           index (inside the unit) of the lane's k-th word
+//  code(j, g, s)        code index (0..63 inside the unit) that slot s of MFMA j holds in quarter g
+//  pos(j, s)            bit position of that code's field inside its 16-bit half
+//  kPmax                every product carries 2^(kPmax - 24)
+// With one quantization group per unit (G32 = false) any dealing works because both MFMAs are summed
+// before scaling; with groups of 32 MFMA j must cover exactly the codes 32j .. 32j+31.
+template <int BITS, bool G32> struct MfmaTraits;
+template <> struct MfmaTraits<2, false> {  // quarter g owns word g (codes 16g .. 16g+15)
+    static constexpr int kLaneWords = 1;
+    static constexpr int kPmax = 8;
+    __device__ static constexpr int word(int k, int g) { (void)k; return g; }
+    __device__ static constexpr int code(int j, int g, int s) {
+        constexpr int t[2][8] = {{0, 8, 1, 9, 2, 10, 3, 11}, {4, 12, 5, 13, 6, 14, 7, 15}};
+        return 16 * g + t[j][s];
+    }
+    __device__ static constexpr int pos(int j, int s) {
+        constexpr int t[2][8] = {{4, 4, 6, 6, 4, 4, 6, 6}, {8, 8, 4, 4, 6, 6, 8, 8}};
+        return t[j][s];
+    }
+};
+template <bool G32> struct MfmaTraits<4, G32> {  // MFMA j reads word 4j + g: it covers codes 32j .. 32j+31
+    static constexpr int kLaneWords = 2;
+    static constexpr int kPmax = 6;
+    __device__ static constexpr int word(int k, int g) { return 4 * k + g; }
+    __device__ static constexpr int code(int j, int g, int s) {
+        constexpr int t[8] = {0, 4, 1, 5, 2, 6, 3, 7};
+        return 32 * j + 8 * g + t[s];
+    }
+    __device__ static constexpr int pos(int j, int s) {
+        constexpr int t[8] = {4, 4, 4, 4, 2, 2, 6, 6};
+        (void)j;
+        return t[s];
+    }
+};
+
+// the 4 registers (8 fp16 subnormals) of MFMA j from the lane's code words
+template <int BITS, bool G32>
+__device__ __forceinline__ void weight_frag(const uint32_t* w, int j, int g, uint32_t (&r)[4]) {
+    if (BITS == 2 && !G32) {
+        const uint32_t W = w[0], a = W << 4, b = W >> 6;
+        if (j == 0) {
+            r[0] = a & 0x00300030u;  // codes (0, 8)  at bits [4,6)
+            r[1] = a & 0x00C000C0u;  // codes (1, 9)  at bits [6,8)
+            r[2] = W & 0x00300030u;  // codes (2, 10) at bits [4,6)
+            r[3] = W & 0x00C000C0u;  // codes (3, 11) at bits [6,8)
+        } else {
+            r[0] = W & 0x03000300u;  // codes (4, 12) at bits [8,10)
+            r[1] = b & 0x00300030u;  // codes (5, 13) at bits [4,6)
+            r[2] = b & 0x00C000C0u;  // codes (6, 14) at bits [6,8)
+            r[3] = b & 0x03000300u;  // codes (7, 15) at bits [8,10)
+        }
+    } else {
+        const uint32_t W = w[j], a = W << 4, b = W >> 6;
+        r[0] = a & 0x00F000F0u;      // codes (0, 4) at bits [4,8)
+        r[1] = W & 0x00F000F0u;      // codes (1, 5) at bits [4,8)
+        r[2] = b & 0x003C003Cu;      // codes (2, 6) at bits [2,6)
+        r[3] = b & 0x03C003C0u;      // codes (3, 7) at bits [6,10)
+    }
+}
+
+__device__ __forceinline__ h16x8 as_h8(const uint32_t (&r)[4]) {
+    uint4 q = make_uint4(r[0], r[1], r[2], r[3]);
+    return __builtin_bit_cast(h16x8, q);
+}
+
+template <int BITS, int UPC, bool G32, int NTPAD, int TILES>
+__global__ __launch_bounds__(kMfmaThreads) void up_gemv_mfma_kernel(const DevExpert* __restrict__ table,
+                                                                     const TokenGroup* __restrict__ groups,
+                                                                     const int32_t* __restrict__ n_groups,
+                                                                     const h16* __restrict__ x, int slots,
+                                                                     float* __restrict__ v,
+                                                                     const float* __restrict__ task_tau,
+                                                                     uint32_t* __restrict__ mask_words, int f) {
+    using Tr = MfmaTraits<BITS, G32>;
+    constexpr int d = UPC * 64;
+    constexpr int LW = Tr::kLaneWords;
+    constexpr int kCw = BITS * 2;               // code words per unit (64 codes)
+    constexpr int LWQ = kCw / 4;                // 128-bit vectors per unit
+    constexpr int GPU_ = G32 ? 2 : 1;           // quantization groups per unit
+    constexpr int kGroupsPerRow = UPC * GPU_;   // scale / zero entries per channel
+    constexpr float kScaleBack = (float)(1 << (24 - Tr::kPmax));
+    extern __shared__ __align__(16) unsigned char lds_raw[];
+    uint4* xfrag = reinterpret_cast<uint4*>(lds_raw);                         // [UPC][2][4][NTPAD]
+    float* xg = reinterpret_cast<float*>(xfrag + (size_t)UPC * 8 * NTPAD);   // [UPC * GPU_][NTPAD]
+    __shared__ float tok_inv_p[16];
+    __shared__ float tok_tau[16];
+    __shared__ int tok_task[16];
+    __shared__ int tok_down[16];
+    __shared__ unsigned tok_amax[16];
+
+    if ((int)blockIdx.y >= n_groups[0]) return;  // the grid is sized for the worst case
+    const TokenGroup* grp = groups + blockIdx.y;  // read in place: indexing a register copy would spill
+    const DevExpert e = table[grp->expert];
+    const int n_tok = grp->n;
+    const int tid = threadIdx.x;
+    const int wave = tid >> 6, lane = tid & 63;
+    const int c = lane & 15, g = lane >> 4;
+
+    FLOE_TL(0);
+    // ---- activations.  One thread per (unit, token) keeps the unit's 64 activations (128 contiguous
+    // bytes) in registers across three steps: (1) the token's largest magnitude, met in LDS with an
+    // integer max on the bit patterns, gives a power of two that keeps 16 * |x'| finite in fp16;
+    // (2) the scaled activations go to LDS as the fragments the MFMAs read: entry (U, j, g, n) holds the
+    // 8 values that meet MFMA j of unit U in lane quarter g for token n, in slot order, each times
+    // 2^(pmax - p); all offsets are compile-time constants; (3) the group sums of x' go beside them.
+    constexpr int kEnt = (UPC * NTPAD + kMfmaThreads - 1) / kMfmaThreads;  // entries per thread
+    if (tid < 16) {
+        tok_amax[tid] = 0u;
+        const bool livetok = tid < n_tok && tid < NTPAD;
+        tok_task[tid] = livetok ? grp->task[tid] : -1;
+        tok_tau[tid] = (livetok && task_tau) ? task_tau[grp->task[tid]] : 0.0f;
+    }
+    __syncthreads();
+    uint4 xq[kEnt][8];
+#pragma unroll
+    for (int en = 0; en < kEnt; ++en) {
+        const int idx = tid + en * kMfmaThreads;
+        const int n = idx % NTPAD, U = idx / NTPAD;
+        float amax = 0.0f;
+        if (idx < UPC * NTPAD && n < n_tok) {
+            const int t = tok_task[n] / slots;
+            const uint4* xr = reinterpret_cast<const uint4*>(x + (size_t)t * d + U * 64);
+#pragma unroll
+            for (int r = 0; r < 8; ++r) xq[en][r] = xr[r];
+#pragma unroll
+            for (int r = 0; r < 8; ++r) {
+                const uint32_t wds[4] = {xq[en][r].x, xq[en][r].y, xq[en][r].z, xq[en][r].w};
+#pragma unroll
+                for (int k = 0; k < 4; ++k) {
+                    const h16x2 p = as_h2(wds[k]);
+                    amax = fmaxf(amax, fmaxf(fabsf((float)p.x), fabsf((float)p.y)));
+                }
+            }
+            atomicMax(&tok_amax[n], __builtin_bit_cast(unsigned, amax));  // non-negative floats order like integers
+        } else {
+#pragma unroll
+            for (int r = 0; r < 8; ++r) xq[en][r] = make_uint4(0u, 0u, 0u, 0u);
+        }
+    }
+    __syncthreads();
+    if (tid < 16) {
+        const float amax = __builtin_bit_cast(float, tok_amax[tid]);
+        const int down = (amax >= 512.0f && amax < 3.0e38f) ? ilogbf(amax) - 8 : 0;  // |x'| < 512
+        tok_down[tid] = down;
+        tok_inv_p[tid] = ldexpf(1.0f, down);
+    }
+    __syncthreads();
+    FLOE_TL(1);
+#pragma unroll
+    for (int en = 0; en < kEnt; ++en) {
+        const int idx = tid + en * kMfmaThreads;
+        if (idx >= UPC * NTPAD) continue;
+        const int n = idx % NTPAD, U = idx / NTPAD;
+        unsigned char* ubase = lds_raw + (size_t)U * (8 * NTPAD * 16) + n * 16;
+        const h16 ps = (h16)ldexpf(1.0f, -tok_down[n]);
+        const h16x2 ps2 = {ps, ps};
+        uint32_t xv[32];  // (x'[2i], x'[2i+1])
+        float gsum[2] = {0.0f, 0.0f};
+        const h16x2 ones = {(h16)1.0f, (h16)1.0f};
+#pragma unroll
+        for (int r = 0; r < 8; ++r) {
+            const uint32_t wds[4] = {xq[en][r].x, xq[en][r].y, xq[en][r].z, xq[en][r].w};
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const h16x2 p = as_h2(wds[k]) * ps2;
+                xv[4 * r + k] = as_u32(p);
+                gsum[G32 ? (r >> 2) : 0] = __builtin_amdgcn_fdot2(p, ones, gsum[G32 ? (r >> 2) : 0], false);
+            }
+        }
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int gq = 0; gq < 4; ++gq)
+#pragma unroll
+                for (int pr = 0; pr < 4; ++pr) {
+                    const int lo = Tr::code(j, gq, 2 * pr), hi = Tr::code(j, gq, 2 * pr + 1);
+                    const uint32_t wl = xv[lo >> 1], wh = xv[hi >> 1];
+                    const uint32_t l16 = (lo & 1) ? (wl >> 16) : (wl & 0xFFFFu);
+                    const uint32_t h16b = (hi & 1) ? (wh & 0xFFFF0000u) : (wh << 16);
+                    const h16x2 mul = {(h16)(float)(1 << (Tr::kPmax - Tr::pos(j, 2 * pr))),
+                                       (h16)(float)(1 << (Tr::kPmax - Tr::pos(j, 2 * pr + 1)))};
+                    const h16x2 val = as_h2(l16 | h16b) * mul;
+                    *reinterpret_cast<uint32_t*>(ubase + ((j * 4 + gq) * NTPAD) * 16 + 4 * pr) = as_u32(val);
+                }
+#pragma unroll
+        for (int q2 = 0; q2 < GPU_; ++q2) xg[(size_t)(U * GPU_ + q2) * NTPAD + n] = gsum[q2];
+    }
+    __syncthreads();
+
+    FLOE_TL(2);
+    // ---- main loop: this wave owns TILES tiles of 16 channels, all UPC units, in blocks of 8 units.
+    // Loads are line-wide: quarter g of a channel's four lanes fetches units 8B+2g and 8B+2g+1 whole
+    // (the four quarters together read contiguous 128 / 256 bytes), and a 4x4 transpose across the lane
+    // quarters (v_permlane32_swap + v_permlane16_swap) hands every quarter ITS word of each unit.
+    // Scales and zeros are fetched the same way (quarter g holds those of block 4Q+g) and passed to the
+    // other quarters with ds_bpermute when their block comes up.
+    const int ch0 = (blockIdx.x * 8 + wave) * (16 * TILES);
+    // uniform base pointers plus 32-bit per-lane byte offsets (f <= 2^20 rows of <= 2 KiB)
+    const char* cbase = reinterpret_cast<const char*>(e.codes);
+    const char* sbase = reinterpret_cast<const char*>(e.scale);
+    const char* zbase = reinterpret_cast<const char*>(e.zero);
+    constexpr int kBlk = 8;                    // units per block
+    constexpr int NB = UPC / kBlk;             // blocks per channel (2, 4 or 8)
+    constexpr int NSB = (NB + 3) / 4;          // super-blocks of 4 blocks (meta registers)
+    constexpr int kRaw = 2 * LWQ;              // uint4 a lane loads per tile per block (its two units)
+    constexpr int kMetaRegs = 4 * GPU_;        // 32-bit registers holding a block's 8 * GPU_ fp16 scales
+    uint32_t coff[TILES], moff[TILES];
+    int chan[TILES];
+#pragma unroll
+    for (int tt = 0; tt < TILES; ++tt) {
+        chan[tt] = ch0 + 16 * tt + c;
+        const uint32_t chl = chan[tt] < f ? chan[tt] : f - 1;  // clamped lanes load valid memory, never store
+        coff[tt] = chl * (UPC * kCw) * 4u + (uint32_t)(2 * g) * (kCw * 4u);
+        moff[tt] = chl * kGroupsPerRow * 2u;
+    }
+    float acc[TILES][4];
+#pragma unroll
+    for (int tt = 0; tt < TILES; ++tt)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) acc[tt][i] = 0.0f;
+
+    // scales / zeros of the whole channel, dealt to the quarters: quarter g keeps block 4Q+g
+    uint32_t ms[TILES][NSB][kMetaRegs], mz[TILES][NSB][kMetaRegs];
+#pragma unroll
+    for (int tt = 0; tt < TILES; ++tt)
+#pragma unroll
+        for (int Q = 0; Q < NSB; ++Q) {
+            const int blk = (4 * Q + g) < NB ? (4 * Q + g) : NB - 1;
+            const uint32_t off = moff[tt] + (uint32_t)(blk * kBlk * GPU_) * 2u;
+#pragma unroll
+            for (int r4 = 0; r4 < GPU_; ++r4) {
+                const uint4 a = *reinterpret_cast<const uint4*>(sbase + off + 16 * r4);
+                const uint4 bq = *reinterpret_cast<const uint4*>(zbase + off + 16 * r4);
+                ms[tt][Q][4 * r4 + 0] = a.x; ms[tt][Q][4 * r4 + 1] = a.y; ms[tt][Q][4 * r4 + 2] = a.z; ms[tt][Q][4 * r4 + 3] = a.w;
+                mz[tt][Q][4 * r4 + 0] = bq.x; mz[tt][Q][4 * r4 + 1] = bq.y; mz[tt][Q][4 * r4 + 2] = bq.z; mz[tt][Q][4 * r4 + 3] = bq.w;
+            }
+        }
+
+    struct Block {
+        uint4 raw[TILES][kRaw];
+    };
+    auto load_block = [&](Block& b, int blk) {
+#pragma unroll
+        for (int tt = 0; tt < TILES; ++tt) {
+            const uint4* p = reinterpret_cast<const uint4*>(cbase + (coff[tt] + (uint32_t)blk * (kBlk * kCw * 4u)));
+#pragma unroll
+            for (int r = 0; r < kRaw; ++r) b.raw[tt][r] = p[r];
+        }
+    };
+    auto transpose4 = [](uint4& q) {  // across the four lane quarters: register k <- word g of quarter k's vector
+        typedef unsigned u32x2 __attribute__((ext_vector_type(2)));
+        u32x2 t;
+        t = __builtin_amdgcn_permlane32_swap(q.x, q.z, false, false); q.x = t.x; q.z = t.y;
+        t = __builtin_amdgcn_permlane32_swap(q.y, q.w, false, false); q.y = t.x; q.w = t.y;
+        t = __builtin_amdgcn_permlane16_swap(q.x, q.y, false, false); q.x = t.x; q.y = t.y;
+        t = __builtin_amdgcn_permlane16_swap(q.z, q.w, false, false); q.z = t.x; q.w = t.y;
+    };
+    auto compute_block = [&](Block& b, int blk) {
+        // meta of this block lives in quarter (blk % 4) of super-block blk / 4
+        const int src_lane4 = (16 * (blk & 3) + c) * 4;
+        uint32_t bs[TILES][kMetaRegs], bz[TILES][kMetaRegs];
+#pragma unroll
+        for (int tt = 0; tt < TILES; ++tt)
+#pragma unroll
+            for (int r = 0; r < kMetaRegs; ++r) {
+                uint32_t sv = ms[tt][0][r], zv = mz[tt][0][r];
+                if (NSB > 1 && blk >= 4) { sv = ms[tt][NSB - 1][r]; zv = mz[tt][NSB - 1][r]; }
+                bs[tt][r] = (uint32_t)__builtin_amdgcn_ds_bpermute(src_lane4, (int)sv);
+                bz[tt][r] = (uint32_t)__builtin_amdgcn_ds_bpermute(src_lane4, (int)zv);
+            }
+#pragma unroll
+        for (int tt = 0; tt < TILES; ++tt)
+#pragma unroll
+            for (int r = 0; r < kRaw; ++r) transpose4(b.raw[tt][r]);
+        // after the transposes: raw[tt][h * LWQ + w4] component k = word (4 * w4 + g) of unit 2k + h
+#pragma unroll
+        for (int uu = 0; uu < kBlk; ++uu) {
+            const int U = blk * kBlk + uu;
+            const int kq = uu >> 1, h = uu & 1;
+            h16x8 xa[2];
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+                // token rows beyond NTPAD repeat earlier ones; their results are never stored
+                const uint4 q = xfrag[((size_t)(U * 2 + j) * 4 + g) * NTPAD + (c & (NTPAD - 1))];
+                xa[j] = __builtin_bit_cast(h16x8, q);
+            }
+            float xgv[GPU_][4];
+#pragma unroll
+            for (int q = 0; q < GPU_; ++q)
+#pragma unroll
+                for (int i = 0; i < 4; ++i) xgv[q][i] = xg[(size_t)(U * GPU_ + q) * NTPAD + ((4 * g + i) & (NTPAD - 1))];
+#pragma unroll
+            for (int tt = 0; tt < TILES; ++tt) {
+                uint32_t w[LW];
+#pragma unroll
+                for (int k = 0; k < LW; ++k) {
+                    const uint4 q = b.raw[tt][h * LWQ + (LWQ == 1 ? 0 : k)];
+                    w[k] = kq == 0 ? q.x : (kq == 1 ? q.y : (kq == 2 ? q.z : q.w));
+                }
+                uint32_t r0[4], r1[4];
+                weight_frag<BITS, G32>(w, 0, g, r0);
+                weight_frag<BITS, G32>(w, 1, g, r1);
+                const f32x4 zero4 = {0.f, 0.f, 0.f, 0.f};
+                auto half_of = [](const uint32_t (&m)[kMetaRegs], int k) -> float {
+                    const h16x2 p = as_h2(m[k >> 1]);
+                    return (k & 1) ? (float)p.y : (float)p.x;
+                };
+                if (G32) {  // each half unit is a quantization group of its own
+                    const f32x4 c0 = __builtin_amdgcn_mfma_f32_16x16x32_f16(xa[0], as_h8(r0), zero4, 0, 0, 0);
+                    const f32x4 c1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(xa[1], as_h8(r1), zero4, 0, 0, 0);
+                    const float s0 = half_of(bs[tt], 2 * uu), z0 = half_of(bz[tt], 2 * uu);
+                    const float s1 = half_of(bs[tt], 2 * uu + 1), z1 = half_of(bz[tt], 2 * uu + 1);
+                    const float a0 = s0 * kScaleBack, a1 = s1 * kScaleBack, b0 = s0 * z0, b1 = s1 * z1;
+#pragma unroll
+                    for (int i = 0; i < 4; ++i)
+                        acc[tt][i] = fmaf(-b1, xgv[GPU_ - 1][i], fmaf(a1, c1[i], fmaf(-b0, xgv[0][i], fmaf(a0, c0[i], acc[tt][i]))));
+                } else {
+                    f32x4 cc = __builtin_amdgcn_mfma_f32_16x16x32_f16(xa[0], as_h8(r0), zero4, 0, 0, 0);
+                    cc = __builtin_amdgcn_mfma_f32_16x16x32_f16(xa[1], as_h8(r1), cc, 0, 0, 0);
+                    const float s = half_of(bs[tt], uu), z = half_of(bz[tt], uu);
+                    const float s16 = s * kScaleBack, sz = s * z;
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) acc[tt][i] = fmaf(-sz, xgv[0][i], fmaf(s16, cc[i], acc[tt][i]));
+                }
+            }
+            __builtin_amdgcn_sched_barrier(0);  // keep the LDS reads of later units from being hoisted up here
+        }
+    };
+
+    static_assert(NB % 2 == 0, "units per channel must be a multiple of 16");
+    FLOE_TL(3);
+    Block b0, b1;
+    load_block(b0, 0);
+    for (int blk = 0; blk < NB; blk += 2) {
+        load_block(b1, blk + 1);
+        compute_block(b0, blk);
+        if (blk + 2 < NB) load_block(b0, blk + 2);
+        compute_block(b1, blk + 1);
+    }
+
+    FLOE_TL(4);
+    // ---- results: lane (c, g) holds channel chan[tt] for tokens 4g .. 4g+3
+    const int nwords = mask_words_per_task(f);
+    uint16_t* mask16 = reinterpret_cast<uint16_t*>(mask_words);
+    const int f_pad = nwords * 32;
+#pragma unroll
+    for (int tt = 0; tt < TILES; ++tt) {
+        const int tile_base = ch0 + 16 * tt;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int n = 4 * g + i;
+            const bool live = n < n_tok;
+            const float val = acc[tt][i] * tok_inv_p[n & 15];
+            const int task = tok_task[n & 15];
+            if (live && chan[tt] < f) v[(size_t)task * f + chan[tt]] = val;
+            const bool keep = live && chan[tt] < f && fabsf(val) > tok_tau[n & 15];
+            const uint64_t m = __ballot(keep);
+            if (mask16 && live && c == 0 && tile_base < f_pad)
+                mask16[(size_t)task * nwords * 2 + (tile_base >> 4)] = (uint16_t)(m >> (16 * g));
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------------
+// Grouping: for every expert the ascending list of tasks (token, slot) routed to it, cut into chunks of
+// `chunk` tasks.  One workgroup; thread e owns expert e.  Deterministic (ascending expert, ascending task).
+// ---------------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(1024) void group_tokens_kernel(const int32_t* __restrict__ task_expert, int n_tasks,
+                                                            int n_all, int chunk, TokenGroup* __restrict__ groups,
+                                                            int32_t* __restrict__ n_groups) {
+    __shared__ int first_group[1024 + 64 + 1];
+    const int tid = threadIdx.x;
+    for (int e = tid; e < n_all; e += blockDim.x) {
+        int cnt = 0;
+        for (int q = 0; q < n_tasks; ++q) cnt += task_expert[q] == e;
+        first_group[e + 1] = (cnt + chunk - 1) / chunk;
+    }
+    __syncthreads();
+    if (tid == 0) {
+        first_group[0] = 0;
+        for (int e = 0; e < n_all; ++e) first_group[e + 1] += first_group[e];
+        n_groups[0] = first_group[n_all];
+    }
+    __syncthreads();
+    for (int e = tid; e < n_all; e += blockDim.x) {
+        int gi = first_group[e], k = 0;
+        for (int q = 0; q < n_tasks; ++q) {
+            if (task_expert[q] != e) continue;
+            if (k == 0) { groups[gi].expert = e; groups[gi].n = 0; }
+            groups[gi].task[k] = q;
+            groups[gi].n = ++k;
+            if (k == chunk) { ++gi; k = 0; }
+        }
+    }
+}
+
+#ifdef FLOE_TIMELINE
+extern "C" int floe_debug_set_timeline_mfma(unsigned long long* p) {
+    return (int)hipMemcpyToSymbol(HIP_SYMBOL(g_timeline), &p, sizeof(p));
+}
+#endif
+
+hipError_t launch_group_tokens(const int32_t* task_expert, int n_tasks, int n_all, int chunk, TokenGroup* groups,
+                               int32_t* n_groups, hipStream_t stream) {
+    group_tokens_kernel<<<dim3(1), dim3(1024), 0, stream>>>(task_expert, n_tasks, n_all, chunk, groups, n_groups);
+    return hipGetLastError();
+}
+
+template <int BITS, int UPC, bool G32, int NTPAD>
+static hipError_t launch_mfma_inst(int max_groups, hipStream_t stream, const DevExpert* table, const TokenGroup* groups,
+                                   const int32_t* n_groups, const h16* x, int slots, float* v, const float* task_tau,
+                                   uint32_t* mask_words, int f) {
+    // channels per wave = 16 * TILES: code blocks are double-buffered and all scales / zeros sit in registers
+    constexpr int TILES = (BITS == 4 && G32) ? 1 : 2;
+    constexpr size_t lds = (size_t)UPC * 8 * NTPAD * 16 + (size_t)UPC * (G32 ? 2 : 1) * NTPAD * 4;
+    static bool attr_set = false;
+    if (!attr_set) {
+        hipError_t rc = hipFuncSetAttribute(reinterpret_cast<const void*>(&up_gemv_mfma_kernel<BITS, UPC, G32, NTPAD, TILES>),
+                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (rc != hipSuccess) return rc;
+        attr_set = true;
+    }
+    const int ch_per_wg = 8 * 16 * TILES;
+    const dim3 grid((f + ch_per_wg - 1) / ch_per_wg, max_groups);
+    up_gemv_mfma_kernel<BITS, UPC, G32, NTPAD, TILES><<<grid, dim3(kMfmaThreads), lds, stream>>>(table, groups, n_groups, x,
+                                                                                                 slots, v, task_tau,
+                                                                                                 mask_words, f);
+    return hipGetLastError();
+}
+
+template <int BITS, int UPC, bool G32>
+static hipError_t launch_mfma_chunk(int chunk, int max_groups, hipStream_t stream, const DevExpert* table,
+                                    const TokenGroup* groups, const int32_t* n_groups, const h16* x, int slots, float* v,
+                                    const float* task_tau, uint32_t* mask_words, int f) {
+    if (chunk <= 8) return launch_mfma_inst<BITS, UPC, G32, 8>(max_groups, stream, table, groups, n_groups, x, slots, v, task_tau, mask_words, f);
+    return launch_mfma_inst<BITS, UPC, G32, 16>(max_groups, stream, table, groups, n_groups, x, slots, v, task_tau, mask_words, f);
+}
+
+template <int BITS, bool G32>
+static hipError_t launch_mfma_upc(int upc, int chunk, int max_groups, hipStream_t stream, const DevExpert* table,
+                                  const TokenGroup* groups, const int32_t* n_groups, const h16* x, int slots, float* v,
+                                  const float* task_tau, uint32_t* mask_words, int f) {
+    if (upc == 64) return launch_mfma_chunk<BITS, 64, G32>(chunk, max_groups, stream, table, groups, n_groups, x, slots, v, task_tau, mask_words, f);
+    if (upc == 32) return launch_mfma_chunk<BITS, 32, G32>(chunk, max_groups, stream, table, groups, n_groups, x, slots, v, task_tau, mask_words, f);
+    return launch_mfma_chunk<BITS, 16, G32>(chunk, max_groups, stream, table, groups, n_groups, x, slots, v, task_tau, mask_words, f);
+}
+
+hipError_t launch_up_gemv_grouped(const DevExpert* table, const TokenGroup* groups, const int32_t* n_groups,
+                                  int max_groups, int chunk, const h16* x, int slots, float* v, const float* task_tau,
+                                  uint32_t* mask_words, int d, int f, int bits, int group, hipStream_t stream) {
+    if (!mfma_grouped_shape(d, bits, group) || max_groups <= 0) return hipErrorInvalidValue;
+    const int upc = d / 64;
+    const bool g32 = group == 32;
+    if (bits == 2) return launch_mfma_upc<2, false>(upc, chunk, max_groups, stream, table, groups, n_groups, x, slots, v, task_tau, mask_words, f);
+    return g32 ? launch_mfma_upc<4, true>(upc, chunk, max_groups, stream, table, groups, n_groups, x, slots, v, task_tau, mask_words, f)
+               : launch_mfma_upc<4, false>(upc, chunk, max_groups, stream, table, groups, n_groups, x, slots, v, task_tau, mask_words, f);
+}
+
+}  // namespace floe
