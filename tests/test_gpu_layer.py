@@ -124,6 +124,10 @@ def test_layer_batches_through_the_matrix_core_gemv():
     _run_layer_case(19, 3, 4096, 530, 4, 64, 2, 0, 2, True, 6, 70)
 
 
+def test_layer_with_more_than_65536_channels():
+    _run_layer_case(20, 3, 512, 66000, 2, 64, 3, 0, 2, True, 2, 97)
+
+
 def test_layer_broadcast_thresholds():
     """tau_stride_t = 0: one constant per expert, as Alg. 1 takes it."""
     import gpu_common as G

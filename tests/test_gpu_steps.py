@@ -208,6 +208,24 @@ def test_expert_ffn_sparse_matches_oracle(d, f, bits, group, T, pcts):
             assert np.all(np.abs(y[t] - y_ref) <= G.Y_BAR * np.abs(y_ref).max() + slack)
 
 
+def test_expert_ffn_with_more_than_65536_channels_uses_the_select_kernel():
+    """Lists longer than 2048 mask words are compacted by the stand-alone select kernel; same results."""
+    G = _gc()
+    import paper_2505_05950_amd as F
+    d, f, bits, group, T = 512, 66000, 2, 64, 2
+    ex_np, ex_dev, x = _expert_case(9, 56, d, f, bits, group, T)
+    v_ref = [O.up_gemv(*ex_np[:3], d, bits, group, x[t]) for t in range(T)]
+    tau = np.array([O.threshold_for_sparsity(v_ref[t], 95) * 1.003 for t in range(T)], np.float32)
+    y = torch.zeros((T, d), dtype=torch.float32, device=G.DEV)
+    y, idx, count = F.floe_expert_ffn_sparse(ex_dev, G.dev(x), G.dev(tau), None, y)
+    torch.cuda.synchronize()
+    y, idx, count = y.cpu().numpy().astype(np.float64), idx.cpu().numpy(), count.cpu().numpy()
+    for t in range(T):
+        got = idx[t, : count[t]]
+        G.check_index_set(got, v_ref[t], float(tau[t]))
+        assert G.rel_err(y[t], O.sparse_ffn(ex_np[3], x[t], v_ref[t], got)[1]) <= G.Y_TIGHT
+
+
 def test_zero_tokens_is_a_no_op():
     G = _gc()
     import paper_2505_05950_amd as F
