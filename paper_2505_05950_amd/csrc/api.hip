@@ -111,25 +111,30 @@ bool mask_path_ok(int f) { return mask_words_per_task(f) <= 2048; }
 struct LayerWs {
     size_t table_off, expert_off, weight_off, tau_off, count_off, mask_off, groups_off, ngroups_off, v_off, idx_off,
         partial_off, total;
-    int n_tasks, nblk;
+    int n_tasks, nblk, nblk_fused;
+    bool fused;
 };
 LayerWs layer_ws(const floe_layer* L, int T) {
     LayerWs w;
     const int slots = L->top_k + L->n_shared;
     w.n_tasks = T * slots;
     w.nblk = gd_blocks(w.n_tasks, L->s.f);
+    w.fused = w.n_tasks <= kFusedMaxTasks &&
+              route_in_place_ok(L->s.d, L->s.bits, L->s.group, L->n_experts, L->top_k, L->n_shared);
+    w.nblk_fused = w.fused ? fused_blocks(L->s.d, L->s.f) : 0;
+    const int nblk_alloc = w.nblk > w.nblk_fused ? w.nblk : w.nblk_fused;
     size_t o = 0;
     w.table_off = o;  o += align_up((size_t)w.n_tasks * sizeof(DevExpert));
     w.expert_off = o; o += align_up((size_t)w.n_tasks * 4);
     w.weight_off = o; o += align_up((size_t)w.n_tasks * 4);
     w.tau_off = o;    o += align_up((size_t)w.n_tasks * 4);
-    w.count_off = o;  o += align_up((size_t)w.n_tasks * 4);
+    w.count_off = o;  o += align_up((size_t)w.n_tasks * (w.nblk_fused > 1 ? w.nblk_fused : 1) * 4);
     w.mask_off = o;   o += align_up((size_t)w.n_tasks * mask_words_per_task(L->s.f) * 4);
     w.groups_off = o; o += align_up((size_t)mfma_max_groups(L->n_experts + L->n_shared, w.n_tasks) * sizeof(TokenGroup));
     w.ngroups_off = o; o += align_up(4);
     w.v_off = o;      o += align_up((size_t)w.n_tasks * L->s.f * 4);
     w.idx_off = o;    o += align_up((size_t)w.n_tasks * L->s.f * 4);
-    w.partial_off = o; o += align_up((size_t)w.n_tasks * w.nblk * L->s.d * 4);
+    w.partial_off = o; o += align_up((size_t)w.n_tasks * nblk_alloc * L->s.d * 4);
     w.total = o;
     return w;
 }
@@ -354,9 +359,24 @@ int floe_moe_layer_decode(const floe_layer* L, const floe_half* x, int T, floe_h
     const bool batch_mfma = T >= 2 && mfma_grouped_shape(L->s.d, L->s.bits, L->s.group) &&
                             mfma_batch_pays(L->n_experts + L->n_shared, w.n_tasks) &&
                             aligned(L->experts ? L->experts[0].up_scale : nullptr, 16);
-    if (mask_ok && !batch_mfma &&
-        route_in_place_ok(L->s.d, L->s.bits, L->s.group, L->n_experts, L->top_k, L->n_shared)) {
-        // three kernels: [router + up GEMV + mask] -> [compaction + gate/down] -> [combine]
+    int nblk = w.nblk, count_parts = 0;
+    if (w.fused && !batch_mfma) {
+        // two kernels: [router + up GEMV + selection + gate/down on the workgroup's own channels] -> [combine]
+        RouteArgs ro;
+        ro.router_cm = reinterpret_cast<const h16*>(L->router_cm);
+        ro.tau = L->tau;
+        ro.tau_stride_t = L->tau_stride_t;
+        ro.n_experts = L->n_experts; ro.top_k = L->top_k; ro.n_shared = L->n_shared; ro.renormalize = L->renormalize;
+        ro.table = static_cast<const DevExpert*>(L->dev_table);
+        ro.task_table = task_table;
+        ro.task_expert = task_expert; ro.task_weight = task_weight; ro.task_tau = task_tau;
+        FLOE_LAUNCH(FLOE_KERNEL_UP_GEMV, st,
+                    launch_fused_layer(map, xh, ro, partial, count, L->s.d, L->s.f, L->s.group, w.n_tasks, st));
+        nblk = w.nblk_fused;
+        count_parts = w.nblk_fused;
+    } else if (mask_ok && !batch_mfma &&
+               route_in_place_ok(L->s.d, L->s.bits, L->s.group, L->n_experts, L->top_k, L->n_shared)) {
+        // larger batches of shapes without a matrix-core path: [router + up GEMV + mask] -> [compaction + gate/down]
         RouteArgs ro;
         ro.router_cm = reinterpret_cast<const h16*>(L->router_cm);
         ro.tau = L->tau;
@@ -414,8 +434,9 @@ int floe_moe_layer_decode(const floe_layer* L, const floe_half* x, int T, floe_h
                                          L->s.f, w.n_tasks, w.nblk, st));
         }
     }
-    FLOE_LAUNCH(FLOE_KERNEL_COMBINE, st, launch_combine(partial, L->s.d, T, slots, w.nblk, nullptr, reinterpret_cast<h16*>(y), st));
-    if (stats) FLOE_HIP(launch_stats(task_expert, count, task_weight, reinterpret_cast<SlotStat*>(stats), w.n_tasks, st));
+    FLOE_LAUNCH(FLOE_KERNEL_COMBINE, st, launch_combine(partial, L->s.d, T, slots, nblk, nullptr, reinterpret_cast<h16*>(y), st));
+    if (stats)
+        FLOE_HIP(launch_stats(task_expert, count, count_parts, task_weight, reinterpret_cast<SlotStat*>(stats), w.n_tasks, st));
     return FLOE_OK;
 }
 
@@ -487,7 +508,7 @@ int floe_moe_layer_decode_offloaded(const floe_layer* L, const floe_offload* o, 
                                  count, task_weight, partial, L->s.d, L->s.f, w.n_tasks, w.nblk, st));
     FLOE_LAUNCH(FLOE_KERNEL_COMBINE, st,
                 launch_combine(partial, L->s.d, T, slots, w.nblk, nullptr, reinterpret_cast<h16*>(y), st));
-    if (stats) FLOE_HIP(launch_stats(task_expert, count, task_weight, reinterpret_cast<SlotStat*>(stats), w.n_tasks, st));
+    if (stats) FLOE_HIP(launch_stats(task_expert, count, 0, task_weight, reinterpret_cast<SlotStat*>(stats), w.n_tasks, st));
     return FLOE_OK;
 }
 

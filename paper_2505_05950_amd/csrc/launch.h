@@ -34,6 +34,14 @@ inline bool route_in_place_ok(int d, int bits, int group, int n_experts, int top
            top_k + n_shared <= 16;
 }
 
+// S1-S5 of a small decode batch in one kernel (shapes of route_in_place_ok): every workgroup routes, computes v
+// for its own block of channels, selects among them and runs gate/down on what it selected.
+// partial[task][fused_blocks][d], wg_count[task][fused_blocks] (selected channels per workgroup).
+int fused_blocks(int d, int f);
+constexpr int kFusedMaxTasks = 16;  // beyond this the partial results outgrow what the fusion saves
+hipError_t launch_fused_layer(const TaskMap& map, const h16* x, const RouteArgs& route, float* partial,
+                              int32_t* wg_count, int d, int f, int group, int n_tasks, hipStream_t stream);
+
 // S2 for decode batches on the matrix cores: tokens routed to the same expert share one pass over its codes.
 struct TokenGroup {
     int32_t expert;    // index into the layer's expert table
@@ -96,8 +104,9 @@ struct SlotStat {
     float weight;
     int32_t pad;
 };
-hipError_t launch_stats(const int32_t* task_expert, const int32_t* count, const float* task_weight, SlotStat* stats,
-                        int n_tasks, hipStream_t stream);
+// count_parts != 0: the count of task q is the sum of count[q * count_parts .. + count_parts)
+hipError_t launch_stats(const int32_t* task_expert, const int32_t* count, int count_parts, const float* task_weight,
+                        SlotStat* stats, int n_tasks, hipStream_t stream);
 
 // S7
 hipError_t launch_stage(const h16* host_gd_dev, int d, int f, const int32_t* idx, const int32_t* count,

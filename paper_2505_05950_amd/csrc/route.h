@@ -46,46 +46,63 @@ __device__ __forceinline__ void route_select(float* prob, int n, int top_k, int 
 
 // The same selection for n <= 16 experts, done by the first 16 lanes of one wave with the logits in
 // registers (no serial LDS round trips).  Every lane of the wave must call it; `logit` is the lane's
-// own logit for lane < n (ignored otherwise).  Results land in sel_id / sel_w (LDS or global) as above.
-// Bit-identical to route_select: same expf, same left-to-right sums, same tie rule.
-__device__ __forceinline__ void route_select_wave16(float logit, int lane, int n, int top_k, int n_shared,
-                                                    int renormalize, int* sel_id, float* sel_w) {
-    if (top_k > 0) {
-        const int l16 = lane & 15;
-        const bool live = l16 < n;
-        const float mx = row16_allreduce_max(live ? logit : -INFINITY);
-        const float p = live ? expf(logit - mx) : 0.0f;
-        // sum in ascending expert order, exactly like the serial loop (lane e of row 0 holds p_e)
-        float sum = 0.0f;
+// own logit for lane < n (ignored otherwise).  Bit-identical to route_select: same expf, same
+// left-to-right sums, same tie rule.  Split in two so that a caller can act on the expert ids (start
+// loading weights) before the divisions that give the routing weights.
+struct Pick16 {
+    float p;    // lane r (< top_k) of every row of 16: unnormalised probability of the r-th pick
+    int id;     // lane r: its expert id
+    float sum;  // softmax denominator (all lanes)
+};
+__device__ __forceinline__ Pick16 route_pick_wave16(float logit, int lane, int n, int top_k) {
+    const int l16 = lane & 15;
+    const bool live = l16 < n;
+    const float mx = row16_allreduce_max(live ? logit : -INFINITY);
+    const float p = live ? expf(logit - mx) : 0.0f;
+    Pick16 out;
+    // sum in ascending expert order, exactly like the serial loop (lane e of row 0 holds p_e)
+    out.sum = 0.0f;
 #pragma unroll
-        for (int e = 0; e < 16; ++e) {
-            const float pe = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, p), e));
-            if (e < n) sum += pe;
-        }
-        float cur = live ? p : -3.0f;
-        float sel = 0.0f;
-        float my_w = 0.0f;
-        int my_id = 0;
-        for (int r = 0; r < top_k; ++r) {
-            // arg-max with ties to the lower id: (value, id) pairs rotate around the row of 16
-            float bv = cur;
-            int bi = l16;
+    for (int e = 0; e < 16; ++e) {
+        const float pe = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, p), e));
+        if (e < n) out.sum += pe;
+    }
+    float cur = live ? p : -3.0f;
+    out.p = 0.0f;
+    out.id = 0;
+    for (int r = 0; r < top_k; ++r) {
+        // arg-max with ties to the lower id: (value, id) pairs rotate around the row of 16
+        float bv = cur;
+        int bi = l16;
 #define FLOE_ARGMAX_STEP(CTRL)                                               \
     {                                                                        \
         const float ov = dpp_movf<CTRL>(bv);                                 \
         const int oi = dpp_movi<CTRL>(bi);                                   \
         if (ov > bv || (ov == bv && oi < bi)) { bv = ov; bi = oi; }          \
     }
-            FLOE_ARGMAX_STEP(0x128) FLOE_ARGMAX_STEP(0x124) FLOE_ARGMAX_STEP(0x122) FLOE_ARGMAX_STEP(0x121)
+        FLOE_ARGMAX_STEP(0x128) FLOE_ARGMAX_STEP(0x124) FLOE_ARGMAX_STEP(0x122) FLOE_ARGMAX_STEP(0x121)
 #undef FLOE_ARGMAX_STEP
-            const float pw = bv / sum;
-            if (l16 == r) { my_w = pw; my_id = bi; }
-            sel += pw;
-            if (l16 == bi) cur = -2.0f;  // taken
-        }
+        if (l16 == r) { out.p = bv; out.id = bi; }
+        if (l16 == bi) cur = -2.0f;  // taken
+    }
+    return out;
+}
+// routing weight of the lane's pick (lane < top_k): p / sum, or that over the sum of the picked ones
+__device__ __forceinline__ float route_weight_wave16(const Pick16& pk, int top_k, int renormalize) {
+    const float pw = pk.p / pk.sum;
+    float sel = 0.0f;
+    for (int r = 0; r < top_k; ++r)
+        sel += __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, pw), r));
+    return renormalize ? pw / sel : pw;
+}
+__device__ __forceinline__ void route_select_wave16(float logit, int lane, int n, int top_k, int n_shared,
+                                                    int renormalize, int* sel_id, float* sel_w) {
+    if (top_k > 0) {
+        const Pick16 pk = route_pick_wave16(logit, lane, n, top_k);
+        const float w = route_weight_wave16(pk, top_k, renormalize);
         if (lane < top_k) {
-            sel_id[lane] = my_id;
-            sel_w[lane] = renormalize ? my_w / sel : my_w;
+            sel_id[lane] = pk.id;
+            sel_w[lane] = w;
         }
     }
     if (lane < n_shared) {

@@ -66,22 +66,29 @@ hipError_t launch_router(const RouterArgs& a, int T, hipStream_t stream) {
     return hipGetLastError();
 }
 
-__global__ void stats_kernel(const int32_t* task_expert, const int32_t* count, const float* task_weight,
-                             SlotStat* stats, int n_tasks) {
+__global__ void stats_kernel(const int32_t* task_expert, const int32_t* count, int count_parts,
+                             const float* task_weight, SlotStat* stats, int n_tasks) {
     const int q = blockIdx.x * blockDim.x + threadIdx.x;
     if (q >= n_tasks) return;
     SlotStat s;
     s.expert = task_expert[q];
-    s.count = count[q];
+    if (count_parts > 0) {
+        int c = 0;
+        for (int b = 0; b < count_parts; ++b) c += count[(size_t)q * count_parts + b];
+        s.count = c;
+    } else {
+        s.count = count[q];
+    }
     s.weight = task_weight[q];
     s.pad = 0;
     stats[q] = s;
 }
 
-hipError_t launch_stats(const int32_t* task_expert, const int32_t* count, const float* task_weight, SlotStat* stats,
-                        int n_tasks, hipStream_t stream) {
+hipError_t launch_stats(const int32_t* task_expert, const int32_t* count, int count_parts, const float* task_weight,
+                        SlotStat* stats, int n_tasks, hipStream_t stream) {
     if (n_tasks == 0) return hipSuccess;
-    stats_kernel<<<dim3((n_tasks + 255) / 256), dim3(256), 0, stream>>>(task_expert, count, task_weight, stats, n_tasks);
+    stats_kernel<<<dim3((n_tasks + 255) / 256), dim3(256), 0, stream>>>(task_expert, count, count_parts, task_weight,
+                                                                        stats, n_tasks);
     return hipGetLastError();
 }
 

@@ -113,22 +113,162 @@ __device__ __forceinline__ void load_unit(const uint32_t* __restrict__ codes, si
     }
 }
 
-template <int BITS, int UPC, bool ROUTED, int kPasses, bool G32>
-__global__ __launch_bounds__(256) void up_gemv_packed_kernel(TaskMap map, const h16* __restrict__ x, RouteArgs ro,
-                                                             float* __restrict__ v,
-                                                             const float* __restrict__ task_tau,
-                                                             uint32_t* __restrict__ mask_words, int f, int gshift) {
+template <int BITS, int UPC, bool G32>
+struct UnitLoad {  // one pass of a lane: the unit's code words and its scale / zero
+    uint32_t cw[PackedTraits<BITS>::kWords];
+    uint32_t s, z;  // one fp16 (groups >= 64) or two (groups of 32)
+    __device__ __forceinline__ void issue(const DevExpert& e, int j, int u, int G, int gshift) {
+        load_unit<BITS>(e.codes, (size_t)j * UPC + u, cw);
+        if (G32) {
+            const size_t mi = (size_t)j * G + 2 * u;  // even index: 4-byte aligned
+            s = *reinterpret_cast<const uint32_t*>(e.scale + mi);
+            z = *reinterpret_cast<const uint32_t*>(e.zero + mi);
+        } else {
+            const size_t mi = (size_t)j * G + ((u * 64) >> gshift);
+            s = *reinterpret_cast<const uint16_t*>(e.scale + mi);
+            z = *reinterpret_cast<const uint16_t*>(e.zero + mi);
+        }
+    }
+};
+
+// ---------------------------------------------------------------------------------------------------
+// S4 + S5 on a workgroup's own channels (fused layer kernel): gathered gate GEMV with SiLU and the
+// product with v (already times the routing weight), then the gathered down GEMV, over the ascending
+// list sel_j[0..n) that the workgroup has just selected.  512 threads.  Per batch of 16 channels every
+// load is issued before anything is used: wave w requests the whole gate columns of channels w and w + 8,
+// every thread its 16-byte piece of the down rows it owns; the gate results meet in LDS, and a thread adds
+// h_c * piece into 8 fp32 accumulators.  With d < 4096 the threads split the rows of a batch between
+// kRg groups, which are summed through LDS at the end.  out: the workgroup's partial y, d floats.
+// ---------------------------------------------------------------------------------------------------
+template <int UPC>
+struct FusedTile {
+    static constexpr int d = 64 * UPC;
+    static constexpr int NV = d / 512;      // uint4 per lane of a gate column
+    static constexpr int VPR = d / 8;       // uint4 per row
+    static constexpr int kRg = 512 / VPR;   // row groups
+    static constexpr int B = 16;            // channels per batch
+    static constexpr int BG = B / 8;        // gate columns per wave
+    static constexpr int RPT = B / kRg;     // down rows per thread
+    static constexpr int kRed = kRg > 1 ? (kRg - 1) * VPR * 8 : 1;
+};
+
+template <int UPC>
+__device__ __forceinline__ void fused_gate_down(const h16* __restrict__ gd, const h16* __restrict__ xt,
+                                                const int* sel_j, const float* sel_h0, int n, float* hl, float* red,
+                                                float* __restrict__ out) {
+    using Tile = FusedTile<UPC>;
+    constexpr int d = Tile::d, NV = Tile::NV, VPR = Tile::VPR, kRg = Tile::kRg, B = Tile::B, BG = Tile::BG,
+                  RPT = Tile::RPT;
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int piece = tid % VPR, rg = tid / VPR;
+    uint4 xr[NV];
+    {
+        const uint4* xp = reinterpret_cast<const uint4*>(xt);
+#pragma unroll
+        for (int r = 0; r < NV; ++r) xr[r] = xp[r * kWave + lane];
+    }
+    float acc[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) acc[i] = 0.0f;
+    for (int b0 = 0; b0 < n; b0 += B) {
+        uint4 gv[BG][NV];
+        uint4 dv[RPT];
+#pragma unroll
+        for (int i = 0; i < BG; ++i) {
+            const int c = b0 + wave + 8 * i;
+            const int j = c < n ? sel_j[c] : -1;
+            const uint4* gp = reinterpret_cast<const uint4*>(gd + (size_t)(j < 0 ? 0 : j) * 2 * d);
+#pragma unroll
+            for (int r = 0; r < NV; ++r) gv[i][r] = j >= 0 ? gp[r * kWave + lane] : make_uint4(0u, 0u, 0u, 0u);
+        }
+#pragma unroll
+        for (int q = 0; q < RPT; ++q) {
+            const int c = b0 + rg + kRg * q;
+            const int j = c < n ? sel_j[c] : -1;
+            const uint4* dp = reinterpret_cast<const uint4*>(gd + (size_t)(j < 0 ? 0 : j) * 2 * d + d);
+            dv[q] = j >= 0 ? dp[piece] : make_uint4(0u, 0u, 0u, 0u);
+        }
+#pragma unroll
+        for (int i = 0; i < BG; ++i) {
+            const int c = b0 + wave + 8 * i;
+            float g = 0.0f;
+#pragma unroll
+            for (int r = 0; r < NV; ++r) {
+                g = dot2(xr[r].x, gv[i][r].x, g);
+                g = dot2(xr[r].y, gv[i][r].y, g);
+                g = dot2(xr[r].z, gv[i][r].z, g);
+                g = dot2(xr[r].w, gv[i][r].w, g);
+            }
+            g = wave_allreduce_sum(g);
+            if (lane == 0) hl[wave + 8 * i] = c < n ? silu(g) * sel_h0[c] : 0.0f;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int q = 0; q < RPT; ++q) {
+            const float h = hl[rg + kRg * q];
+            const uint32_t wds[4] = {dv[q].x, dv[q].y, dv[q].z, dv[q].w};
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const h16x2 pr = as_h2(wds[k]);
+                acc[2 * k + 0] = fmaf(h, (float)pr.x, acc[2 * k + 0]);
+                acc[2 * k + 1] = fmaf(h, (float)pr.y, acc[2 * k + 1]);
+            }
+        }
+        __syncthreads();  // hl is rewritten by the next batch
+    }
+    if (kRg > 1) {
+        if (rg > 0) {
+#pragma unroll
+            for (int i = 0; i < 8; ++i) red[((rg - 1) * VPR + piece) * 8 + i] = acc[i];
+        }
+        __syncthreads();
+        if (rg == 0) {
+#pragma unroll
+            for (int g2 = 1; g2 < kRg; ++g2)
+#pragma unroll
+                for (int i = 0; i < 8; ++i) acc[i] += red[((g2 - 1) * VPR + piece) * 8 + i];
+        }
+    }
+    if (rg == 0) {
+        float4* o4 = reinterpret_cast<float4*>(out + (size_t)piece * 8);
+        o4[0] = make_float4(acc[0], acc[1], acc[2], acc[3]);
+        o4[1] = make_float4(acc[4], acc[5], acc[6], acc[7]);
+    }
+}
+
+// kDepth passes of loads are in flight per wave: the next one is requested as soon as a pass has been consumed,
+// so the arithmetic runs under the stream of loads instead of after it.
+// FUSED (routed, 8 waves): the workgroup goes on with S3-S5 for the channels it has selected itself and writes a
+// partial y (and its count of selected channels); v and the mask never leave the compute unit.  Selection is per
+// channel, so no workgroup needs to know what another one has selected.  TOUCH: one word of every 128-byte line
+// of a selected channel's [gate | down] chunk is requested at once, so that the chunk is on its way into the
+// caches while the codes are still streaming.
+template <int BITS, int UPC, bool ROUTED, int kPasses, bool G32, int NW, int kDepth, bool FUSED = false,
+          bool TOUCH = false>
+__global__ __launch_bounds__(NW * 64) void up_gemv_packed_kernel(TaskMap map, const h16* __restrict__ x, RouteArgs ro,
+                                                                 float* __restrict__ v,
+                                                                 const float* __restrict__ task_tau,
+                                                                 uint32_t* __restrict__ mask_words, int f, int gshift,
+                                                                 float* __restrict__ partial,
+                                                                 int32_t* __restrict__ wg_count) {
+    static_assert(!FUSED || (ROUTED && NW == 8), "the fused variant routes in place and has 8 waves");
     constexpr int CPW = kWave / UPC;  // channels per wave pass
     constexpr int d = UPC * 64;
-    constexpr int kCw = PackedTraits<BITS>::kWords;
-    constexpr int kWords = (kPasses * CPW * 4 + 31) / 32;  // mask words per workgroup
-    static_assert((kPasses * CPW * 4) % 32 == 0, "a workgroup covers whole mask words");
+    constexpr int kCh = NW * kPasses * CPW;  // channels per workgroup
+    constexpr int kWords = (kCh + 31) / 32;
+    static_assert(kCh % 8 == 0, "a workgroup covers whole mask bytes");
+    static_assert(kDepth >= 1 && kDepth <= kPasses, "depth of the load pipeline");
+    constexpr int kParts = NW >= 16 ? 2 : 1;  // pieces a router row is cut into (one wave per piece)
     __shared__ uint32_t mw[kWords];
-    __shared__ float prob[16];
-    __shared__ int sel_id[16];
-    __shared__ float sel_w[16];
+    __shared__ float plog[16 * kParts];
     __shared__ DevExpert tab[32];
     __shared__ float taus[32];
+    __shared__ float vloc[FUSED ? kCh : 1];   // v of the workgroup's channels
+    __shared__ int sel_j[FUSED ? kCh : 1];    // selected channels, ascending
+    __shared__ float sel_h0[FUSED ? kCh : 1]; // their v times the routing weight
+    __shared__ int wprefix[kWords + 1];
+    __shared__ float hl[16];
+    __shared__ float red[FUSED ? FusedTile<UPC>::kRed : 1];
     const int tid = threadIdx.x;
     const int wave = tid >> 6, lane = tid & 63;
     const int sub = lane / UPC, u = lane % UPC;
@@ -140,7 +280,9 @@ __global__ __launch_bounds__(256) void up_gemv_packed_kernel(TaskMap map, const 
 
     DevExpert e;
     float tau = 0.0f;
-    bool want_mask = mask_words != nullptr;
+    float wgt = 1.0f;  // routing weight of this task (fused variant)
+    uint32_t touchv[FUSED && TOUCH ? kPasses : 1][2] = {};
+    bool want_mask = FUSED || mask_words != nullptr;
     uint32_t raw[32];  // this lane's 64 activations
     {
         const uint4* xq = reinterpret_cast<const uint4*>(x + (size_t)t * d + u * 64);
@@ -150,6 +292,7 @@ __global__ __launch_bounds__(256) void up_gemv_packed_kernel(TaskMap map, const 
             raw[4 * r + 0] = q.x; raw[4 * r + 1] = q.y; raw[4 * r + 2] = q.z; raw[4 * r + 3] = q.w;
         }
     }
+    Pick16 pick{};
     if (ROUTED) {
         // ---- S1 in place: every workgroup of the layer computes the same few dot products (n_experts <= 16,
         // the router matrix sits in L2), so no kernel of its own and no global hand-off is needed.
@@ -159,53 +302,55 @@ __global__ __launch_bounds__(256) void up_gemv_packed_kernel(TaskMap map, const 
             tab[tid] = ro.table[tid];
             taus[tid] = ro.tau[(size_t)t * ro.tau_stride_t + tid];
         }
-        // a whole wave per expert, two experts in flight per wave, fully coalesced 16-byte pieces
-        constexpr int NVR = d / 512;
-        uint4 xl[NVR];
-        {
-            const uint4* xp4 = reinterpret_cast<const uint4*>(x + (size_t)t * d);
-#pragma unroll
-            for (int r = 0; r < NVR; ++r) xl[r] = xp4[r * kWave + lane];
-        }
-        for (int e0 = wave * 2; e0 < ro.n_experts; e0 += 8) {
-            uint4 w[2][NVR];
+        // a wave per piece of an expert's row, two pieces in flight per wave, fully coalesced 16-byte loads
+        constexpr int NVR = d / 512 / kParts;
+        const int n_items = ro.n_experts * kParts;
+        const uint4* xp4 = reinterpret_cast<const uint4*>(x + (size_t)t * d);
+        for (int it0 = wave; it0 < n_items; it0 += 2 * NW) {
+            uint4 w[2][NVR], xl[2][NVR];
 #pragma unroll
             for (int q = 0; q < 2; ++q) {
-                const int ex = e0 + q < ro.n_experts ? e0 + q : e0;
+                const int it = it0 + q * NW < n_items ? it0 + q * NW : it0;
+                const int ex = it / kParts, part = it % kParts;
                 const uint4* wq = reinterpret_cast<const uint4*>(ro.router_cm + (size_t)ex * d);
 #pragma unroll
-                for (int r = 0; r < NVR; ++r) w[q][r] = wq[r * kWave + lane];
+                for (int r = 0; r < NVR; ++r) {
+                    w[q][r] = wq[(part * NVR + r) * kWave + lane];
+                    xl[q][r] = xp4[(part * NVR + r) * kWave + lane];
+                }
             }
 #pragma unroll
             for (int q = 0; q < 2; ++q) {
                 float acc = 0.0f;
 #pragma unroll
                 for (int r = 0; r < NVR; ++r) {
-                    acc = dot2(xl[r].x, w[q][r].x, acc);
-                    acc = dot2(xl[r].y, w[q][r].y, acc);
-                    acc = dot2(xl[r].z, w[q][r].z, acc);
-                    acc = dot2(xl[r].w, w[q][r].w, acc);
+                    acc = dot2(xl[q][r].x, w[q][r].x, acc);
+                    acc = dot2(xl[q][r].y, w[q][r].y, acc);
+                    acc = dot2(xl[q][r].z, w[q][r].z, acc);
+                    acc = dot2(xl[q][r].w, w[q][r].w, acc);
                 }
                 acc = group_reduce_sum_to_last<64>(acc);
-                if (lane == kWave - 1 && e0 + q < ro.n_experts) prob[e0 + q] = acc;
+                if (lane == kWave - 1 && it0 + q * NW < n_items) plog[it0 + q * NW] = acc;
             }
         }
         FLOE_TL(1);
         __syncthreads();
-        if (wave == 0)
-            route_select_wave16(prob[lane & 15], lane, ro.n_experts, ro.top_k, ro.n_shared, ro.renormalize, sel_id, sel_w);
-        __syncthreads();
-        FLOE_TL(2);
+        // every wave picks the experts for itself from the logits in LDS: no second barrier, and only the ids
+        // (not yet the weights) stand between the logits and the first request for codes
+        float lg = 0.0f;
+        if ((lane & 15) < ro.n_experts) {
+#pragma unroll
+            for (int q = 0; q < kParts; ++q) lg += plog[(lane & 15) * kParts + q];
+        }
         const int slot = task - t * map.slots;
-        const int ex = sel_id[slot];
+        int ex = ro.n_experts + (slot - ro.top_k);  // a shared expert
+        if (ro.top_k > 0) {
+            pick = route_pick_wave16(lg, lane, ro.n_experts, ro.top_k);
+            if (slot < ro.top_k) ex = __builtin_amdgcn_readlane(pick.id, slot);
+        }
+        FLOE_TL(2);
         e = tab[ex];
         tau = taus[ex];
-        if (blockIdx.x == 0 && tid == 0) {
-            ro.task_table[task] = e;
-            ro.task_expert[task] = ex;
-            ro.task_weight[task] = sel_w[slot];
-            ro.task_tau[task] = tau;
-        }
     } else {
         e = task_expert_of(map, task);
         want_mask = want_mask && task_tau != nullptr;
@@ -213,23 +358,29 @@ __global__ __launch_bounds__(256) void up_gemv_packed_kernel(TaskMap map, const 
     }
 
     FLOE_TL(3);
-    // ---- issue the weight loads: kPasses passes of CPW channels per wave
-    const int jw = (blockIdx.x * 4 + wave) * (kPasses * CPW);
-    uint32_t cw[kPasses][kCw];
-    uint32_t meta_s[kPasses], meta_z[kPasses];  // one fp16 (groups >= 64) or two (groups of 32) per unit
+    // ---- request the first kDepth passes (a pass = CPW channels per wave)
+    const int jw = (blockIdx.x * NW + wave) * (kPasses * CPW);
+    UnitLoad<BITS, UPC, G32> ld[kDepth];
+    auto channel_of = [&](int p) {
+        const int j = jw + p * CPW + sub;
+        return j < f ? j : f - 1;  // keep the address in bounds; the result of a clamped lane is not stored
+    };
 #pragma unroll
-    for (int p = 0; p < kPasses; ++p) {
-        int j = jw + p * CPW + sub;
-        j = j < f ? j : f - 1;  // keep the address in bounds; the result of a clamped lane is not stored
-        load_unit<BITS>(e.codes, (size_t)j * UPC + u, cw[p]);
-        if (G32) {
-            const size_t mi = (size_t)j * G + 2 * u;  // even index: 4-byte aligned
-            meta_s[p] = *reinterpret_cast<const uint32_t*>(e.scale + mi);
-            meta_z[p] = *reinterpret_cast<const uint32_t*>(e.zero + mi);
-        } else {
-            const size_t mi = (size_t)j * G + ((u * 64) >> gshift);
-            meta_s[p] = *reinterpret_cast<const uint16_t*>(e.scale + mi);
-            meta_z[p] = *reinterpret_cast<const uint16_t*>(e.zero + mi);
+    for (int p = 0; p < kDepth; ++p) ld[p].issue(e, channel_of(p), u, G, gshift);
+    FLOE_TL(7);
+
+    if (ROUTED && (FUSED || (blockIdx.x == 0 && wave == 0))) {
+        const int slot = task - t * map.slots;
+        if (ro.top_k > 0) {
+            const float wl = route_weight_wave16(pick, ro.top_k, ro.renormalize);
+            if (slot < ro.top_k) wgt = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, wl), slot));
+        }
+        if (blockIdx.x == 0 && tid == 0) {  // the task's routing record, for the kernels that follow
+            const int ex = slot < ro.top_k ? __builtin_amdgcn_readlane(pick.id, slot) : ro.n_experts + (slot - ro.top_k);
+            ro.task_table[task] = e;
+            ro.task_expert[task] = ex;
+            ro.task_weight[task] = wgt;
+            ro.task_tau[task] = tau;
         }
     }
 
@@ -243,38 +394,93 @@ __global__ __launch_bounds__(256) void up_gemv_packed_kernel(TaskMap map, const 
     unit_prepare<BITS>(raw, down, xs, Xoff, Xg);
     uint32_t magic = 0x3C003C00u;
     asm volatile("" : "+v"(magic));  // keep it in a VGPR: v_and_or_b32 takes one scalar operand only
-    __syncthreads();                 // mw zeroed
+    FLOE_TL(8);
+    if (!ROUTED) __syncthreads();  // mw zeroed (the routed path has passed a barrier already)
     FLOE_TL(4);
 
 #pragma unroll
     for (int p = 0; p < kPasses; ++p) {
         const int j = jw + p * CPW + sub;
-        const float dot0 = half_unit_dot<BITS>(cw[p], xs, 0, magic);
-        const float dot1 = half_unit_dot<BITS>(cw[p], xs, 1, magic);
+        UnitLoad<BITS, UPC, G32>& L = ld[p % kDepth];
+        const float dot0 = half_unit_dot<BITS>(L.cw, xs, 0, magic);
+        const float dot1 = half_unit_dot<BITS>(L.cw, xs, 1, magic);
         float part;
         if (G32) {
-            const h16x2 s2 = as_h2(meta_s[p]), z2 = as_h2(meta_z[p]);
+            const h16x2 s2 = as_h2(L.s), z2 = as_h2(L.z);
             part = (float)s2.x * fmaf(-(float)z2.x, Xg[0], dot0 - Xoff[0]) +
                    (float)s2.y * fmaf(-(float)z2.y, Xg[1], dot1 - Xoff[1]);
         } else {
-            const float s = (float)as_h2(meta_s[p]).x, z = (float)as_h2(meta_z[p]).x;
+            const float s = (float)as_h2(L.s).x, z = (float)as_h2(L.z).x;
             part = s * fmaf(-z, Xg[0] + Xg[1], (dot0 + dot1) - (Xoff[0] + Xoff[1]));
         }
+        if (p + kDepth < kPasses) L.issue(e, channel_of(p + kDepth), u, G, gshift);
         part = group_reduce_sum_to_last<UPC>(part) * inv_p;
         if (p == 0) FLOE_TL(5);
+        const bool hit = u == UPC - 1 && j < f && want_mask && fabsf(part) > tau;
         if (u == UPC - 1 && j < f) {
-            v[(size_t)task * f + j] = part;
-            if (want_mask && fabsf(part) > tau) {
-                const int local = j - blockIdx.x * (4 * kPasses * CPW);
-                atomicOr(&mw[local >> 5], 1u << (local & 31));
+            const int local = j - blockIdx.x * kCh;
+            if (FUSED) vloc[local] = part;
+            else v[(size_t)task * f + j] = part;
+            if (hit) atomicOr(&mw[local >> 5], 1u << (local & 31));
+        }
+        if (FUSED && TOUCH && UPC == 64) {
+            // one channel per wave and pass: the branch is wave-uniform.  The words are not looked at before the
+            // end of the loop, so the wave does not wait for them here.
+            if (__ballot(hit)) {
+                const uint32_t* row = reinterpret_cast<const uint32_t*>(e.gd + (size_t)(jw + p) * 2 * d);
+                touchv[p][0] = row[lane * 32];
+                touchv[p][1] = row[(lane + 64) * 32];
             }
         }
+        __builtin_amdgcn_sched_barrier(0);  // keep the request for pass p + kDepth where it is
     }
     FLOE_TL(6);
-    if (want_mask) {
+    if (FUSED) {
+        // ---- S3 for the workgroup's own channels: ascending list out of the mask bits in LDS
         __syncthreads();
-        const int word = blockIdx.x * kWords + tid;
-        if (tid < kWords && word < mask_words_per_task(f)) mask_words[(size_t)task * mask_words_per_task(f) + word] = mw[tid];
+        if (tid == 0) {
+            int run = 0;
+#pragma unroll
+            for (int w = 0; w < kWords; ++w) {
+                wprefix[w] = run;
+                run += __popc(mw[w]);
+            }
+            wprefix[kWords] = run;
+            wg_count[(size_t)task * gridDim.x + blockIdx.x] = run;
+        }
+        __syncthreads();
+        if (tid < kCh) {
+            const uint32_t word = mw[tid >> 5];
+            if ((word >> (tid & 31)) & 1u) {
+                const int pos = wprefix[tid >> 5] + __popc(word & ((1u << (tid & 31)) - 1u));
+                sel_j[pos] = blockIdx.x * kCh + tid;
+                sel_h0[pos] = vloc[tid] * wgt;
+            }
+        }
+        const int n = wprefix[kWords];
+        __syncthreads();
+        if (TOUCH) {
+            uint32_t touch = 0u;
+#pragma unroll
+            for (int p = 0; p < (FUSED && TOUCH ? kPasses : 1); ++p) touch ^= touchv[p][0] ^ touchv[p][1];
+            if (touch == 0x9E3779B9u && f < 0) sel_h0[0] = 0.0f;  // never true: keeps the early requests alive
+        }
+        fused_gate_down<UPC>(e.gd, x + (size_t)t * d, sel_j, sel_h0, n, hl, red,
+                             partial + ((size_t)task * gridDim.x + blockIdx.x) * d);
+        FLOE_TL(9);
+    } else if (want_mask) {
+        // the workgroup's channels start on a byte of the task's mask; the last workgroup also clears what is
+        // left of the last word, so that every byte of the mask is written by exactly one workgroup
+        __syncthreads();
+        const int n_bytes = mask_words_per_task(f) * 4;
+        uint8_t* mb = reinterpret_cast<uint8_t*>(mask_words + (size_t)task * mask_words_per_task(f));
+        const int b = blockIdx.x * (kCh / 8) + tid;
+        const bool last = blockIdx.x == gridDim.x - 1;
+        if (tid < kCh / 8) {
+            if (b < n_bytes) mb[b] = reinterpret_cast<const uint8_t*>(mw)[tid];
+        } else if (last && tid < kCh / 8 + 4 && b < n_bytes) {
+            mb[b] = 0;
+        }
     }
 }
 
@@ -290,23 +496,33 @@ static int ilog2_exact(int g) {
     return s;
 }
 
-constexpr int kPassesPlain = 8, kPassesRouted = 16;
+// Launch shapes.  Plain: 4 waves x 8 passes.  Routed (the T-small layer path): 16 waves x 7 passes, which at
+// d = 4096, f = 14336 and two tasks is exactly one workgroup per compute unit (2 x 128 workgroups of 112 channels).
+constexpr int kPassesPlain = 8, kWavesPlain = 4;
+#ifndef FLOE_RW
+#define FLOE_RW 8
+#define FLOE_RP 14
+#define FLOE_RD 6
+#endif
+constexpr int kPassesRouted = FLOE_RP, kWavesRouted = FLOE_RW, kDepthRouted = FLOE_RD;
+constexpr int kDepthPlain = 4;
 
 template <int BITS, int UPC>
 static void launch_packed(bool routed, bool g32, int f, int n_tasks, hipStream_t stream, const TaskMap& map,
                           const h16* x, const RouteArgs& ro, float* v, const float* task_tau, uint32_t* mask_words,
                           int gshift) {
-    const dim3 block(256);
+    const int waves = routed ? kWavesRouted : kWavesPlain;
     const int passes = routed ? kPassesRouted : kPassesPlain;
-    const int ch_per_wg = 4 * passes * (64 / UPC);
+    const dim3 block(waves * 64);
+    const int ch_per_wg = waves * passes * (64 / UPC);
     const dim3 grid((f + ch_per_wg - 1) / ch_per_wg, n_tasks);
     if (routed) {
         if (BITS == 2 && !g32)
-            up_gemv_packed_kernel<2, UPC, true, kPassesRouted, false><<<grid, block, 0, stream>>>(map, x, ro, v, task_tau, mask_words, f, gshift);
+            up_gemv_packed_kernel<2, UPC, true, kPassesRouted, false, kWavesRouted, kDepthRouted><<<grid, block, 0, stream>>>(map, x, ro, v, task_tau, mask_words, f, gshift, nullptr, nullptr);
     } else if (g32) {
-        up_gemv_packed_kernel<BITS, UPC, false, kPassesPlain, true><<<grid, block, 0, stream>>>(map, x, ro, v, task_tau, mask_words, f, gshift);
+        up_gemv_packed_kernel<BITS, UPC, false, kPassesPlain, true, kWavesPlain, kDepthPlain><<<grid, block, 0, stream>>>(map, x, ro, v, task_tau, mask_words, f, gshift, nullptr, nullptr);
     } else {
-        up_gemv_packed_kernel<BITS, UPC, false, kPassesPlain, false><<<grid, block, 0, stream>>>(map, x, ro, v, task_tau, mask_words, f, gshift);
+        up_gemv_packed_kernel<BITS, UPC, false, kPassesPlain, false, kWavesPlain, kDepthPlain><<<grid, block, 0, stream>>>(map, x, ro, v, task_tau, mask_words, f, gshift, nullptr, nullptr);
     }
 }
 
@@ -317,6 +533,35 @@ static void launch_packed_upc(int upc, bool routed, bool g32, int f, int n_tasks
     if (upc == 64) launch_packed<BITS, 64>(routed, g32, f, n_tasks, stream, map, x, ro, v, task_tau, mask_words, gshift);
     else if (upc == 32) launch_packed<BITS, 32>(routed, g32, f, n_tasks, stream, map, x, ro, v, task_tau, mask_words, gshift);
     else launch_packed<BITS, 16>(routed, g32, f, n_tasks, stream, map, x, ro, v, task_tau, mask_words, gshift);
+}
+
+// S1-S5 of the small-batch layer path in one kernel (INT2, group >= 64, <= 16 experts): grid (fused_blocks, n_tasks)
+#ifndef FLOE_FUSED_TOUCH
+#define FLOE_FUSED_TOUCH true
+#endif
+int fused_blocks(int d, int f) {
+    const int ch = kWavesRouted * kPassesRouted * (64 / (d / 64));
+    return (f + ch - 1) / ch;
+}
+template <int UPC>
+static void launch_fused_upc(const TaskMap& map, const h16* x, const RouteArgs& ro, float* partial, int32_t* wg_count,
+                             int f, int gshift, int n_tasks, hipStream_t stream) {
+    static_assert(kWavesRouted == 8, "fused variant");
+    const dim3 grid(fused_blocks(UPC * 64, f), n_tasks), block(kWavesRouted * 64);
+    up_gemv_packed_kernel<2, UPC, true, kPassesRouted, false, kWavesRouted, kDepthRouted, true, FLOE_FUSED_TOUCH>
+        <<<grid, block, 0, stream>>>(map, x, ro, nullptr, nullptr, nullptr, f, gshift, partial, wg_count);
+}
+hipError_t launch_fused_layer(const TaskMap& map, const h16* x, const RouteArgs& route, float* partial,
+                              int32_t* wg_count, int d, int f, int group, int n_tasks, hipStream_t stream) {
+    if (f == 0 || n_tasks == 0) return hipSuccess;
+    const int gshift = ilog2_exact(group);
+    switch (d) {
+        case 4096: launch_fused_upc<64>(map, x, route, partial, wg_count, f, gshift, n_tasks, stream); break;
+        case 2048: launch_fused_upc<32>(map, x, route, partial, wg_count, f, gshift, n_tasks, stream); break;
+        case 1024: launch_fused_upc<16>(map, x, route, partial, wg_count, f, gshift, n_tasks, stream); break;
+        default: return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
 }
 
 hipError_t launch_up_gemv(const TaskMap& map, const h16* x, const RouteArgs* route, float* v, const float* task_tau,
