@@ -113,16 +113,17 @@ __device__ __forceinline__ float wave_allreduce_max_nonneg(float x) {
 // constant 100 MHz clock into g_timeline[wg * 16 + slot].  Compiled out of the product library.
 #ifdef FLOE_TIMELINE
 static __device__ unsigned long long* g_timeline = nullptr;  // one copy per translation unit
-#define FLOE_TL(slot)                                                                                      \
+#define FLOE_TL_AT(slot, thread)                                                                           \
     do {                                                                                                   \
-        if (g_timeline && threadIdx.x == 0)                                                                \
+        if (g_timeline && threadIdx.x == (thread))                                                         \
             g_timeline[((size_t)blockIdx.y * gridDim.x + blockIdx.x) * 16 + (slot)] = wall_clock64();      \
     } while (0)
 #else
-#define FLOE_TL(slot) \
-    do {              \
+#define FLOE_TL_AT(slot, thread) \
+    do {                         \
     } while (0)
 #endif
+#define FLOE_TL(slot) FLOE_TL_AT(slot, 0)
 
 __device__ __forceinline__ float silu(float g) { return g / (1.0f + __expf(-g)); }
 

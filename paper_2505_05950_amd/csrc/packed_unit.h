@@ -1,0 +1,61 @@
+// Pieces shared by the kernels that stream packed codes (up_gemv.hip, fused_layer.hip): a lane's load of one
+// 64-code unit with its scale / zero, and the value of a channel from it.
+#pragma once
+
+#include "floe_dev.h"
+#include "xprep.h"
+
+namespace floe {
+
+template <int BITS>
+__device__ __forceinline__ void load_unit(const uint32_t* __restrict__ codes, size_t unit_index, uint32_t* cw) {
+    constexpr int W = PackedTraits<BITS>::kWords;
+    const uint32_t* p = codes + unit_index * W;
+    if (BITS == 2) {
+        const uint4 q = *reinterpret_cast<const uint4*>(p);
+        cw[0] = q.x; cw[1] = q.y; cw[2] = q.z; cw[3] = q.w;
+    } else if (BITS == 4) {
+        const uint4 q0 = reinterpret_cast<const uint4*>(p)[0], q1 = reinterpret_cast<const uint4*>(p)[1];
+        cw[0] = q0.x; cw[1] = q0.y; cw[2] = q0.z; cw[3] = q0.w;
+        cw[4] = q1.x; cw[5] = q1.y; cw[6] = q1.z; cw[7] = q1.w;
+    } else {  // 24 bytes, 8-byte aligned
+        const uint2 q0 = reinterpret_cast<const uint2*>(p)[0], q1 = reinterpret_cast<const uint2*>(p)[1],
+                    q2 = reinterpret_cast<const uint2*>(p)[2];
+        cw[0] = q0.x; cw[1] = q0.y; cw[2] = q1.x; cw[3] = q1.y; cw[4] = q2.x; cw[5] = q2.y;
+    }
+}
+
+template <int BITS, int UPC, bool G32>
+struct UnitLoad {  // one pass of a lane: the unit's code words and its scale / zero
+    uint32_t cw[PackedTraits<BITS>::kWords];
+    uint32_t s, z;  // one fp16 (groups >= 64) or two (groups of 32)
+    __device__ __forceinline__ void issue(const DevExpert& e, int j, int u, int G, int gshift) {
+        load_unit<BITS>(e.codes, (size_t)j * UPC + u, cw);
+        if (G32) {
+            const size_t mi = (size_t)j * G + 2 * u;  // even index: 4-byte aligned
+            s = *reinterpret_cast<const uint32_t*>(e.scale + mi);
+            z = *reinterpret_cast<const uint32_t*>(e.zero + mi);
+        } else {
+            const size_t mi = (size_t)j * G + ((u * 64) >> gshift);
+            s = *reinterpret_cast<const uint16_t*>(e.scale + mi);
+            z = *reinterpret_cast<const uint16_t*>(e.zero + mi);
+        }
+    }
+};
+
+
+// s * (sum x'q - Xoff - z * Xg) of a lane's unit: the lane's share of v_j (before the sum over the channel's lanes)
+template <int BITS, int UPC, bool G32>
+__device__ __forceinline__ float unit_value(const UnitLoad<BITS, UPC, G32>& L, const uint32_t (&xs)[32],
+                                            const float (&Xoff)[2], const float (&Xg)[2], uint32_t magic) {
+    const float dot0 = half_unit_dot<BITS>(L.cw, xs, 0, magic);
+    const float dot1 = half_unit_dot<BITS>(L.cw, xs, 1, magic);
+    if (G32) {
+        const h16x2 s2 = as_h2(L.s), z2 = as_h2(L.z);
+        return (float)s2.x * fmaf(-(float)z2.x, Xg[0], dot0 - Xoff[0]) + (float)s2.y * fmaf(-(float)z2.y, Xg[1], dot1 - Xoff[1]);
+    }
+    const float sc = (float)as_h2(L.s).x, z = (float)as_h2(L.z).x;
+    return sc * fmaf(-z, Xg[0] + Xg[1], (dot0 + dot1) - (Xoff[0] + Xoff[1]));
+}
+
+}  // namespace floe

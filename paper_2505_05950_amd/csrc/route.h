@@ -124,4 +124,42 @@ struct RouteArgs {
     float* task_tau;          // [n_tasks] out
 };
 
+// Router logits of one token by a workgroup of NW waves, for kernels that route in place: a wave per piece of an
+// expert's row (kParts pieces per row), two pieces in flight per wave, fully coalesced 16-byte loads.
+// plog[e * kParts + part] receives the partial dot product; the caller sums the parts after a barrier.
+template <int D, int NW, int kParts>
+__device__ __forceinline__ void route_logits_to_lds(const h16* __restrict__ xt, const RouteArgs& ro, int wave, int lane,
+                                                    float* plog) {
+    constexpr int NVR = D / 512 / kParts;
+    const int n_items = ro.n_experts * kParts;
+    const uint4* xp4 = reinterpret_cast<const uint4*>(xt);
+    for (int it0 = wave; it0 < n_items; it0 += 2 * NW) {
+        uint4 w[2][NVR], xl[2][NVR];
+#pragma unroll
+        for (int q = 0; q < 2; ++q) {
+            const int it = it0 + q * NW < n_items ? it0 + q * NW : it0;
+            const int ex = it / kParts, part = it % kParts;
+            const uint4* wq = reinterpret_cast<const uint4*>(ro.router_cm + (size_t)ex * D);
+#pragma unroll
+            for (int r = 0; r < NVR; ++r) {
+                w[q][r] = wq[(part * NVR + r) * kWave + lane];
+                xl[q][r] = xp4[(part * NVR + r) * kWave + lane];
+            }
+        }
+#pragma unroll
+        for (int q = 0; q < 2; ++q) {
+            float acc = 0.0f;
+#pragma unroll
+            for (int r = 0; r < NVR; ++r) {
+                acc = dot2(xl[q][r].x, w[q][r].x, acc);
+                acc = dot2(xl[q][r].y, w[q][r].y, acc);
+                acc = dot2(xl[q][r].z, w[q][r].z, acc);
+                acc = dot2(xl[q][r].w, w[q][r].w, acc);
+            }
+            acc = group_reduce_sum_to_last<64>(acc);
+            if (lane == kWave - 1 && it0 + q * NW < n_items) plog[it0 + q * NW] = acc;
+        }
+    }
+}
+
 }  // namespace floe

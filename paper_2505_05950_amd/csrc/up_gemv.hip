@@ -5,6 +5,7 @@
 // so the per-weight work is "extract the code, multiply-accumulate with x".
 #include "floe_dev.h"
 #include "launch.h"
+#include "packed_unit.h"
 #include "route.h"
 #include "xprep.h"
 
@@ -95,163 +96,14 @@ __global__ __launch_bounds__(256) void up_gemv_generic_kernel(TaskMap map, const
 // All weight loads of the kPasses passes are issued before the first one is used.
 // ROUTED (INT2 layer path, <= 16 experts): the workgroup first computes the router itself.
 // ---------------------------------------------------------------------------------------------------
-template <int BITS>
-__device__ __forceinline__ void load_unit(const uint32_t* __restrict__ codes, size_t unit_index, uint32_t* cw) {
-    constexpr int W = PackedTraits<BITS>::kWords;
-    const uint32_t* p = codes + unit_index * W;
-    if (BITS == 2) {
-        const uint4 q = *reinterpret_cast<const uint4*>(p);
-        cw[0] = q.x; cw[1] = q.y; cw[2] = q.z; cw[3] = q.w;
-    } else if (BITS == 4) {
-        const uint4 q0 = reinterpret_cast<const uint4*>(p)[0], q1 = reinterpret_cast<const uint4*>(p)[1];
-        cw[0] = q0.x; cw[1] = q0.y; cw[2] = q0.z; cw[3] = q0.w;
-        cw[4] = q1.x; cw[5] = q1.y; cw[6] = q1.z; cw[7] = q1.w;
-    } else {  // 24 bytes, 8-byte aligned
-        const uint2 q0 = reinterpret_cast<const uint2*>(p)[0], q1 = reinterpret_cast<const uint2*>(p)[1],
-                    q2 = reinterpret_cast<const uint2*>(p)[2];
-        cw[0] = q0.x; cw[1] = q0.y; cw[2] = q1.x; cw[3] = q1.y; cw[4] = q2.x; cw[5] = q2.y;
-    }
-}
-
-template <int BITS, int UPC, bool G32>
-struct UnitLoad {  // one pass of a lane: the unit's code words and its scale / zero
-    uint32_t cw[PackedTraits<BITS>::kWords];
-    uint32_t s, z;  // one fp16 (groups >= 64) or two (groups of 32)
-    __device__ __forceinline__ void issue(const DevExpert& e, int j, int u, int G, int gshift) {
-        load_unit<BITS>(e.codes, (size_t)j * UPC + u, cw);
-        if (G32) {
-            const size_t mi = (size_t)j * G + 2 * u;  // even index: 4-byte aligned
-            s = *reinterpret_cast<const uint32_t*>(e.scale + mi);
-            z = *reinterpret_cast<const uint32_t*>(e.zero + mi);
-        } else {
-            const size_t mi = (size_t)j * G + ((u * 64) >> gshift);
-            s = *reinterpret_cast<const uint16_t*>(e.scale + mi);
-            z = *reinterpret_cast<const uint16_t*>(e.zero + mi);
-        }
-    }
-};
-
-// ---------------------------------------------------------------------------------------------------
-// S4 + S5 on a workgroup's own channels (fused layer kernel): gathered gate GEMV with SiLU and the
-// product with v (already times the routing weight), then the gathered down GEMV, over the ascending
-// list sel_j[0..n) that the workgroup has just selected.  512 threads.  Per batch of 16 channels every
-// load is issued before anything is used: wave w requests the whole gate columns of channels w and w + 8,
-// every thread its 16-byte piece of the down rows it owns; the gate results meet in LDS, and a thread adds
-// h_c * piece into 8 fp32 accumulators.  With d < 4096 the threads split the rows of a batch between
-// kRg groups, which are summed through LDS at the end.  out: the workgroup's partial y, d floats.
-// ---------------------------------------------------------------------------------------------------
-template <int UPC>
-struct FusedTile {
-    static constexpr int d = 64 * UPC;
-    static constexpr int NV = d / 512;      // uint4 per lane of a gate column
-    static constexpr int VPR = d / 8;       // uint4 per row
-    static constexpr int kRg = 512 / VPR;   // row groups
-    static constexpr int B = 16;            // channels per batch
-    static constexpr int BG = B / 8;        // gate columns per wave
-    static constexpr int RPT = B / kRg;     // down rows per thread
-    static constexpr int kRed = kRg > 1 ? (kRg - 1) * VPR * 8 : 1;
-};
-
-template <int UPC>
-__device__ __forceinline__ void fused_gate_down(const h16* __restrict__ gd, const h16* __restrict__ xt,
-                                                const int* sel_j, const float* sel_h0, int n, float* hl, float* red,
-                                                float* __restrict__ out) {
-    using Tile = FusedTile<UPC>;
-    constexpr int d = Tile::d, NV = Tile::NV, VPR = Tile::VPR, kRg = Tile::kRg, B = Tile::B, BG = Tile::BG,
-                  RPT = Tile::RPT;
-    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
-    const int piece = tid % VPR, rg = tid / VPR;
-    uint4 xr[NV];
-    {
-        const uint4* xp = reinterpret_cast<const uint4*>(xt);
-#pragma unroll
-        for (int r = 0; r < NV; ++r) xr[r] = xp[r * kWave + lane];
-    }
-    float acc[8];
-#pragma unroll
-    for (int i = 0; i < 8; ++i) acc[i] = 0.0f;
-    for (int b0 = 0; b0 < n; b0 += B) {
-        uint4 gv[BG][NV];
-        uint4 dv[RPT];
-#pragma unroll
-        for (int i = 0; i < BG; ++i) {
-            const int c = b0 + wave + 8 * i;
-            const int j = c < n ? sel_j[c] : -1;
-            const uint4* gp = reinterpret_cast<const uint4*>(gd + (size_t)(j < 0 ? 0 : j) * 2 * d);
-#pragma unroll
-            for (int r = 0; r < NV; ++r) gv[i][r] = j >= 0 ? gp[r * kWave + lane] : make_uint4(0u, 0u, 0u, 0u);
-        }
-#pragma unroll
-        for (int q = 0; q < RPT; ++q) {
-            const int c = b0 + rg + kRg * q;
-            const int j = c < n ? sel_j[c] : -1;
-            const uint4* dp = reinterpret_cast<const uint4*>(gd + (size_t)(j < 0 ? 0 : j) * 2 * d + d);
-            dv[q] = j >= 0 ? dp[piece] : make_uint4(0u, 0u, 0u, 0u);
-        }
-#pragma unroll
-        for (int i = 0; i < BG; ++i) {
-            const int c = b0 + wave + 8 * i;
-            float g = 0.0f;
-#pragma unroll
-            for (int r = 0; r < NV; ++r) {
-                g = dot2(xr[r].x, gv[i][r].x, g);
-                g = dot2(xr[r].y, gv[i][r].y, g);
-                g = dot2(xr[r].z, gv[i][r].z, g);
-                g = dot2(xr[r].w, gv[i][r].w, g);
-            }
-            g = wave_allreduce_sum(g);
-            if (lane == 0) hl[wave + 8 * i] = c < n ? silu(g) * sel_h0[c] : 0.0f;
-        }
-        __syncthreads();
-#pragma unroll
-        for (int q = 0; q < RPT; ++q) {
-            const float h = hl[rg + kRg * q];
-            const uint32_t wds[4] = {dv[q].x, dv[q].y, dv[q].z, dv[q].w};
-#pragma unroll
-            for (int k = 0; k < 4; ++k) {
-                const h16x2 pr = as_h2(wds[k]);
-                acc[2 * k + 0] = fmaf(h, (float)pr.x, acc[2 * k + 0]);
-                acc[2 * k + 1] = fmaf(h, (float)pr.y, acc[2 * k + 1]);
-            }
-        }
-        __syncthreads();  // hl is rewritten by the next batch
-    }
-    if (kRg > 1) {
-        if (rg > 0) {
-#pragma unroll
-            for (int i = 0; i < 8; ++i) red[((rg - 1) * VPR + piece) * 8 + i] = acc[i];
-        }
-        __syncthreads();
-        if (rg == 0) {
-#pragma unroll
-            for (int g2 = 1; g2 < kRg; ++g2)
-#pragma unroll
-                for (int i = 0; i < 8; ++i) acc[i] += red[((g2 - 1) * VPR + piece) * 8 + i];
-        }
-    }
-    if (rg == 0) {
-        float4* o4 = reinterpret_cast<float4*>(out + (size_t)piece * 8);
-        o4[0] = make_float4(acc[0], acc[1], acc[2], acc[3]);
-        o4[1] = make_float4(acc[4], acc[5], acc[6], acc[7]);
-    }
-}
-
 // kDepth passes of loads are in flight per wave: the next one is requested as soon as a pass has been consumed,
 // so the arithmetic runs under the stream of loads instead of after it.
-// FUSED (routed, 8 waves): the workgroup goes on with S3-S5 for the channels it has selected itself and writes a
-// partial y (and its count of selected channels); v and the mask never leave the compute unit.  Selection is per
-// channel, so no workgroup needs to know what another one has selected.  TOUCH: one word of every 128-byte line
-// of a selected channel's [gate | down] chunk is requested at once, so that the chunk is on its way into the
-// caches while the codes are still streaming.
-template <int BITS, int UPC, bool ROUTED, int kPasses, bool G32, int NW, int kDepth, bool FUSED = false,
-          bool TOUCH = false>
+template <int BITS, int UPC, bool ROUTED, int kPasses, bool G32, int NW, int kDepth>
 __global__ __launch_bounds__(NW * 64) void up_gemv_packed_kernel(TaskMap map, const h16* __restrict__ x, RouteArgs ro,
                                                                  float* __restrict__ v,
                                                                  const float* __restrict__ task_tau,
-                                                                 uint32_t* __restrict__ mask_words, int f, int gshift,
-                                                                 float* __restrict__ partial,
-                                                                 int32_t* __restrict__ wg_count) {
-    static_assert(!FUSED || (ROUTED && NW == 8), "the fused variant routes in place and has 8 waves");
+                                                                 uint32_t* __restrict__ mask_words, int f,
+                                                                 int gshift) {
     constexpr int CPW = kWave / UPC;  // channels per wave pass
     constexpr int d = UPC * 64;
     constexpr int kCh = NW * kPasses * CPW;  // channels per workgroup
@@ -263,12 +115,6 @@ __global__ __launch_bounds__(NW * 64) void up_gemv_packed_kernel(TaskMap map, co
     __shared__ float plog[16 * kParts];
     __shared__ DevExpert tab[32];
     __shared__ float taus[32];
-    __shared__ float vloc[FUSED ? kCh : 1];   // v of the workgroup's channels
-    __shared__ int sel_j[FUSED ? kCh : 1];    // selected channels, ascending
-    __shared__ float sel_h0[FUSED ? kCh : 1]; // their v times the routing weight
-    __shared__ int wprefix[kWords + 1];
-    __shared__ float hl[16];
-    __shared__ float red[FUSED ? FusedTile<UPC>::kRed : 1];
     const int tid = threadIdx.x;
     const int wave = tid >> 6, lane = tid & 63;
     const int sub = lane / UPC, u = lane % UPC;
@@ -280,9 +126,7 @@ __global__ __launch_bounds__(NW * 64) void up_gemv_packed_kernel(TaskMap map, co
 
     DevExpert e;
     float tau = 0.0f;
-    float wgt = 1.0f;  // routing weight of this task (fused variant)
-    uint32_t touchv[FUSED && TOUCH ? kPasses : 1][2] = {};
-    bool want_mask = FUSED || mask_words != nullptr;
+    bool want_mask = mask_words != nullptr;
     uint32_t raw[32];  // this lane's 64 activations
     {
         const uint4* xq = reinterpret_cast<const uint4*>(x + (size_t)t * d + u * 64);
@@ -302,37 +146,7 @@ __global__ __launch_bounds__(NW * 64) void up_gemv_packed_kernel(TaskMap map, co
             tab[tid] = ro.table[tid];
             taus[tid] = ro.tau[(size_t)t * ro.tau_stride_t + tid];
         }
-        // a wave per piece of an expert's row, two pieces in flight per wave, fully coalesced 16-byte loads
-        constexpr int NVR = d / 512 / kParts;
-        const int n_items = ro.n_experts * kParts;
-        const uint4* xp4 = reinterpret_cast<const uint4*>(x + (size_t)t * d);
-        for (int it0 = wave; it0 < n_items; it0 += 2 * NW) {
-            uint4 w[2][NVR], xl[2][NVR];
-#pragma unroll
-            for (int q = 0; q < 2; ++q) {
-                const int it = it0 + q * NW < n_items ? it0 + q * NW : it0;
-                const int ex = it / kParts, part = it % kParts;
-                const uint4* wq = reinterpret_cast<const uint4*>(ro.router_cm + (size_t)ex * d);
-#pragma unroll
-                for (int r = 0; r < NVR; ++r) {
-                    w[q][r] = wq[(part * NVR + r) * kWave + lane];
-                    xl[q][r] = xp4[(part * NVR + r) * kWave + lane];
-                }
-            }
-#pragma unroll
-            for (int q = 0; q < 2; ++q) {
-                float acc = 0.0f;
-#pragma unroll
-                for (int r = 0; r < NVR; ++r) {
-                    acc = dot2(xl[q][r].x, w[q][r].x, acc);
-                    acc = dot2(xl[q][r].y, w[q][r].y, acc);
-                    acc = dot2(xl[q][r].z, w[q][r].z, acc);
-                    acc = dot2(xl[q][r].w, w[q][r].w, acc);
-                }
-                acc = group_reduce_sum_to_last<64>(acc);
-                if (lane == kWave - 1 && it0 + q * NW < n_items) plog[it0 + q * NW] = acc;
-            }
-        }
+        route_logits_to_lds<d, NW, kParts>(x + (size_t)t * d, ro, wave, lane, plog);
         FLOE_TL(1);
         __syncthreads();
         // every wave picks the experts for itself from the logits in LDS: no second barrier, and only the ids
@@ -369,13 +183,14 @@ __global__ __launch_bounds__(NW * 64) void up_gemv_packed_kernel(TaskMap map, co
     for (int p = 0; p < kDepth; ++p) ld[p].issue(e, channel_of(p), u, G, gshift);
     FLOE_TL(7);
 
-    if (ROUTED && (FUSED || (blockIdx.x == 0 && wave == 0))) {
+    if (ROUTED && blockIdx.x == 0 && wave == 0) {  // the task's routing record, for the kernels that follow
         const int slot = task - t * map.slots;
+        float wgt = 1.0f;
         if (ro.top_k > 0) {
             const float wl = route_weight_wave16(pick, ro.top_k, ro.renormalize);
             if (slot < ro.top_k) wgt = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, wl), slot));
         }
-        if (blockIdx.x == 0 && tid == 0) {  // the task's routing record, for the kernels that follow
+        if (lane == 0) {
             const int ex = slot < ro.top_k ? __builtin_amdgcn_readlane(pick.id, slot) : ro.n_experts + (slot - ro.top_k);
             ro.task_table[task] = e;
             ro.task_expert[task] = ex;
@@ -402,73 +217,21 @@ __global__ __launch_bounds__(NW * 64) void up_gemv_packed_kernel(TaskMap map, co
     for (int p = 0; p < kPasses; ++p) {
         const int j = jw + p * CPW + sub;
         UnitLoad<BITS, UPC, G32>& L = ld[p % kDepth];
-        const float dot0 = half_unit_dot<BITS>(L.cw, xs, 0, magic);
-        const float dot1 = half_unit_dot<BITS>(L.cw, xs, 1, magic);
-        float part;
-        if (G32) {
-            const h16x2 s2 = as_h2(L.s), z2 = as_h2(L.z);
-            part = (float)s2.x * fmaf(-(float)z2.x, Xg[0], dot0 - Xoff[0]) +
-                   (float)s2.y * fmaf(-(float)z2.y, Xg[1], dot1 - Xoff[1]);
-        } else {
-            const float s = (float)as_h2(L.s).x, z = (float)as_h2(L.z).x;
-            part = s * fmaf(-z, Xg[0] + Xg[1], (dot0 + dot1) - (Xoff[0] + Xoff[1]));
-        }
+        float part = unit_value<BITS, UPC, G32>(L, xs, Xoff, Xg, magic);
         if (p + kDepth < kPasses) L.issue(e, channel_of(p + kDepth), u, G, gshift);
         part = group_reduce_sum_to_last<UPC>(part) * inv_p;
         if (p == 0) FLOE_TL(5);
-        const bool hit = u == UPC - 1 && j < f && want_mask && fabsf(part) > tau;
         if (u == UPC - 1 && j < f) {
-            const int local = j - blockIdx.x * kCh;
-            if (FUSED) vloc[local] = part;
-            else v[(size_t)task * f + j] = part;
-            if (hit) atomicOr(&mw[local >> 5], 1u << (local & 31));
-        }
-        if (FUSED && TOUCH && UPC == 64) {
-            // one channel per wave and pass: the branch is wave-uniform.  The words are not looked at before the
-            // end of the loop, so the wave does not wait for them here.
-            if (__ballot(hit)) {
-                const uint32_t* row = reinterpret_cast<const uint32_t*>(e.gd + (size_t)(jw + p) * 2 * d);
-                touchv[p][0] = row[lane * 32];
-                touchv[p][1] = row[(lane + 64) * 32];
+            v[(size_t)task * f + j] = part;
+            if (want_mask && fabsf(part) > tau) {
+                const int local = j - blockIdx.x * kCh;
+                atomicOr(&mw[local >> 5], 1u << (local & 31));
             }
         }
         __builtin_amdgcn_sched_barrier(0);  // keep the request for pass p + kDepth where it is
     }
     FLOE_TL(6);
-    if (FUSED) {
-        // ---- S3 for the workgroup's own channels: ascending list out of the mask bits in LDS
-        __syncthreads();
-        if (tid == 0) {
-            int run = 0;
-#pragma unroll
-            for (int w = 0; w < kWords; ++w) {
-                wprefix[w] = run;
-                run += __popc(mw[w]);
-            }
-            wprefix[kWords] = run;
-            wg_count[(size_t)task * gridDim.x + blockIdx.x] = run;
-        }
-        __syncthreads();
-        if (tid < kCh) {
-            const uint32_t word = mw[tid >> 5];
-            if ((word >> (tid & 31)) & 1u) {
-                const int pos = wprefix[tid >> 5] + __popc(word & ((1u << (tid & 31)) - 1u));
-                sel_j[pos] = blockIdx.x * kCh + tid;
-                sel_h0[pos] = vloc[tid] * wgt;
-            }
-        }
-        const int n = wprefix[kWords];
-        __syncthreads();
-        if (TOUCH) {
-            uint32_t touch = 0u;
-#pragma unroll
-            for (int p = 0; p < (FUSED && TOUCH ? kPasses : 1); ++p) touch ^= touchv[p][0] ^ touchv[p][1];
-            if (touch == 0x9E3779B9u && f < 0) sel_h0[0] = 0.0f;  // never true: keeps the early requests alive
-        }
-        fused_gate_down<UPC>(e.gd, x + (size_t)t * d, sel_j, sel_h0, n, hl, red,
-                             partial + ((size_t)task * gridDim.x + blockIdx.x) * d);
-        FLOE_TL(9);
-    } else if (want_mask) {
+    if (want_mask) {
         // the workgroup's channels start on a byte of the task's mask; the last workgroup also clears what is
         // left of the last word, so that every byte of the mask is written by exactly one workgroup
         __syncthreads();
@@ -518,11 +281,11 @@ static void launch_packed(bool routed, bool g32, int f, int n_tasks, hipStream_t
     const dim3 grid((f + ch_per_wg - 1) / ch_per_wg, n_tasks);
     if (routed) {
         if (BITS == 2 && !g32)
-            up_gemv_packed_kernel<2, UPC, true, kPassesRouted, false, kWavesRouted, kDepthRouted><<<grid, block, 0, stream>>>(map, x, ro, v, task_tau, mask_words, f, gshift, nullptr, nullptr);
+            up_gemv_packed_kernel<2, UPC, true, kPassesRouted, false, kWavesRouted, kDepthRouted><<<grid, block, 0, stream>>>(map, x, ro, v, task_tau, mask_words, f, gshift);
     } else if (g32) {
-        up_gemv_packed_kernel<BITS, UPC, false, kPassesPlain, true, kWavesPlain, kDepthPlain><<<grid, block, 0, stream>>>(map, x, ro, v, task_tau, mask_words, f, gshift, nullptr, nullptr);
+        up_gemv_packed_kernel<BITS, UPC, false, kPassesPlain, true, kWavesPlain, kDepthPlain><<<grid, block, 0, stream>>>(map, x, ro, v, task_tau, mask_words, f, gshift);
     } else {
-        up_gemv_packed_kernel<BITS, UPC, false, kPassesPlain, false, kWavesPlain, kDepthPlain><<<grid, block, 0, stream>>>(map, x, ro, v, task_tau, mask_words, f, gshift, nullptr, nullptr);
+        up_gemv_packed_kernel<BITS, UPC, false, kPassesPlain, false, kWavesPlain, kDepthPlain><<<grid, block, 0, stream>>>(map, x, ro, v, task_tau, mask_words, f, gshift);
     }
 }
 
@@ -533,35 +296,6 @@ static void launch_packed_upc(int upc, bool routed, bool g32, int f, int n_tasks
     if (upc == 64) launch_packed<BITS, 64>(routed, g32, f, n_tasks, stream, map, x, ro, v, task_tau, mask_words, gshift);
     else if (upc == 32) launch_packed<BITS, 32>(routed, g32, f, n_tasks, stream, map, x, ro, v, task_tau, mask_words, gshift);
     else launch_packed<BITS, 16>(routed, g32, f, n_tasks, stream, map, x, ro, v, task_tau, mask_words, gshift);
-}
-
-// S1-S5 of the small-batch layer path in one kernel (INT2, group >= 64, <= 16 experts): grid (fused_blocks, n_tasks)
-#ifndef FLOE_FUSED_TOUCH
-#define FLOE_FUSED_TOUCH true
-#endif
-int fused_blocks(int d, int f) {
-    const int ch = kWavesRouted * kPassesRouted * (64 / (d / 64));
-    return (f + ch - 1) / ch;
-}
-template <int UPC>
-static void launch_fused_upc(const TaskMap& map, const h16* x, const RouteArgs& ro, float* partial, int32_t* wg_count,
-                             int f, int gshift, int n_tasks, hipStream_t stream) {
-    static_assert(kWavesRouted == 8, "fused variant");
-    const dim3 grid(fused_blocks(UPC * 64, f), n_tasks), block(kWavesRouted * 64);
-    up_gemv_packed_kernel<2, UPC, true, kPassesRouted, false, kWavesRouted, kDepthRouted, true, FLOE_FUSED_TOUCH>
-        <<<grid, block, 0, stream>>>(map, x, ro, nullptr, nullptr, nullptr, f, gshift, partial, wg_count);
-}
-hipError_t launch_fused_layer(const TaskMap& map, const h16* x, const RouteArgs& route, float* partial,
-                              int32_t* wg_count, int d, int f, int group, int n_tasks, hipStream_t stream) {
-    if (f == 0 || n_tasks == 0) return hipSuccess;
-    const int gshift = ilog2_exact(group);
-    switch (d) {
-        case 4096: launch_fused_upc<64>(map, x, route, partial, wg_count, f, gshift, n_tasks, stream); break;
-        case 2048: launch_fused_upc<32>(map, x, route, partial, wg_count, f, gshift, n_tasks, stream); break;
-        case 1024: launch_fused_upc<16>(map, x, route, partial, wg_count, f, gshift, n_tasks, stream); break;
-        default: return hipErrorInvalidValue;
-    }
-    return hipGetLastError();
 }
 
 hipError_t launch_up_gemv(const TaskMap& map, const h16* x, const RouteArgs* route, float* v, const float* task_tau,
