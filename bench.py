@@ -31,7 +31,7 @@ CONFIG_ID, SEED = 3, 0
 N_TOKENS = 16          # distinct decode tokens the steps cycle through
 # HBM bytes per launch of each kernel for THIS workload, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs scaled by
 # a plain 256 MiB copy (profiles/layer_decode_config3_T1_hbm_traffic.md); hardware counters cannot be read from here
-MEASURED_TRAFFIC_BYTES = {"up_gemv": 37.73e6, "gate_down": 51.56e6, "combine": 4.24e6}
+MEASURED_TRAFFIC_BYTES = {"fused_ffn": None, "combine": None}
 
 
 def log(*a):
@@ -189,14 +189,14 @@ def main():
 
     # ---------------------------------------------------------------- per-kernel durations (HIP events)
     # A pair of events around one kernel reads the kernel's duration plus a fixed cost o of the two markers.
-    # In the timed graph the three kernels of a step run back to back (each waits for the one before it), so a
-    # step lasts the sum of their durations: o = (sum of the three bracketed reads - graph step time) / 3.
+    # In the timed graph the kernels of a step run back to back (each waits for the one before it), so a
+    # step lasts the sum of their durations: o = (sum of the bracketed reads - graph step time) / number of kernels.
     # With --launch stream there is no such step time, and o comes from a copy kernel instead: a bracket around
     # one launch reads t + o, one around nine launches 9t + o.
-    # (With <= 16 experts the router runs inside the up_gemv kernel: there is no router launch to bracket.)
+    # (At T = 1 the layer is two kernels: router, up GEMV, selection and gate/down in one, then the combine.)
     raw = {}
     with torch.cuda.stream(stream):
-        for name in ("up_gemv", "gate_down", "combine"):
+        for name in ("fused_ffn", "combine"):
             pairs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(K)]
             for a, b in pairs:          # torch creates the hipEvent_t on first record
                 a.record(stream)
@@ -231,17 +231,17 @@ def main():
     torch.cuda.synchronize()
 
     # ---------------------------------------------------------------- byte model (algorithmic bytes)
+    # what the method has to move per layer-token: the routed experts' codes, scales and zeros; the [gate | down]
+    # chunks of the selected channels; the router matrix, x; one fp32 result per routed expert and the fp16 output.
+    # (v, the mask and the index list stay inside the compute unit and are not counted.)
     codes_meta = D * F_INT * BITS // 8 + 4 * F_INT * (D // GROUP)
     k_steps = np.array([Ks[(W + i) % N_TOKENS] for i in range(K)])          # [K][TOP_K]
     k_mean = float(np.mean(k_steps.sum(axis=1)))
-    bytes_up = TOP_K * (codes_meta + 4 * F_INT) + 2 * D                       # codes+scale+zero, v write, x
-    # selected gate columns and down rows, their v and index entries, the v scan of the selection, x, y
-    bytes_gd = k_mean * (2 * 2 * D + 4 + 4) + TOP_K * 4 * F_INT + 2 * D + TOP_K * 4 * D
     bytes_router = N_EXPERTS * D * 2 + 2 * D
+    bytes_fused = TOP_K * codes_meta + k_mean * 2 * 2 * D + bytes_router + TOP_K * 4 * D
     bytes_combine = TOP_K * 4 * D + 2 * D
-    bytes_up += bytes_router                                                  # the router runs inside this kernel
-    bytes_step = bytes_up + bytes_gd + bytes_combine
-    kernel_bytes = {"up_gemv": bytes_up, "gate_down": bytes_gd, "combine": bytes_combine}
+    bytes_step = bytes_fused + bytes_combine
+    kernel_bytes = {"fused_ffn": bytes_fused, "combine": bytes_combine}
     dominant = max(per_kernel, key=lambda n: per_kernel[n])
     dom_gbs = kernel_bytes[dominant] / (per_kernel[dominant] * 1e-6) / 1e9
     kernels = {n: {"us": round(per_kernel[n], 3), "algorithmic_bytes": int(kernel_bytes[n]),
@@ -253,7 +253,7 @@ def main():
                 "layer_frac": round(bytes_step / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
                 "event_bracket_overhead_us": round(bracket_us, 3),
                 "timing": "hipEvent pair recorded around each launch of the kernel in a second pass over the same K steps, "
-                          "minus the cost of the two markers (live: a third of what the three bracketed reads sum to beyond the graph's step time)"}
+                          "minus the cost of the two markers (live: the share per kernel of what the bracketed reads sum to beyond the graph's step time)"}
 
     if args.calib_copy:
         src = torch.ones((64 << 20,), dtype=torch.float32, device=dev)     # 256 MiB read + 256 MiB written per copy
@@ -349,11 +349,15 @@ def bench_expert(args, np, torch, S, FL, dev):
             cnt = torch.zeros((1,), dtype=torch.int32, device=dev)
             ws = torch.empty((FL.floe_expert_workspace_bytes(D, F_INT, bits, GROUP, 1) + 512,), dtype=torch.uint8, device=dev)
 
-            def call(i):
-                FL.floe_expert_ffn_sparse(experts[i % copies], x, tau, None, y, idx, cnt, ws)
-            ms = _graph_time(torch, stream, call, K, W)
+            FL.floe_expert_ffn_sparse(experts[0], x, tau, None, y, idx, cnt, ws)      # once with the list: K
+            torch.cuda.synchronize()
             Ksel = int(cnt.item())
-            nbytes = D * F_INT * bits // 8 + 4 * F_INT * (D // GROUP) + 2 * Ksel * 2 * D + 8 * F_INT + 4 * Ksel + 2 * D + 4 * D
+
+            def call(i):            # timed: y only (the index list is not needed for the result)
+                FL.floe_expert_ffn_sparse(experts[i % copies], x, tau, None, y, None, None, ws, want_list=False)
+            ms = _graph_time(torch, stream, call, K, W)
+            # codes + scales + zeros, the selected [gate | down] chunks, x, y (v and the list stay on chip)
+            nbytes = D * F_INT * bits // 8 + 4 * F_INT * (D // GROUP) + 2 * Ksel * 2 * D + 2 * D + 4 * D
             rows.append({"bits": bits, "sparsity_pct": pct, "K": Ksel, "us_per_expert_ffn": round(ms * 1e3, 3),
                          "algorithmic_bytes": nbytes, "GBps": round(nbytes / (ms * 1e-3) / 1e9, 1),
                          "frac_of_hbm_peak": round(nbytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)})

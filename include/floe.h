@@ -76,7 +76,8 @@ typedef enum {
     FLOE_KERNEL_SELECT = 4,
     FLOE_KERNEL_GATE_DOWN = 5,
     FLOE_KERNEL_COMBINE = 6,
-    FLOE_KERNEL_STAGE = 7
+    FLOE_KERNEL_STAGE = 7,
+    FLOE_KERNEL_FUSED_FFN = 8 /* (router +) up GEMV + selection + gate/down of small batches, one kernel */
 } floe_kernel_id;
 int floe_profile_kernel(int kernel_id, void* start_event, void* stop_event);
 
@@ -138,7 +139,8 @@ int floe_gate_down_sparse(const floe_expert* e, const floe_half* x, int T, const
  * S2..S5 -- the whole of Alg. 1 for one expert and T independent tokens (each token has its own
  * threshold tau[t], its own mask and its own result):
  *   v = x . W_up^Q;  idx, count from |v| > tau;  y_acc += out_scale * (sparse gate/down product).
- * idx dev [T][f] and count dev [T] are outputs (the staging call and the parity checks consume them).
+ * idx dev [T][f] and count dev [T] are outputs (the staging call and the parity checks consume them); pass both
+ * as NULL when the list itself is not wanted (the result y_acc is the same; small batches then skip building it).
  * The intermediate v lives in the workspace.  e->gd must be the full (unstaged) matrix.
  */
 int floe_expert_ffn_sparse(const floe_expert* e, const floe_half* x, int T, const float* tau,

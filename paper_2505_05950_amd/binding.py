@@ -87,7 +87,8 @@ def floe_status_string(status: int) -> str:
     return load().floe_status_string(status).decode()
 
 
-KERNEL_IDS = {"none": 0, "quantize": 1, "router": 2, "up_gemv": 3, "select": 4, "gate_down": 5, "combine": 6, "stage": 7}
+KERNEL_IDS = {"none": 0, "quantize": 1, "router": 2, "up_gemv": 3, "select": 4, "gate_down": 5, "combine": 6, "stage": 7,
+              "fused_ffn": 8}
 
 
 def floe_profile_kernel(kernel: str, start_event=None, stop_event=None):
@@ -199,13 +200,17 @@ def floe_gate_down_sparse(e: Expert, x, v, idx, count, out_scale, y_acc, workspa
     return y_acc
 
 
-def floe_expert_ffn_sparse(e: Expert, x, tau, out_scale, y_acc, idx=None, count=None, workspace=None, stream=None):
-    """Alg. 1 for T tokens; returns (y_acc, idx, count)."""
+def floe_expert_ffn_sparse(e: Expert, x, tau, out_scale, y_acc, idx=None, count=None, workspace=None, stream=None,
+                           want_list=True):
+    """Alg. 1 for T tokens; returns (y_acc, idx, count); want_list=False passes no list buffers (idx, count = None)."""
     T = x.shape[0]
-    if idx is None:
-        idx = torch.full((T, e.f), -1, dtype=torch.int32, device=x.device)
-    if count is None:
-        count = torch.empty((T,), dtype=torch.int32, device=x.device)
+    if want_list:
+        if idx is None:
+            idx = torch.full((T, e.f), -1, dtype=torch.int32, device=x.device)
+        if count is None:
+            count = torch.empty((T,), dtype=torch.int32, device=x.device)
+    else:
+        idx = count = None
     if workspace is None:
         workspace = _workspace(floe_expert_workspace_bytes(e.d, e.f, e.bits, e.group, T), x.device)
     wp, wn = _aligned_ptr(workspace)

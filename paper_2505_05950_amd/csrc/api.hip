@@ -88,18 +88,23 @@ TaskMap single_map(const floe_expert* e) {
     return m;
 }
 
-// workspace of the one-expert entry points: [v: T*f floats][mask words][partial: T*nblk*d floats]
+// workspace of the one-expert entry points: [v: T*f floats][mask words][counts][idx when not fused][partial: T*nblk*d floats]
 struct ExpertWs {
-    size_t v_off, mask_off, partial_off, total;
-    int nblk;
+    size_t v_off, mask_off, count_off, idx_off, partial_off, total;
+    int nblk, fused_passes, nblk_fused;
 };
 ExpertWs expert_ws(const floe_shape* s, int T) {
     ExpertWs w;
     w.nblk = gd_blocks(T, s->f);
+    w.fused_passes = packed_fast_shape(s->d, s->bits, s->group) ? fused_passes(s->d, s->f, T) : 0;
+    w.nblk_fused = w.fused_passes ? fused_blocks(s->d, s->f, w.fused_passes) : 0;
+    const int nblk_alloc = w.nblk > w.nblk_fused ? w.nblk : w.nblk_fused;
     size_t o = 0;
     w.v_off = o;       o += align_up((size_t)T * s->f * sizeof(float));
     w.mask_off = o;    o += align_up((size_t)T * mask_words_per_task(s->f) * sizeof(uint32_t));
-    w.partial_off = o; o += align_up((size_t)T * w.nblk * s->d * sizeof(float));
+    w.count_off = o;   o += align_up((size_t)T * (w.nblk_fused > 1 ? w.nblk_fused : 1) * sizeof(int32_t));
+    w.idx_off = o;     o += w.fused_passes ? 0 : align_up((size_t)T * s->f * sizeof(int32_t));  // list for callers that pass none
+    w.partial_off = o; o += align_up((size_t)T * nblk_alloc * s->d * sizeof(float));
     w.total = o;
     return w;
 }
@@ -111,17 +116,15 @@ bool mask_path_ok(int f) { return mask_words_per_task(f) <= 2048; }
 struct LayerWs {
     size_t table_off, expert_off, weight_off, tau_off, count_off, mask_off, groups_off, ngroups_off, v_off, idx_off,
         partial_off, total;
-    int n_tasks, nblk, nblk_fused;
-    bool fused;
+    int n_tasks, nblk, nblk_fused, fused_passes;
 };
 LayerWs layer_ws(const floe_layer* L, int T) {
     LayerWs w;
     const int slots = L->top_k + L->n_shared;
     w.n_tasks = T * slots;
     w.nblk = gd_blocks(w.n_tasks, L->s.f);
-    w.fused = w.n_tasks <= kFusedMaxTasks &&
-              route_in_place_ok(L->s.d, L->s.bits, L->s.group, L->n_experts, L->top_k, L->n_shared);
-    w.nblk_fused = w.fused ? fused_blocks(L->s.d, L->s.f) : 0;
+    w.fused_passes = packed_fast_shape(L->s.d, L->s.bits, L->s.group) ? fused_passes(L->s.d, L->s.f, w.n_tasks) : 0;
+    w.nblk_fused = w.fused_passes ? fused_blocks(L->s.d, L->s.f, w.fused_passes) : 0;
     const int nblk_alloc = w.nblk > w.nblk_fused ? w.nblk : w.nblk_fused;
     size_t o = 0;
     w.table_off = o;  o += align_up((size_t)w.n_tasks * sizeof(DevExpert));
@@ -173,7 +176,7 @@ int floe_last_hip_error(void) { return g_last_hip_error; }
 int floe_abi_version(void) { return 2; }
 
 int floe_profile_kernel(int kernel_id, void* start_event, void* stop_event) {
-    if (kernel_id < 0 || kernel_id > FLOE_KERNEL_STAGE) return FLOE_EINVAL;
+    if (kernel_id < 0 || kernel_id > FLOE_KERNEL_FUSED_FFN) return FLOE_EINVAL;
     if (kernel_id != 0 && (!start_event || !stop_event)) return FLOE_EINVAL;
     g_hook.id = kernel_id;
     g_hook.start = (hipEvent_t)start_event;
@@ -255,8 +258,8 @@ int floe_expert_ffn_sparse(const floe_expert* e, const floe_half* x, int T, cons
     if (rc) return rc;
     if ((rc = check_T(T))) return rc;
     if (T == 0) return FLOE_OK;
-    if (!e->up_codes || !e->up_scale || !e->up_zero || !e->gd || !x || !tau || !y_acc || !idx || !count || !workspace)
-        return FLOE_EINVAL;
+    if (!e->up_codes || !e->up_scale || !e->up_zero || !e->gd || !x || !tau || !y_acc || !workspace) return FLOE_EINVAL;
+    if ((idx == nullptr) != (count == nullptr)) return FLOE_EINVAL;  // the list and its length come together
     if (!aligned(e->up_codes, 16) || !aligned(e->gd, 16) || !aligned(x, 16) || !aligned(y_acc, 16) ||
         !aligned(workspace, kAlign))
         return FLOE_EINVAL;
@@ -269,22 +272,39 @@ int floe_expert_ffn_sparse(const floe_expert* e, const floe_half* x, int T, cons
     const TaskMap map = single_map(e);
     const h16* xh = reinterpret_cast<const h16*>(x);
     uint32_t* mask = reinterpret_cast<uint32_t*>(static_cast<char*>(workspace) + w.mask_off);
-    if (mask_path_ok(e->s.f)) {
-        // the GEMV leaves one mask bit per channel; the gate/down kernel compacts them and writes idx / count
-        FLOE_LAUNCH(FLOE_KERNEL_UP_GEMV, st,
-                    launch_up_gemv(map, xh, nullptr, v, tau, mask, e->s.d, e->s.f, e->s.bits, e->s.group, T, st));
-        FLOE_LAUNCH(FLOE_KERNEL_GATE_DOWN, st,
-                    launch_gate_down(map, nullptr, e->s.f, xh, v, mask, idx, count, out_scale, partial, e->s.d, e->s.f, T,
-                                     w.nblk, st));
+    int nblk = w.nblk;
+    if (w.fused_passes) {
+        // small batch: GEMV, selection and gate/down in one kernel; the list, when asked for, is cut from v afterwards
+        FusedArgs a{};
+        a.map = map; a.x = xh; a.route = nullptr; a.task_tau = tau; a.task_scale = out_scale;
+        a.v_out = idx ? v : nullptr;
+        a.partial = partial;
+        a.wg_count = reinterpret_cast<int32_t*>(static_cast<char*>(workspace) + w.count_off);
+        a.d = e->s.d; a.f = e->s.f; a.group = e->s.group; a.n_tasks = T; a.passes = w.fused_passes;
+        FLOE_LAUNCH(FLOE_KERNEL_FUSED_FFN, st, launch_fused(a, e->s.bits, st));
+        if (idx) FLOE_LAUNCH(FLOE_KERNEL_SELECT, st, launch_select(v, e->s.f, T, tau, idx, count, st));
+        nblk = w.nblk_fused;
     } else {
-        FLOE_LAUNCH(FLOE_KERNEL_UP_GEMV, st,
-                    launch_up_gemv(map, xh, nullptr, v, nullptr, nullptr, e->s.d, e->s.f, e->s.bits, e->s.group, T, st));
-        FLOE_LAUNCH(FLOE_KERNEL_SELECT, st, launch_select(v, e->s.f, T, tau, idx, count, st));
-        FLOE_LAUNCH(FLOE_KERNEL_GATE_DOWN, st,
-                    launch_gate_down(map, nullptr, e->s.f, xh, v, nullptr, idx, count, out_scale, partial, e->s.d, e->s.f, T,
-                                     w.nblk, st));
+        // a caller that wants no list still gets one built, in the workspace
+        int32_t* idx_ws = idx ? idx : reinterpret_cast<int32_t*>(static_cast<char*>(workspace) + w.idx_off);
+        int32_t* count_ws = count ? count : reinterpret_cast<int32_t*>(static_cast<char*>(workspace) + w.count_off);
+        if (mask_path_ok(e->s.f)) {
+            // the GEMV leaves one mask bit per channel; the gate/down kernel compacts them and writes idx / count
+            FLOE_LAUNCH(FLOE_KERNEL_UP_GEMV, st,
+                        launch_up_gemv(map, xh, nullptr, v, tau, mask, e->s.d, e->s.f, e->s.bits, e->s.group, T, st));
+            FLOE_LAUNCH(FLOE_KERNEL_GATE_DOWN, st,
+                        launch_gate_down(map, nullptr, e->s.f, xh, v, mask, idx_ws, count_ws, out_scale, partial, e->s.d,
+                                         e->s.f, T, w.nblk, st));
+        } else {
+            FLOE_LAUNCH(FLOE_KERNEL_UP_GEMV, st,
+                        launch_up_gemv(map, xh, nullptr, v, nullptr, nullptr, e->s.d, e->s.f, e->s.bits, e->s.group, T, st));
+            FLOE_LAUNCH(FLOE_KERNEL_SELECT, st, launch_select(v, e->s.f, T, tau, idx_ws, count_ws, st));
+            FLOE_LAUNCH(FLOE_KERNEL_GATE_DOWN, st,
+                        launch_gate_down(map, nullptr, e->s.f, xh, v, nullptr, idx_ws, count_ws, out_scale, partial, e->s.d,
+                                         e->s.f, T, w.nblk, st));
+        }
     }
-    FLOE_LAUNCH(FLOE_KERNEL_COMBINE, st, launch_combine(partial, e->s.d, T, 1, w.nblk, y_acc, nullptr, st));
+    FLOE_LAUNCH(FLOE_KERNEL_COMBINE, st, launch_combine(partial, e->s.d, T, 1, nblk, y_acc, nullptr, st));
     return FLOE_OK;
 }
 
@@ -360,8 +380,10 @@ int floe_moe_layer_decode(const floe_layer* L, const floe_half* x, int T, floe_h
                             mfma_batch_pays(L->n_experts + L->n_shared, w.n_tasks) &&
                             aligned(L->experts ? L->experts[0].up_scale : nullptr, 16);
     int nblk = w.nblk, count_parts = 0;
-    if (w.fused && !batch_mfma) {
-        // two kernels: [router + up GEMV + selection + gate/down on the workgroup's own channels] -> [combine]
+    if (w.fused_passes && !batch_mfma) {
+        // small batch: [(router +) up GEMV + selection + gate/down on the workgroup's own channels] -> [combine];
+        // with INT2 and <= 16 experts the router runs inside the same kernel, otherwise in one of its own before it
+        const bool in_place = route_in_place_ok(L->s.d, L->s.bits, L->s.group, L->n_experts, L->top_k, L->n_shared);
         RouteArgs ro;
         ro.router_cm = reinterpret_cast<const h16*>(L->router_cm);
         ro.tau = L->tau;
@@ -370,8 +392,24 @@ int floe_moe_layer_decode(const floe_layer* L, const floe_half* x, int T, floe_h
         ro.table = static_cast<const DevExpert*>(L->dev_table);
         ro.task_table = task_table;
         ro.task_expert = task_expert; ro.task_weight = task_weight; ro.task_tau = task_tau;
-        FLOE_LAUNCH(FLOE_KERNEL_UP_GEMV, st,
-                    launch_fused_layer(map, xh, ro, partial, count, L->s.d, L->s.f, L->s.group, w.n_tasks, st));
+        if (!in_place) {
+            RouterArgs ra;
+            ra.router_cm = ro.router_cm;
+            ra.x = xh;
+            ra.tau = L->tau;
+            ra.tau_stride_t = L->tau_stride_t;
+            ra.n_experts = L->n_experts; ra.top_k = L->top_k; ra.n_shared = L->n_shared; ra.renormalize = L->renormalize;
+            ra.d = L->s.d;
+            ra.table = ro.table;
+            ra.task_table = task_table;
+            ra.task_expert = task_expert; ra.task_weight = task_weight; ra.task_tau = task_tau;
+            FLOE_LAUNCH(FLOE_KERNEL_ROUTER, st, launch_router(ra, T, st));
+        }
+        FusedArgs a{};
+        a.map = map; a.x = xh; a.route = in_place ? &ro : nullptr; a.task_tau = task_tau; a.task_scale = task_weight;
+        a.v_out = nullptr; a.partial = partial; a.wg_count = count;
+        a.d = L->s.d; a.f = L->s.f; a.group = L->s.group; a.n_tasks = w.n_tasks; a.passes = w.fused_passes;
+        FLOE_LAUNCH(FLOE_KERNEL_FUSED_FFN, st, launch_fused(a, L->s.bits, st));
         nblk = w.nblk_fused;
         count_parts = w.nblk_fused;
     } else if (mask_ok && !batch_mfma &&

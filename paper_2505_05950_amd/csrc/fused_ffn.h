@@ -1,0 +1,313 @@
+// (S1 +) S2-S5 of a small decode batch in ONE kernel (Sec. 3.3 router; Alg. 1 steps 2-5 with the quantized up
+// projection of Sec. 3.2.2 and the compact [gate | down] chunks of Sec. 3.4.2).  Template for every bit width;
+// instantiated in fused_int2.hip / fused_int3.hip / fused_int4.hip.
+//
+// Why one kernel: the threshold test of Alg. 1 is per channel, so a workgroup that has computed v for a block
+// of channels knows, without hearing from anybody else, which of ITS channels take part in steps 4-5; it can
+// run them itself and hand over a partial y.  v, the mask and the index list never leave the compute unit, and
+// two kernel boundaries (launch, drain, dependent prologue) disappear.
+//
+// Why two kinds of waves: a layer-token moves 37 MB of codes and 47 MB of selected chunks, and the kernel lasts
+// as long as that stream plus whatever is not overlapped with it.  The chunk of a selected channel should
+// therefore be requested the moment the channel is known, while the code stream keeps flowing.  The hardware
+// counts a wave's outstanding loads in order, so a wave that mixes a deep static pipeline of code loads with
+// data-dependent chunk loads ends up waiting for one because of the other.  So the workgroup (12 waves) splits:
+//   * 4 producer waves stream the codes (kDepth passes in flight each), compute v_j on packed fp16 dot
+//     products (see up_gemv.hip / xprep.h), compare with tau and push (j, v_j * routing weight) of every
+//     selected channel into a queue in LDS - one queue per producer, written by nobody else;
+//   * 8 consumer waves, two per queue taking its entries in turn: request the chunk (a whole gate column and down row per
+//     wave, coalesced), x . gate on dot2 + DPP, SiLU, and h * down row into d/64 fp32 accumulators per lane.
+// A producer never waits for a consumer; a consumer polls its queue in LDS and leaves once its producer has
+// raised its flag and the queue is empty, so every wave reaches the final barrier.  Queue k of workgroup b
+// always holds the same channels in the same order, hence the sums are formed in a fixed order and the result
+// is reproducible bit for bit.  After the barrier the four accumulators meet in LDS and the workgroup stores
+// one partial y; S6 (combine_kernel) adds the partials.
+#pragma once
+
+#include "floe_dev.h"
+#include "launch.h"
+#include "packed_unit.h"
+#include "route.h"
+#include "xprep.h"
+
+namespace floe {
+
+constexpr int kFusedProducers = 4;
+constexpr int kFusedCpp = 2;                                    // consumer waves per producer (queue entries dealt in turn)
+constexpr int kFusedConsumers = kFusedProducers * kFusedCpp;
+constexpr int kFusedThreads = (kFusedProducers + kFusedConsumers) * 64;
+static_assert(kFusedProducers * fused_passes_long == 112 && fused_producers == kFusedProducers, "launch.h states the block sizes");
+
+__device__ __forceinline__ int lds_peek(const int* p) { return *reinterpret_cast<const volatile int*>(p); }
+
+// ROUTED: the workgroup routes in place (INT2, <= 16 experts); otherwise the task's expert comes from `map`, its
+// threshold from task_tau and its output scale from task_scale (nullptr = 1).
+// kPasses channels-per-wave passes per producer, kDepth of them in flight.  v_out (optional): v[task][f].
+template <int BITS, int UPC, bool G32, bool ROUTED, int kPasses, int kDepth>
+__global__ __launch_bounds__(kFusedThreads) void fused_ffn_kernel(TaskMap map, const h16* __restrict__ x, RouteArgs ro,
+                                                                  const float* __restrict__ task_tau,
+                                                                  const float* __restrict__ task_scale, int f,
+                                                                  int gshift, float* __restrict__ v_out,
+                                                                  float* __restrict__ partial,
+                                                                  int32_t* __restrict__ wg_count) {
+    constexpr int d = 64 * UPC;
+    constexpr int CPW = kWave / UPC;      // channels per wave pass
+    constexpr int NV = d / 512;           // uint4 per lane of a gate column / down row
+    constexpr int kQ = kPasses * CPW;     // queue capacity = channels per producer
+    static_assert(kDepth >= 1 && kDepth <= kPasses, "depth of the load pipeline");
+    __shared__ float plog[16];
+    __shared__ DevExpert tab[32];
+    __shared__ float taus[32];
+    __shared__ int qj[kFusedProducers][kQ];     // selected channel, -1 = not written yet
+    __shared__ float qh[kFusedProducers][kQ];   // its v times the routing weight
+    __shared__ int done[kFusedProducers];
+    __shared__ int n_sel;
+    __shared__ float yred[kFusedConsumers][d];
+    __shared__ uint4 xlds[d / 8];               // the token, for the consumers' gate dot products
+    const int tid = threadIdx.x;
+    const int wave = tid >> 6, lane = tid & 63;
+    const int task = blockIdx.y;
+    const int t = task / map.slots;
+    const int slot = task - t * map.slots;
+    const h16* xt = x + (size_t)t * d;
+    for (int i = tid; i < kFusedProducers * kQ; i += kFusedThreads) (&qj[0][0])[i] = -1;
+    if (tid < kFusedProducers) done[tid] = 0;
+    if (tid == 0) n_sel = 0;
+    for (int i = tid; i < d / 8; i += kFusedThreads) xlds[i] = reinterpret_cast<const uint4*>(xt)[i];
+    FLOE_TL(0);
+
+    const bool producer = wave < kFusedProducers;
+    const int u = lane % UPC, sub = lane / UPC;
+    uint32_t raw[32];  // producer: this lane's 64 activations (the unit it owns in every channel)
+    if (producer) {
+        const uint4* xq = reinterpret_cast<const uint4*>(xt + u * 64);
+#pragma unroll
+        for (int r = 0; r < 8; ++r) {
+            const uint4 q = xq[r];
+            raw[4 * r + 0] = q.x; raw[4 * r + 1] = q.y; raw[4 * r + 2] = q.z; raw[4 * r + 3] = q.w;
+        }
+    }
+    DevExpert e;
+    float tau;
+    Pick16 pick{};
+    int ex = 0;
+    if (ROUTED) {
+        // ---- S1 in place (as in the routed GEMV kernel): all waves share the router's dot products
+        if (tid < ro.n_experts + ro.n_shared) {
+            tab[tid] = ro.table[tid];
+            taus[tid] = ro.tau[(size_t)t * ro.tau_stride_t + tid];
+        }
+        route_logits_to_lds<d, kFusedThreads / 64, 1>(xt, ro, wave, lane, plog);
+        FLOE_TL(1);
+        __syncthreads();
+        ex = ro.n_experts + (slot - ro.top_k);  // a shared expert
+        if (ro.top_k > 0) {
+            const float lg = (lane & 15) < ro.n_experts ? plog[lane & 15] : 0.0f;
+            pick = route_pick_wave16(lg, lane, ro.n_experts, ro.top_k);
+            if (slot < ro.top_k) ex = __builtin_amdgcn_readlane(pick.id, slot);
+        }
+        e = tab[ex];
+        tau = taus[ex];
+    } else {
+        e = task_expert_of(map, task);
+        tau = task_tau[task];
+        __syncthreads();  // queues, flags and xlds are set up
+    }
+    FLOE_TL(2);
+
+    if (producer) {
+        // ================================================================ producer: codes -> v -> queue
+        const int G = d >> gshift;
+        const int jw = (blockIdx.x * kFusedProducers + wave) * kQ;
+        auto channel_of = [&](int p) {
+            const int j = jw + p * CPW + sub;
+            return j < f ? j : f - 1;  // keep the address in bounds; a clamped lane's result is not used
+        };
+        UnitLoad<BITS, UPC, G32> ld[kDepth];
+#pragma unroll
+        for (int p = 0; p < kDepth; ++p) ld[p].issue(e, channel_of(p), u, G, gshift);
+        FLOE_TL(3);
+
+        float wgt = 1.0f;
+        if (ROUTED) {
+            if (ro.top_k > 0) {
+                const float wl = route_weight_wave16(pick, ro.top_k, ro.renormalize);
+                if (slot < ro.top_k) wgt = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, wl), slot));
+            }
+            if (blockIdx.x == 0 && tid == 0) {  // the task's routing record (statistics)
+                ro.task_table[task] = e;
+                ro.task_expert[task] = ex;
+                ro.task_weight[task] = wgt;
+                ro.task_tau[task] = tau;
+            }
+        } else if (task_scale) {
+            wgt = task_scale[task];
+        }
+
+        uint32_t xs[32];
+        float Xg[2], Xoff[2];
+        // every group of UPC lanes holds the whole token, so the wave-wide maximum is the token's
+        const float amax = wave_allreduce_max_nonneg(unit_amax(raw));
+        const int down = xprep_down<BITS>(amax);
+        const float inv_p = ldexpf(1.0f, down);
+        unit_prepare<BITS>(raw, down, xs, Xoff, Xg);
+        uint32_t magic = 0x3C003C00u;
+        asm volatile("" : "+v"(magic));  // keep it in a VGPR: v_and_or_b32 takes one scalar operand only
+        FLOE_TL(4);
+
+        int k = 0;  // entries pushed so far (wave-uniform)
+#pragma unroll 1
+        for (int p0 = 0; p0 < kPasses; p0 += kDepth) {
+#pragma unroll
+            for (int i = 0; i < kDepth; ++i) {
+                const int p = p0 + i;
+                if (kPasses % kDepth != 0 && p >= kPasses) break;  // last, shorter round (wave-uniform)
+                const int j = jw + p * CPW + sub;
+                float part = unit_value<BITS, UPC, G32>(ld[i], xs, Xoff, Xg, magic);
+                if (p + kDepth < kPasses) ld[i].issue(e, channel_of(p + kDepth), u, G, gshift);
+                part = group_reduce_sum_to_last<UPC>(part) * inv_p;
+                const bool mine = u == UPC - 1 && j < f;
+                if (v_out && mine) v_out[(size_t)task * f + j] = part;
+                const bool hit = mine && fabsf(part) > tau;
+                unsigned long long hits = __ballot(hit);
+                while (hits) {  // wave-uniform; ascending channel order
+                    const int bit = __ffsll((long long)hits) - 1;
+                    hits &= hits - 1;
+                    if (lane == bit) {
+                        // the same lane writes both words; LDS keeps a wave's accesses in order, so whoever sees
+                        // the channel id also sees the value
+                        *reinterpret_cast<volatile float*>(&qh[wave][k]) = part * wgt;
+                        *reinterpret_cast<volatile int*>(&qj[wave][k]) = j;
+                    }
+                    ++k;
+                }
+                __builtin_amdgcn_sched_barrier(0);  // keep the request for pass p + kDepth where it is
+            }
+        }
+        if (lane == 0) {
+            *reinterpret_cast<volatile int*>(&done[wave]) = 1;  // after the last push, in program order
+            atomicAdd(&n_sel, k);
+        }
+        FLOE_TL(5);
+    } else {
+        // ================================================================ consumer: queue -> chunk -> y
+        const int c = wave - kFusedProducers;   // consumer id: serves queue c / kFusedCpp, entries c % kFusedCpp, + kFusedCpp, ...
+        const int qc = c / kFusedCpp;
+        float acc[8 * NV];
+#pragma unroll
+        for (int i = 0; i < 8 * NV; ++i) acc[i] = 0.0f;
+        int k = c % kFusedCpp;
+        for (;;) {
+            int j = __builtin_amdgcn_readfirstlane(lds_peek(&qj[qc][k < kQ ? k : kQ - 1]));
+            if (k >= kQ) break;  // the queue cannot hold more than its producer has channels
+            if (j < 0) {
+                if (__builtin_amdgcn_readfirstlane(lds_peek(&done[qc])) == 0) {
+                    __builtin_amdgcn_s_sleep(8);
+                    continue;
+                }
+                // the flag is raised after the last push: look once more, then the queue is known to be empty
+                j = __builtin_amdgcn_readfirstlane(lds_peek(&qj[qc][k]));
+                if (j < 0) break;
+            }
+            const float h0 = __builtin_bit_cast(float, __builtin_amdgcn_readfirstlane(lds_peek(reinterpret_cast<const int*>(&qh[qc][k]))));
+            const uint4* gp = reinterpret_cast<const uint4*>(e.gd + (size_t)j * 2 * d);
+            uint4 gv[NV], dv[NV];
+#pragma unroll
+            for (int r = 0; r < NV; ++r) gv[r] = gp[r * kWave + lane];
+#pragma unroll
+            for (int r = 0; r < NV; ++r) dv[r] = gp[(d / 8) + r * kWave + lane];
+            float g = 0.0f;
+#pragma unroll
+            for (int r = 0; r < NV; ++r) {
+                const uint4 xr = xlds[r * kWave + lane];
+                g = dot2(xr.x, gv[r].x, g);
+                g = dot2(xr.y, gv[r].y, g);
+                g = dot2(xr.z, gv[r].z, g);
+                g = dot2(xr.w, gv[r].w, g);
+            }
+            g = wave_allreduce_sum(g);
+            const float h = silu(g) * h0;
+#pragma unroll
+            for (int r = 0; r < NV; ++r) {
+                const uint32_t wds[4] = {dv[r].x, dv[r].y, dv[r].z, dv[r].w};
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const h16x2 pr = as_h2(wds[q]);
+                    acc[r * 8 + 2 * q + 0] = fmaf(h, (float)pr.x, acc[r * 8 + 2 * q + 0]);
+                    acc[r * 8 + 2 * q + 1] = fmaf(h, (float)pr.y, acc[r * 8 + 2 * q + 1]);
+                }
+            }
+            k += kFusedCpp;
+        }
+        // lane owns columns [(r * 64 + lane) * 8, + 8)
+#pragma unroll
+        for (int r = 0; r < NV; ++r) {
+            float4* o4 = reinterpret_cast<float4*>(&yred[c][(r * kWave + lane) * 8]);
+            o4[0] = make_float4(acc[r * 8 + 0], acc[r * 8 + 1], acc[r * 8 + 2], acc[r * 8 + 3]);
+            o4[1] = make_float4(acc[r * 8 + 4], acc[r * 8 + 5], acc[r * 8 + 6], acc[r * 8 + 7]);
+        }
+        FLOE_TL_AT(6, kFusedProducers * 64);
+    }
+    __syncthreads();
+    FLOE_TL(7);
+    // ---- the workgroup's partial y: consumers summed in a fixed order
+    float4* out = reinterpret_cast<float4*>(partial + ((size_t)task * gridDim.x + blockIdx.x) * d);
+    for (int c4 = tid; c4 < d / 4; c4 += kFusedThreads) {
+        float4 s = reinterpret_cast<const float4*>(&yred[0][0])[c4];
+#pragma unroll
+        for (int c = 1; c < kFusedConsumers; ++c) {
+            const float4 a = reinterpret_cast<const float4*>(&yred[c][0])[c4];
+            s.x += a.x; s.y += a.y; s.z += a.z; s.w += a.w;
+        }
+        out[c4] = s;
+    }
+    if (tid == 0) wg_count[(size_t)task * gridDim.x + blockIdx.x] = n_sel;
+    FLOE_TL(8);
+}
+
+// ---- launch: bits fixed by the translation unit, the rest chosen here
+template <int BITS, int UPC, bool G32>
+static hipError_t fused_launch_shape(const FusedArgs& a, int gshift, hipStream_t stream) {
+    const dim3 grid(fused_blocks(a.d, a.f, a.passes), a.n_tasks), block(kFusedThreads);
+    const RouteArgs ro = a.route ? *a.route : RouteArgs{};
+    constexpr int kDepth = BITS == 2 ? 7 : 4;  // passes in flight per producer wave (registers: 6 / 8 / 10 per pass)
+#define FLOE_FUSED_GO(ROUTED, P)                                                                                 \
+    fused_ffn_kernel<BITS, UPC, G32, ROUTED, P, kDepth><<<grid, block, 0, stream>>>(a.map, a.x, ro, a.task_tau,   \
+                                                                                    a.task_scale, a.f, gshift,    \
+                                                                                    a.v_out, a.partial, a.wg_count)
+#define FLOE_FUSED_PASSES(ROUTED)                                               \
+    switch (a.passes) {                                                         \
+        case fused_passes_long: FLOE_FUSED_GO(ROUTED, fused_passes_long); break; \
+        case fused_passes_mid: FLOE_FUSED_GO(ROUTED, fused_passes_mid); break;   \
+        case fused_passes_short: FLOE_FUSED_GO(ROUTED, fused_passes_short); break; \
+        default: return hipErrorInvalidValue;                                   \
+    }
+    if (a.route) {
+        if constexpr (BITS == 2 && !G32) {
+            FLOE_FUSED_PASSES(true)
+        } else {
+            return hipErrorInvalidValue;
+        }
+    } else {
+        FLOE_FUSED_PASSES(false)
+    }
+#undef FLOE_FUSED_PASSES
+#undef FLOE_FUSED_GO
+    return hipGetLastError();
+}
+
+template <int BITS>
+static hipError_t fused_launch_bits(const FusedArgs& a, hipStream_t stream) {
+    if (a.f == 0 || a.n_tasks == 0) return hipSuccess;
+    int gshift = 0;
+    while ((1 << gshift) < a.group) ++gshift;
+    const bool g32 = a.group == 32;
+    switch (a.d) {
+        case 4096: return g32 ? fused_launch_shape<BITS, 64, true>(a, gshift, stream) : fused_launch_shape<BITS, 64, false>(a, gshift, stream);
+        case 2048: return g32 ? fused_launch_shape<BITS, 32, true>(a, gshift, stream) : fused_launch_shape<BITS, 32, false>(a, gshift, stream);
+        case 1024: return g32 ? fused_launch_shape<BITS, 16, true>(a, gshift, stream) : fused_launch_shape<BITS, 16, false>(a, gshift, stream);
+        default: return hipErrorInvalidValue;
+    }
+}
+
+}  // namespace floe

@@ -34,13 +34,29 @@ inline bool route_in_place_ok(int d, int bits, int group, int n_experts, int top
            top_k + n_shared <= 16;
 }
 
-// S1-S5 of a small decode batch in one kernel (shapes of route_in_place_ok): every workgroup routes, computes v
-// for its own block of channels, selects among them and runs gate/down on what it selected.
-// partial[task][fused_blocks][d], wg_count[task][fused_blocks] (selected channels per workgroup).
-int fused_blocks(int d, int f);
-constexpr int kFusedMaxTasks = 16;  // beyond this the partial results outgrow what the fusion saves
-hipError_t launch_fused_layer(const TaskMap& map, const h16* x, const RouteArgs& route, float* partial,
-                              int32_t* wg_count, int d, int f, int group, int n_tasks, hipStream_t stream);
+// (S1 +) S2-S5 of a small decode batch in one kernel (packed shapes, any bit width): every workgroup computes v for
+// its own block of channels, selects among them and runs gate/down on what it selected (fused_ffn.h).
+// With `route` the workgroup also routes in place (shapes of route_in_place_ok); otherwise map / task_tau /
+// task_scale describe the tasks.  partial[task][blocks][d], wg_count[task][blocks] (selected channels per
+// workgroup), v_out (optional) [task][f].
+constexpr int fused_producers = 4;                          // producer waves per workgroup
+constexpr int fused_passes_long = 28, fused_passes_mid = 14, fused_passes_short = 7;  // channel passes per producer wave
+constexpr int kFusedMaxTasks = 16;        // beyond these the partial results outgrow what the fusion saves
+constexpr int kFusedMaxWorkgroups = 2048;
+struct FusedArgs {
+    TaskMap map;
+    const h16* x;
+    const RouteArgs* route;
+    const float* task_tau;
+    const float* task_scale;
+    float* v_out;
+    float* partial;
+    int32_t* wg_count;
+    int d, f, group, n_tasks, passes;
+};
+int fused_passes(int d, int f, int n_tasks);  // 0: not fused
+int fused_blocks(int d, int f, int passes);
+hipError_t launch_fused(const FusedArgs& a, int bits, hipStream_t stream);
 
 // S2 for decode batches on the matrix cores: tokens routed to the same expert share one pass over its codes.
 struct TokenGroup {

@@ -116,6 +116,20 @@ def test_layer_top_k_equals_all_experts():
     _run_layer_case(13, 3, 1024, 768, 2, 64, 4, 0, 4, True, 2, 50)
 
 
+def test_layer_small_batches_through_the_fused_kernel():
+    # INT2, group >= 64, <= 16 experts and <= 16 (token, slot) tasks: router, GEMV, selection and gate/down run in
+    # one kernel.  Ragged f (last workgroup and last producer wave partly empty), every supported d, shared experts,
+    # a queue filled to its capacity (0 %: every channel selected) and a nearly empty one (99 %).
+    _run_layer_case(21, 3, 2048, 901, 2, 128, 5, 1, 2, False, 3, 75)
+    _run_layer_case(22, 3, 4096, 300, 2, 64, 16, 0, 4, True, 2, 60)
+    _run_layer_case(23, 3, 4096, 250, 2, 256, 3, 0, 1, False, 2, 0)
+    _run_layer_case(24, 3, 1024, 1500, 2, 64, 8, 0, 2, True, 8, 99)
+    # other bit widths and more than 16 experts: the router runs as a kernel of its own in front of the fused one
+    _run_layer_case(25, 5, 2048, 1408, 3, 32, 16, 2, 6, False, 2, 85)
+    _run_layer_case(26, 5, 1024, 700, 4, 32, 20, 1, 3, True, 3, 70)
+    _run_layer_case(27, 3, 4096, 200, 3, 128, 4, 0, 2, True, 1, 50)
+
+
 def test_layer_batches_through_the_matrix_core_gemv():
     """Decode batches group the tokens of an expert (chunks of 16) and run S2 on the matrix cores:
     INT4 / INT2, groups of 32 and 64, more than 16 tokens per expert, ragged f."""

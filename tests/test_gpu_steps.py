@@ -208,6 +208,31 @@ def test_expert_ffn_sparse_matches_oracle(d, f, bits, group, T, pcts):
             assert np.all(np.abs(y[t] - y_ref) <= G.Y_BAR * np.abs(y_ref).max() + slack)
 
 
+@pytest.mark.parametrize("d,f,bits,group,T", [(4096, 530, 2, 64, 3), (2048, 1000, 3, 32, 2), (1024, 300, 4, 128, 17),
+                                              (512, 400, 2, 64, 2)])
+def test_expert_ffn_without_a_list_gives_the_same_result(d, f, bits, group, T):
+    """idx = count = NULL: the same y, whether the list is skipped (small batches of packed shapes) or built in the workspace."""
+    G = _gc()
+    import paper_2505_05950_amd as F
+    ex_np, ex_dev, x = _expert_case(12, 57, d, f, bits, group, T)
+    v_ref = [O.up_gemv(*ex_np[:3], d, bits, group, x[t]) for t in range(T)]
+    tau = np.array([O.threshold_for_sparsity(v_ref[t], 80) * 1.002 for t in range(T)], np.float32)
+    scale = G.dev(np.linspace(0.5, 1.5, T).astype(np.float32))
+    y1 = torch.zeros((T, d), dtype=torch.float32, device=G.DEV)
+    y2 = torch.zeros((T, d), dtype=torch.float32, device=G.DEV)
+    y1, idx, count = F.floe_expert_ffn_sparse(ex_dev, G.dev(x), G.dev(tau), scale, y1)
+    y2, none_idx, none_count = F.floe_expert_ffn_sparse(ex_dev, G.dev(x), G.dev(tau), scale, y2, want_list=False)
+    torch.cuda.synchronize()
+    assert none_idx is None and none_count is None
+    assert torch.equal(y1, y2)
+    y1, idx, count = y1.cpu().numpy().astype(np.float64), idx.cpu().numpy(), count.cpu().numpy()
+    for t in range(T):
+        got = idx[t, : count[t]]
+        G.check_index_set(got, v_ref[t], float(tau[t]))
+        w = 0.5 + t / max(T - 1, 1)
+        assert G.rel_err(y1[t], w * O.sparse_ffn(ex_np[3], x[t], v_ref[t], got)[1]) <= G.Y_TIGHT
+
+
 def test_expert_ffn_with_more_than_65536_channels_uses_the_select_kernel():
     """Lists longer than 2048 mask words are compacted by the stand-alone select kernel; same results."""
     G = _gc()
