@@ -371,53 +371,138 @@ def bench_expert(args, np, torch, S, FL, dev):
 
 
 def bench_stage(args, np, torch, S, FL, dev):
-    """Transfer experiment of Sec. 4.1 (random 20 % of one expert's channels, 20 trials) plus the 10 % case of
-    the decode path: selected [gate | down] chunks from pinned host memory to HBM with floe_stage_channels,
-    beside a plain pinned hipMemcpy of the same number of bytes."""
+    """Transfer experiment of Sec. 4.1 / Sec. 3.4.2 (random 20 % of one expert's channels, 20 trials) plus the 10 %
+    case of the decode path.  Selected channels go from pinned host memory to HBM by
+      gather_compact : floe_stage_channels on the compact [gate | down] layout (one 4d-byte chunk per channel),
+      gather_split   : the same kernel on two separate matrices (two 2d-byte chunks per channel: no compact layout),
+      gather_chunk_* : the same bytes cut into smaller chunks (8 KiB, 4 KiB),
+      cpu_pack       : rows packed by the host's threads into a pinned buffer, then one asynchronous copy
+                       (the list has to come back to the host first; timed with and without that),
+      per_row_copies : one asynchronous copy per selected chunk (the naive way),
+    beside one plain pinned copy of the same number of bytes."""
     trials = 20
     _, gd = S.expert_weights(SEED, 4, D, F_INT)
     host = torch.from_numpy(gd).pin_memory()
+    host_gate = torch.from_numpy(np.ascontiguousarray(gd[:, 0, :])).pin_memory()
+    host_down = torch.from_numpy(np.ascontiguousarray(gd[:, 1, :])).pin_memory()
     side = torch.cuda.Stream()
+    torch.set_num_threads(max(1, min(16, os.cpu_count() or 1)))
+
+    def timed(fn, n=trials, warm=3):
+        ts = []
+        for tr in range(n + warm):
+            prep = fn(tr, None)
+            torch.cuda.synchronize()
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            t0 = time.perf_counter()
+            a.record(side)
+            fn(tr, prep)
+            b.record(side)
+            b.synchronize()
+            wall = (time.perf_counter() - t0) * 1e3
+            if tr >= warm:
+                ts.append((a.elapsed_time(b), wall))
+        return float(np.mean([t[0] for t in ts])), float(np.mean([t[1] for t in ts]))
+
     out = []
     for frac in (0.2, 0.1):
         Ksel = int(F_INT * frac)
+        nbytes = Ksel * 4 * D
         dst = torch.empty((Ksel, 2, D), dtype=torch.float16, device=dev)
         cnt = torch.tensor([Ksel], dtype=torch.int32, device=dev)
-        times = []
-        for tr in range(trials + 3):
-            sel = S.random_channel_subset(SEED, 4, F_INT, Ksel, salt=tr)
-            idx = torch.from_numpy(sel).to(dev)
-            torch.cuda.synchronize()
-            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            a.record(side)
+        res = {"fraction": frac, "channels": Ksel, "bytes": nbytes}
+
+        def sel_dev(tr):
+            return torch.from_numpy(S.random_channel_subset(SEED, 4, F_INT, Ksel, salt=tr)).to(dev)
+
+        # --- gather kernel, compact layout
+        def gather_compact(tr, idx):
+            if idx is None:
+                return sel_dev(tr)
             FL.floe_stage_channels(host, idx, cnt, Ksel, dst, None, side, None)
-            b.record(side)
-            b.synchronize()
-            if tr >= 3:
-                times.append(a.elapsed_time(b))
-        nbytes = Ksel * 4 * D
-        # plain contiguous pinned copy of the same size
+        ms, _ = timed(gather_compact)
+        res["gather_compact_GBps"] = round(nbytes / ms / 1e6, 2)
+
+        # --- gather kernel, gate and down in two matrices
+        dst_g = torch.empty((Ksel, 2, D // 2), dtype=torch.float16, device=dev)
+        dst_d = torch.empty((Ksel, 2, D // 2), dtype=torch.float16, device=dev)
+        hg, hd = host_gate.view(F_INT, 2, D // 2), host_down.view(F_INT, 2, D // 2)
+
+        def gather_split(tr, idx):
+            if idx is None:
+                return sel_dev(tr)
+            FL.floe_stage_channels(hg, idx, cnt, Ksel, dst_g, None, side, None)
+            FL.floe_stage_channels(hd, idx, cnt, Ksel, dst_d, None, side, None)
+        ms, _ = timed(gather_split)
+        res["gather_split_GBps"] = round(nbytes / ms / 1e6, 2)
+
+        # --- gather kernel, smaller chunks: the matrix seen as [f * c][2][d / c], c x as many rows selected
+        for c in (2, 4):
+            hv = host.view(F_INT * c, 2, D // c)
+            dstc = torch.empty((Ksel * c, 2, D // c), dtype=torch.float16, device=dev)
+            cntc = torch.tensor([Ksel * c], dtype=torch.int32, device=dev)
+
+            def gather_chunk(tr, idx, c=c, hv=hv, dstc=dstc, cntc=cntc):
+                if idx is None:
+                    base = S.random_channel_subset(SEED, 4, F_INT, Ksel, salt=tr).astype(np.int64)
+                    fine = (base[:, None] * c + np.arange(c)[None, :]).reshape(-1).astype(np.int32)
+                    return torch.from_numpy(fine).to(dev)
+                FL.floe_stage_channels(hv, idx, cntc, Ksel * c, dstc, None, side, None)
+            ms, _ = timed(gather_chunk)
+            res[f"gather_chunk_{16 // c}KiB_GBps"] = round(nbytes / ms / 1e6, 2)
+
+        # --- host threads pack into pinned memory, one copy
+        packed = torch.empty((Ksel, 2, D), dtype=torch.float16).pin_memory()
+
+        def cpu_pack(tr, idx):
+            if idx is None:
+                return sel_dev(tr)
+            idx_h = idx.cpu().long()                    # the list lives on the device: it has to come back first
+            torch.index_select(host, 0, idx_h, out=packed)
+            with torch.cuda.stream(side):
+                dst.copy_(packed, non_blocking=True)
+        _, wall = timed(cpu_pack, n=10)
+        res["cpu_pack_GBps"] = round(nbytes / wall / 1e6, 2)
+
+        def cpu_pack_list_on_host(tr, idx_h):
+            if idx_h is None:
+                return torch.from_numpy(S.random_channel_subset(SEED, 4, F_INT, Ksel, salt=tr)).long()
+            torch.index_select(host, 0, idx_h, out=packed)
+            with torch.cuda.stream(side):
+                dst.copy_(packed, non_blocking=True)
+        _, wall = timed(cpu_pack_list_on_host, n=10)
+        res["cpu_pack_list_on_host_GBps"] = round(nbytes / wall / 1e6, 2)
+
+        # --- one copy per chunk
+        def per_row(tr, idx_h):
+            if idx_h is None:
+                return S.random_channel_subset(SEED, 4, F_INT, Ksel, salt=tr).tolist()
+            with torch.cuda.stream(side):
+                for k, j in enumerate(idx_h):
+                    dst[k].copy_(host[j], non_blocking=True)
+        _, wall = timed(per_row, n=3, warm=1)
+        res["per_row_copies_GBps"] = round(nbytes / wall / 1e6, 2)
+
+        # --- plain contiguous pinned copy of the same size
         flat = host.view(-1)[: nbytes // 2]
         dflat = torch.empty_like(flat, device=dev)
-        ctimes = []
-        for tr in range(trials + 3):
-            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+
+        def plain(tr, prep):
+            if prep is None:
+                return 1
             with torch.cuda.stream(side):
-                a.record(side)
                 dflat.copy_(flat, non_blocking=True)
-                b.record(side)
-            b.synchronize()
-            if tr >= 3:
-                ctimes.append(a.elapsed_time(b))
-        ms, cms = float(np.mean(times)), float(np.mean(ctimes))
-        out.append({"fraction": frac, "channels": Ksel, "bytes": nbytes, "stage_ms": round(ms, 4),
-                    "stage_GBps": round(nbytes / ms / 1e6, 2), "memcpy_ms": round(cms, 4),
-                    "memcpy_GBps": round(nbytes / cms / 1e6, 2), "frac_of_memcpy": round(cms / ms, 3)})
-        log(f"[bench] stage {frac:.0%}: {ms:.3f} ms ({out[-1]['stage_GBps']} GB/s) vs pinned memcpy {cms:.3f} ms ({out[-1]['memcpy_GBps']} GB/s)")
-    print(json.dumps({"metric": "host->HBM GB/s for selected channel chunks (compact layout)", "value": out[0]["stage_GBps"],
+        ms, _ = timed(plain)
+        res["memcpy_GBps"] = round(nbytes / ms / 1e6, 2)
+        res["gather_compact_frac_of_memcpy"] = round(res["gather_compact_GBps"] / res["memcpy_GBps"], 3)
+        out.append(res)
+        log(f"[bench] stage {frac:.0%}: " + ", ".join(f"{k}={v}" for k, v in res.items() if k.endswith("GBps")))
+    print(json.dumps({"metric": "host->HBM GB/s for selected channel chunks (compact layout)", "value": out[0]["gather_compact_GBps"],
                       "unit": "GB/s", "n_gpus": 1, "higher_is_better": True, "data": "synthetic",
                       "config": {"workload": "one Mixtral-shaped expert's [gate|down] matrix in pinned host memory, random "
-                                             "20 % / 10 % of channels, 20 trials each (Sec. 4.1 protocol)"},
+                                             "20 % / 10 % of channels, 20 trials each (Sec. 4.1 protocol); kernel-gather timed "
+                                             "with hipEvents on the side stream, host-driven variants by wall clock",
+                                 "host_threads": torch.get_num_threads()},
                       "results": out}), flush=True)
 
 
@@ -455,6 +540,16 @@ def bench_stack(args, np, torch, S, FL, dev):
             c, s_, zz = (t.clone() for t in base[e][0])
             experts.append(FL.Expert(D, F_INT, BITS, GROUP, c, s_, zz, pinned[l % pool][e]))
         layers.append(FL.Layer(experts, 0, TOP_K, True, wr_dev.clone(), tau_e, False, gd_on_host=True))
+    # resident twins of the layers for the VRAM-budget sweep (Sec. 4.2: more memory = more layers kept whole in HBM);
+    # they alias a small pool of device copies: 4 x 1.88 GB is beyond any cache, HBM reads are what they would be
+    pool_dev = 4
+    gd_dev = [[torch.from_numpy(base[e][1]).to(dev) for e in range(N_EXPERTS)] for _ in range(pool_dev)]
+    layers_res = []
+    for l in range(n_layers):
+        ex = layers[l].experts
+        experts = [FL.Expert(D, F_INT, BITS, GROUP, ex[e].up_codes, ex[e].up_scale, ex[e].up_zero, gd_dev[l % pool_dev][e])
+                   for e in range(N_EXPERTS)]
+        layers_res.append(FL.Layer(experts, 0, TOP_K, True, layers[l].router_cm, tau_e, False))
     cap = 2048
     staging = torch.empty((TOP_K, cap, 2, D), dtype=torch.float16, device=dev)
     overflow = torch.zeros((TOP_K,), dtype=torch.int32, device=dev)
@@ -462,27 +557,44 @@ def bench_stack(args, np, torch, S, FL, dev):
     side = torch.cuda.Stream()
     ev_a, ev_b = torch.cuda.Event(), torch.cuda.Event()
     ws = layers[0].workspace(1)
+    ws_res = layers_res[0].workspace(1)
     y = torch.empty((1, D), dtype=torch.float16, device=dev)
     toks = torch.from_numpy(S.tokens(SEED, 4, n_tok + n_warm, D, layer=9)).to(dev)
-    lat, staged, ovf = [], [], 0
-    for i in range(n_tok + n_warm):
-        x = toks[i:i + 1].contiguous()
-        torch.cuda.synchronize()
-        t1 = time.perf_counter()
-        for l in range(n_layers):
-            FL.floe_moe_layer_decode_offloaded(layers[l], x, staging, cap, side, ev_a, ev_b, y=y, stats=stats[l],
-                                               overflow=overflow, workspace=ws)
-            yf = y.float()
-            x = (yf / yf.std()).half()
-        torch.cuda.synchronize()
-        dt = time.perf_counter() - t1
-        ovf += int(overflow.sum().item())
-        if i >= n_warm:
-            lat.append(dt)
-            ks = stats.cpu().numpy().reshape(n_layers, TOP_K, 4)[:, :, 1]
-            staged.append(int(np.minimum(ks, cap).sum()) * 4 * D)
-    ms = float(np.mean(lat)) * 1e3
-    nbytes = float(np.mean(staged))
+    layer_gb = N_EXPERTS * F_INT * 2 * D * 2 / 1e9
+    fixed_gb = (n_layers * N_EXPERTS * (D * F_INT * BITS // 8 + 4 * F_INT * (D // GROUP)) + staging.numel() * 2) / 1e9
+
+    def run(n_res):
+        """n_res leading layers resident, the rest offloaded; returns (ms per token, staged bytes per token, overflows)"""
+        lat, staged, ovf = [], [], 0
+        for i in range(n_tok + n_warm):
+            x = toks[i:i + 1].contiguous()
+            torch.cuda.synchronize()
+            t1 = time.perf_counter()
+            for l in range(n_layers):
+                if l < n_res:
+                    FL.floe_moe_layer_decode(layers_res[l], x, y, stats[l], ws_res)
+                else:
+                    FL.floe_moe_layer_decode_offloaded(layers[l], x, staging, cap, side, ev_a, ev_b, y=y, stats=stats[l],
+                                                       overflow=overflow, workspace=ws)
+                yf = y.float()
+                x = (yf / yf.std()).half()
+            torch.cuda.synchronize()
+            dt = time.perf_counter() - t1
+            ovf += int(overflow.sum().item())
+            if i >= n_warm:
+                lat.append(dt)
+                ks = stats.cpu().numpy().reshape(n_layers, TOP_K, 4)[n_res:, :, 1]
+                staged.append(int(np.minimum(ks, cap).sum()) * 4 * D)
+        return float(np.mean(lat)) * 1e3, float(np.mean(staged)), ovf
+
+    ms, nbytes, ovf = run(0)
+    sweep = []
+    for budget in (12, 16, 20, 24, 32, 48, 66):
+        n_res = int(max(0, min(n_layers, (budget - fixed_gb) // layer_gb)))
+        b_ms, b_bytes, _ = run(n_res)
+        sweep.append({"vram_budget_GB": budget, "resident_layers": n_res, "ms_per_token": round(b_ms, 3),
+                      "tokens_per_s": round(1e3 / b_ms, 1), "staged_MB_per_token": round(b_bytes / 1e6, 1)})
+        log(f"[bench] budget {budget} GB: {n_res} layers resident, {b_ms:.2f} ms/token, {b_bytes / 1e6:.0f} MB staged")
     # plain pinned copy of the same volume for reference
     flat = pinned[0][0].view(-1)
     dflat = torch.empty((flat.numel(),), dtype=torch.float16, device=dev)
@@ -500,8 +612,8 @@ def bench_stack(args, np, torch, S, FL, dev):
                                  "overflowed_lists": ovf},
                       "staged_bytes_per_token": int(nbytes), "staged_GBps": round(nbytes / (ms * 1e-3) / 1e9, 2),
                       "pinned_memcpy_GBps": round(peak, 2), "tokens_per_s": round(1e3 / ms, 2),
-                      "resident_hbm_GB": round((n_layers * N_EXPERTS * (D * F_INT * BITS // 8 + 4 * F_INT * (D // GROUP))
-                                                + staging.numel() * 2) / 1e9, 2)}), flush=True)
+                      "resident_hbm_GB": round(fixed_gb, 2),
+                      "vram_budget_sweep": sweep}), flush=True)
 
 
 def bench_batch(args, np, torch, S, FL, dev):
