@@ -214,6 +214,59 @@ int floe_moe_layer_decode_offloaded(const floe_layer* L, const floe_offload* o, 
                                     floe_slot_stat* stats, void* workspace, size_t workspace_bytes, void* stream);
 
 /* ------------------------------------------------------------------------------------------------
+ * Prefetching the next layer (intra-expert reuse, Sec. 3.3 and Fig. 1(c)): hidden states of neighbouring layers are
+ * alike, so the router and the up projection of layer i + 1 applied to the input of layer i predict which experts
+ * layer i + 1 will route to and which of their channels will pass the threshold.
+ *
+ * floe_moe_layer_prefetch: on p->prefetch_stream, after everything enqueued on `stream` so far (x_cur is valid there):
+ *   router, up GEMV and selection of layer L on x_cur; the selected chunks of every predicted (token, slot) are copied
+ *   from pinned host memory into slab q = token * slots + slot of p->staging (at most capacity_rows each);
+ *   p->pred_expert[q], p->pred_count[q] and p->row_of[q][j] (staging row of channel j, -1 = not staged) describe them;
+ *   p->ev_prefetched is recorded when all of that is in place.  workspace: floe_layer_workspace_bytes(L, T), NOT the
+ *   one a decode call may be using at the same time.
+ * floe_moe_layer_decode_prefetched: the layer's real input x on `stream`: router, up GEMV, selection; then, per
+ *   (token, slot): the predicted slab of the same token that holds the same expert is reused - its hits stay where they
+ *   are, the misses get fresh rows behind them - and an expert that was not predicted takes a spare slab
+ *   (p->staging has 2 * T * slots slabs).  Only the misses cross the bus (m->miss_stream); gate/down and combine follow
+ *   on `stream`.  Results are identical to floe_moe_layer_decode_offloaded unless a slab overflows
+ *   (m->overflow[q] = 1: channels without a row are left out).  prefetch_stats: dev [T * slots] or NULL.
+ * Buffers: staging dev [2 * T * slots][capacity_rows][2][d]; pred_expert, pred_count dev [T * slots];
+ * row_of dev [T * slots][f]; events are hipEvent_t owned by the caller; two floe_prefetch objects alternate between
+ * neighbouring layers.
+ */
+typedef struct {
+    floe_half* staging;
+    int32_t capacity_rows;
+    int32_t* pred_expert;
+    int32_t* pred_count;
+    int32_t* row_of;
+    void* prefetch_stream;
+    void* ev_inputs_ready;
+    void* ev_prefetched;
+} floe_prefetch;
+
+typedef struct {
+    void* miss_stream;
+    void* ev_lists_ready;
+    void* ev_staged;
+    int32_t* overflow; /* dev [T * slots] or NULL */
+} floe_miss_path;
+
+typedef struct {
+    int32_t expert_predicted; /* 1: a predicted slab of the token held this expert */
+    int32_t predicted;        /* channels that were staged ahead for it */
+    int32_t hits;             /* selected channels found among them */
+    int32_t misses;           /* selected channels that had to be copied now */
+} floe_prefetch_stat;
+
+int floe_moe_layer_prefetch(const floe_layer* L, const floe_prefetch* p, const floe_half* x_cur, int T, void* workspace,
+                            size_t workspace_bytes, void* stream);
+int floe_moe_layer_decode_prefetched(const floe_layer* L, const floe_prefetch* p, const floe_miss_path* m,
+                                     const floe_half* x, int T, floe_half* y, floe_slot_stat* stats,
+                                     floe_prefetch_stat* prefetch_stats, void* workspace, size_t workspace_bytes,
+                                     void* stream);
+
+/* ------------------------------------------------------------------------------------------------
  * S7 -- Sec. 3.4.2 (compact asynchronous transfer), done the MI355X way: a copy kernel on a side
  * stream reads the selected 4*d-byte [gate | down] chunks straight out of pinned, device-mapped host
  * memory, so the device-resident index list never travels to the host.

@@ -44,6 +44,17 @@ class _Offload(C.Structure):
                 ("side_stream", C.c_void_p), ("ev_lists_ready", C.c_void_p), ("ev_staged", C.c_void_p)]
 
 
+class _Prefetch(C.Structure):
+    _fields_ = [("staging", C.c_void_p), ("capacity_rows", C.c_int32), ("pred_expert", C.c_void_p),
+                ("pred_count", C.c_void_p), ("row_of", C.c_void_p), ("prefetch_stream", C.c_void_p),
+                ("ev_inputs_ready", C.c_void_p), ("ev_prefetched", C.c_void_p)]
+
+
+class _MissPath(C.Structure):
+    _fields_ = [("miss_stream", C.c_void_p), ("ev_lists_ready", C.c_void_p), ("ev_staged", C.c_void_p),
+                ("overflow", C.c_void_p)]
+
+
 def lib_path() -> str:
     return os.path.join(_HERE, _LIB_NAME)
 
@@ -78,6 +89,9 @@ def load():
     lib.floe_layer_workspace_bytes.argtypes = [C.POINTER(_Layer), i32]
     lib.floe_moe_layer_decode.argtypes = [C.POINTER(_Layer), vp, i32, vp, vp, vp, sz, vp]
     lib.floe_moe_layer_decode_offloaded.argtypes = [C.POINTER(_Layer), C.POINTER(_Offload), vp, i32, vp, vp, vp, sz, vp]
+    lib.floe_moe_layer_prefetch.argtypes = [C.POINTER(_Layer), C.POINTER(_Prefetch), vp, i32, vp, sz, vp]
+    lib.floe_moe_layer_decode_prefetched.argtypes = [C.POINTER(_Layer), C.POINTER(_Prefetch), C.POINTER(_MissPath), vp, i32,
+                                                     vp, vp, vp, vp, sz, vp]
     lib.floe_stage_channels.argtypes = [vp, i32, i32, vp, vp, i32, vp, vp, vp, vp]
     _lib = lib
     return lib
@@ -251,6 +265,10 @@ class Layer:
         self._c.tau = tau.data_ptr()
         self._c.tau_stride_t = self.tau_stride
 
+    def new_workspace(self, T: int) -> torch.Tensor:
+        """A workspace of its own (e.g. for a prefetch that runs beside a decode call)."""
+        return _workspace(floe_layer_workspace_bytes(self, T), self.tau.device)
+
     def workspace(self, T: int) -> torch.Tensor:
         if T not in self._ws:
             self._ws[T] = _workspace(floe_layer_workspace_bytes(self, T), self.tau.device)
@@ -300,6 +318,68 @@ def floe_moe_layer_decode_offloaded(L: Layer, x, staging, capacity_rows, side_st
                    side_stream.cuda_stream, ev_lists_ready.cuda_event, ev_staged.cuda_event)
     _check(load().floe_moe_layer_decode_offloaded(C.byref(L._c), C.byref(off), _ptr(x), T, _ptr(y), _ptr(stats), wp, wn,
                                                   _stream(stream)), "floe_moe_layer_decode_offloaded")
+    return y
+
+
+PREFETCH_STAT_DTYPE = np.dtype([("expert_predicted", np.int32), ("predicted", np.int32), ("hits", np.int32),
+                                ("misses", np.int32)])
+
+
+class Prefetch:
+    """Buffers and events of one floe_prefetch object (two of them alternate between neighbouring layers):
+    staging [2*T*slots][capacity][2][d], predicted expert / count per task, row map [T*slots][f]."""
+
+    def __init__(self, L: "Layer", T: int, capacity_rows: int, prefetch_stream, device=None):
+        dev = device if device is not None else L.tau.device
+        slots = L.top_k + L.n_shared
+        n = T * slots
+        self.T, self.capacity_rows, self.stream = T, int(capacity_rows), prefetch_stream
+        self.staging = torch.empty((2 * n, capacity_rows, 2, L.d), dtype=torch.float16, device=dev)
+        self.pred_expert = torch.full((n,), -1, dtype=torch.int32, device=dev)
+        self.pred_count = torch.zeros((n,), dtype=torch.int32, device=dev)
+        self.row_of = torch.full((n, L.f), -1, dtype=torch.int32, device=dev)
+        self.ev_inputs_ready, self.ev_prefetched = torch.cuda.Event(), torch.cuda.Event()
+        # torch creates the hipEvent_t lazily on the first record(); after this the library alone records them
+        self.ev_inputs_ready.record(torch.cuda.current_stream())
+        self.ev_prefetched.record(prefetch_stream)
+        self._c = _Prefetch(self.staging.data_ptr(), self.capacity_rows, self.pred_expert.data_ptr(),
+                            self.pred_count.data_ptr(), self.row_of.data_ptr(), prefetch_stream.cuda_stream,
+                            self.ev_inputs_ready.cuda_event, self.ev_prefetched.cuda_event)
+
+
+class MissPath:
+    """Stream and events on which the channels that were not predicted are copied."""
+
+    def __init__(self, miss_stream, n_tasks: int, device):
+        self.stream = miss_stream
+        self.overflow = torch.zeros((n_tasks,), dtype=torch.int32, device=device)
+        self.ev_lists_ready, self.ev_staged = torch.cuda.Event(), torch.cuda.Event()
+        self.ev_lists_ready.record(torch.cuda.current_stream())
+        self.ev_staged.record(miss_stream)
+        self._c = _MissPath(miss_stream.cuda_stream, self.ev_lists_ready.cuda_event, self.ev_staged.cuda_event,
+                            self.overflow.data_ptr())
+
+
+def floe_moe_layer_prefetch(L: Layer, P: Prefetch, x_cur, workspace, stream=None):
+    """Predicts layer L's experts and channels from x_cur and copies their chunks ahead (on P.stream)."""
+    T = x_cur.shape[0]
+    wp, wn = _aligned_ptr(workspace)
+    _check(load().floe_moe_layer_prefetch(C.byref(L._c), C.byref(P._c), _ptr(x_cur), T, wp, wn, _stream(stream)),
+           "floe_moe_layer_prefetch")
+
+
+def floe_moe_layer_decode_prefetched(L: Layer, P: Prefetch, M: MissPath, x, y=None, stats=None, prefetch_stats=None,
+                                     workspace=None, stream=None):
+    """Layer decode on staging rows that floe_moe_layer_prefetch has (partly) filled; only the misses are copied now."""
+    T = x.shape[0]
+    if y is None:
+        y = torch.empty((T, L.d), dtype=torch.float16, device=x.device)
+    if workspace is None:
+        workspace = L.workspace(T)
+    wp, wn = _aligned_ptr(workspace)
+    _check(load().floe_moe_layer_decode_prefetched(C.byref(L._c), C.byref(P._c), C.byref(M._c), _ptr(x), T, _ptr(y),
+                                                   _ptr(stats), _ptr(prefetch_stats), wp, wn, _stream(stream)),
+           "floe_moe_layer_decode_prefetched")
     return y
 
 

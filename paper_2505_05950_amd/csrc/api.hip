@@ -115,7 +115,7 @@ bool mask_path_ok(int f) { return mask_words_per_task(f) <= 2048; }
 // workspace of the layer: per-task table, counts, mask words, v, idx, partial
 struct LayerWs {
     size_t table_off, expert_off, weight_off, tau_off, count_off, mask_off, groups_off, ngroups_off, v_off, idx_off,
-        partial_off, total;
+        rows_off, missidx_off, missrows_off, misscount_off, partial_off, total;
     int n_tasks, nblk, nblk_fused, fused_passes;
 };
 LayerWs layer_ws(const floe_layer* L, int T) {
@@ -137,6 +137,12 @@ LayerWs layer_ws(const floe_layer* L, int T) {
     w.ngroups_off = o; o += align_up(4);
     w.v_off = o;      o += align_up((size_t)w.n_tasks * L->s.f * 4);
     w.idx_off = o;    o += align_up((size_t)w.n_tasks * L->s.f * 4);
+    // host-resident gate/down: row map and miss lists of the prefetched decode
+    const size_t per_list = L->gd_on_host ? align_up((size_t)w.n_tasks * L->s.f * 4) : 0;
+    w.rows_off = o;      o += per_list;
+    w.missidx_off = o;   o += per_list;
+    w.missrows_off = o;  o += per_list;
+    w.misscount_off = o; o += L->gd_on_host ? align_up((size_t)w.n_tasks * 4) : 0;
     w.partial_off = o; o += align_up((size_t)w.n_tasks * nblk_alloc * L->s.d * 4);
     w.total = o;
     return w;
@@ -153,6 +159,51 @@ int check_layer(const floe_layer* L) {
     if (L->top_k > 0 && !L->router_cm) return FLOE_EINVAL;
     if (!L->tau) return FLOE_EINVAL;
     if (L->tau_stride_t != 0 && L->tau_stride_t != L->n_experts + L->n_shared) return FLOE_EINVAL;
+    return FLOE_OK;
+}
+
+// S1-S3 of a layer as separate results in the workspace (offloaded paths need the index lists in memory):
+// task table / expert / weight / tau, v, idx, count.
+int layer_lists(const floe_layer* L, const LayerWs& w, char* base, const h16* xh, int T, hipStream_t st) {
+    DevExpert* task_table = reinterpret_cast<DevExpert*>(base + w.table_off);
+    int32_t* task_expert = reinterpret_cast<int32_t*>(base + w.expert_off);
+    float* task_weight = reinterpret_cast<float*>(base + w.weight_off);
+    float* task_tau = reinterpret_cast<float*>(base + w.tau_off);
+    int32_t* count = reinterpret_cast<int32_t*>(base + w.count_off);
+    float* v = reinterpret_cast<float*>(base + w.v_off);
+    int32_t* idx = reinterpret_cast<int32_t*>(base + w.idx_off);
+    TaskMap map{};
+    map.task_table = task_table;
+    map.slots = L->top_k + L->n_shared;
+    if (route_in_place_ok(L->s.d, L->s.bits, L->s.group, L->n_experts, L->top_k, L->n_shared)) {
+        RouteArgs ro;
+        ro.router_cm = reinterpret_cast<const h16*>(L->router_cm);
+        ro.tau = L->tau;
+        ro.tau_stride_t = L->tau_stride_t;
+        ro.n_experts = L->n_experts; ro.top_k = L->top_k; ro.n_shared = L->n_shared; ro.renormalize = L->renormalize;
+        ro.table = static_cast<const DevExpert*>(L->dev_table);
+        ro.task_table = task_table;
+        ro.task_expert = task_expert; ro.task_weight = task_weight; ro.task_tau = task_tau;
+        FLOE_LAUNCH(FLOE_KERNEL_UP_GEMV, st,
+                    launch_up_gemv(map, xh, &ro, v, nullptr, nullptr, L->s.d, L->s.f, L->s.bits, L->s.group,
+                                   w.n_tasks, st));
+    } else {
+        RouterArgs ra;
+        ra.router_cm = reinterpret_cast<const h16*>(L->router_cm);
+        ra.x = xh;
+        ra.tau = L->tau;
+        ra.tau_stride_t = L->tau_stride_t;
+        ra.n_experts = L->n_experts; ra.top_k = L->top_k; ra.n_shared = L->n_shared; ra.renormalize = L->renormalize;
+        ra.d = L->s.d;
+        ra.table = static_cast<const DevExpert*>(L->dev_table);
+        ra.task_table = task_table;
+        ra.task_expert = task_expert; ra.task_weight = task_weight; ra.task_tau = task_tau;
+        FLOE_LAUNCH(FLOE_KERNEL_ROUTER, st, launch_router(ra, T, st));
+        FLOE_LAUNCH(FLOE_KERNEL_UP_GEMV, st,
+                    launch_up_gemv(map, xh, nullptr, v, nullptr, nullptr, L->s.d, L->s.f, L->s.bits, L->s.group,
+                                   w.n_tasks, st));
+    }
+    FLOE_LAUNCH(FLOE_KERNEL_SELECT, st, launch_select(v, L->s.f, w.n_tasks, task_tau, idx, count, st));
     return FLOE_OK;
 }
 
@@ -173,7 +224,7 @@ const char* floe_status_string(int status) {
 }
 
 int floe_last_hip_error(void) { return g_last_hip_error; }
-int floe_abi_version(void) { return 2; }
+int floe_abi_version(void) { return 3; }
 
 int floe_profile_kernel(int kernel_id, void* start_event, void* stop_event) {
     if (kernel_id < 0 || kernel_id > FLOE_KERNEL_FUSED_FFN) return FLOE_EINVAL;
@@ -505,35 +556,7 @@ int floe_moe_layer_decode_offloaded(const floe_layer* L, const floe_offload* o, 
     TaskMap map{};
     map.task_table = task_table;
     map.slots = slots;
-    if (route_in_place_ok(L->s.d, L->s.bits, L->s.group, L->n_experts, L->top_k, L->n_shared)) {
-        RouteArgs ro;
-        ro.router_cm = reinterpret_cast<const h16*>(L->router_cm);
-        ro.tau = L->tau;
-        ro.tau_stride_t = L->tau_stride_t;
-        ro.n_experts = L->n_experts; ro.top_k = L->top_k; ro.n_shared = L->n_shared; ro.renormalize = L->renormalize;
-        ro.table = static_cast<const DevExpert*>(L->dev_table);
-        ro.task_table = task_table;
-        ro.task_expert = task_expert; ro.task_weight = task_weight; ro.task_tau = task_tau;
-        FLOE_LAUNCH(FLOE_KERNEL_UP_GEMV, st,
-                    launch_up_gemv(map, xh, &ro, v, nullptr, nullptr, L->s.d, L->s.f, L->s.bits, L->s.group,
-                                   w.n_tasks, st));
-    } else {
-        RouterArgs ra;
-        ra.router_cm = reinterpret_cast<const h16*>(L->router_cm);
-        ra.x = xh;
-        ra.tau = L->tau;
-        ra.tau_stride_t = L->tau_stride_t;
-        ra.n_experts = L->n_experts; ra.top_k = L->top_k; ra.n_shared = L->n_shared; ra.renormalize = L->renormalize;
-        ra.d = L->s.d;
-        ra.table = static_cast<const DevExpert*>(L->dev_table);
-        ra.task_table = task_table;
-        ra.task_expert = task_expert; ra.task_weight = task_weight; ra.task_tau = task_tau;
-        FLOE_LAUNCH(FLOE_KERNEL_ROUTER, st, launch_router(ra, T, st));
-        FLOE_LAUNCH(FLOE_KERNEL_UP_GEMV, st,
-                    launch_up_gemv(map, xh, nullptr, v, nullptr, nullptr, L->s.d, L->s.f, L->s.bits, L->s.group,
-                                   w.n_tasks, st));
-    }
-    FLOE_LAUNCH(FLOE_KERNEL_SELECT, st, launch_select(v, L->s.f, w.n_tasks, task_tau, idx, count, st));
+    if ((rc = layer_lists(L, w, base, xh, T, st))) return rc;
     FLOE_HIP(hipEventRecord((hipEvent_t)o->ev_lists_ready, st));
     FLOE_HIP(hipStreamWaitEvent(side, (hipEvent_t)o->ev_lists_ready, 0));
     FLOE_LAUNCH(FLOE_KERNEL_STAGE, side,
@@ -544,6 +567,94 @@ int floe_moe_layer_decode_offloaded(const floe_layer* L, const floe_offload* o, 
     FLOE_LAUNCH(FLOE_KERNEL_GATE_DOWN, st,
                 launch_gate_down(map, reinterpret_cast<const h16*>(o->staging), o->capacity_rows, xh, v, nullptr, idx,
                                  count, task_weight, partial, L->s.d, L->s.f, w.n_tasks, w.nblk, st));
+    FLOE_LAUNCH(FLOE_KERNEL_COMBINE, st,
+                launch_combine(partial, L->s.d, T, slots, w.nblk, nullptr, reinterpret_cast<h16*>(y), st));
+    if (stats) FLOE_HIP(launch_stats(task_expert, count, 0, task_weight, reinterpret_cast<SlotStat*>(stats), w.n_tasks, st));
+    return FLOE_OK;
+}
+
+int floe_moe_layer_prefetch(const floe_layer* L, const floe_prefetch* p, const floe_half* x_cur, int T, void* workspace,
+                            size_t workspace_bytes, void* stream) {
+    int rc = check_layer(L);
+    if (rc) return rc;
+    if ((rc = check_T(T))) return rc;
+    if (T == 0) return FLOE_OK;
+    if (!p || !p->staging || !p->pred_expert || !p->pred_count || !p->row_of || !p->ev_inputs_ready || !p->ev_prefetched ||
+        p->capacity_rows <= 0)
+        return FLOE_EINVAL;
+    if (!L->dev_table || !L->gd_on_host || !x_cur || !workspace) return FLOE_EINVAL;
+    if (!aligned(x_cur, 16) || !aligned(workspace, kAlign) || !aligned(p->staging, 16)) return FLOE_EINVAL;
+    const LayerWs w = layer_ws(L, T);
+    if (workspace_bytes < w.total) return FLOE_EWORKSPACE;
+    char* base = static_cast<char*>(workspace);
+    hipStream_t st = (hipStream_t)stream, side = (hipStream_t)p->prefetch_stream;
+    // everything below runs on the prefetch stream, after whatever produced x_cur on `stream`
+    FLOE_HIP(hipEventRecord((hipEvent_t)p->ev_inputs_ready, st));
+    FLOE_HIP(hipStreamWaitEvent(side, (hipEvent_t)p->ev_inputs_ready, 0));
+    if ((rc = layer_lists(L, w, base, reinterpret_cast<const h16*>(x_cur), T, side))) return rc;
+    const DevExpert* task_table = reinterpret_cast<const DevExpert*>(base + w.table_off);
+    const int32_t* task_expert = reinterpret_cast<const int32_t*>(base + w.expert_off);
+    const int32_t* count = reinterpret_cast<const int32_t*>(base + w.count_off);
+    const int32_t* idx = reinterpret_cast<const int32_t*>(base + w.idx_off);
+    FLOE_LAUNCH(FLOE_KERNEL_STAGE, side,
+                launch_stage_tasks(task_table, L->s.d, L->s.f, idx, count, p->capacity_rows,
+                                   reinterpret_cast<h16*>(p->staging), nullptr, w.n_tasks, side));
+    FLOE_HIP(launch_rowmap(idx, count, task_expert, L->s.f, p->capacity_rows, p->row_of, p->pred_expert, p->pred_count,
+                           w.n_tasks, side));
+    FLOE_HIP(hipEventRecord((hipEvent_t)p->ev_prefetched, side));
+    return FLOE_OK;
+}
+
+int floe_moe_layer_decode_prefetched(const floe_layer* L, const floe_prefetch* p, const floe_miss_path* m,
+                                     const floe_half* x, int T, floe_half* y, floe_slot_stat* stats,
+                                     floe_prefetch_stat* prefetch_stats, void* workspace, size_t workspace_bytes,
+                                     void* stream) {
+    static_assert(sizeof(floe_prefetch_stat) == sizeof(PrefetchStat), "prefetch stat record layout");
+    int rc = check_layer(L);
+    if (rc) return rc;
+    if ((rc = check_T(T))) return rc;
+    if (T == 0) return FLOE_OK;
+    if (!p || !p->staging || !p->pred_expert || !p->pred_count || !p->row_of || !p->ev_prefetched || p->capacity_rows <= 0)
+        return FLOE_EINVAL;
+    if (!m || !m->ev_lists_ready || !m->ev_staged) return FLOE_EINVAL;
+    if (!L->dev_table || !L->gd_on_host || !x || !y || !workspace) return FLOE_EINVAL;
+    if (!aligned(x, 16) || !aligned(y, 8) || !aligned(workspace, kAlign) || !aligned(p->staging, 16)) return FLOE_EINVAL;
+    const LayerWs w = layer_ws(L, T);
+    if (workspace_bytes < w.total) return FLOE_EWORKSPACE;
+    char* base = static_cast<char*>(workspace);
+    DevExpert* task_table = reinterpret_cast<DevExpert*>(base + w.table_off);
+    int32_t* task_expert = reinterpret_cast<int32_t*>(base + w.expert_off);
+    float* task_weight = reinterpret_cast<float*>(base + w.weight_off);
+    int32_t* count = reinterpret_cast<int32_t*>(base + w.count_off);
+    float* v = reinterpret_cast<float*>(base + w.v_off);
+    int32_t* idx = reinterpret_cast<int32_t*>(base + w.idx_off);
+    int32_t* rows = reinterpret_cast<int32_t*>(base + w.rows_off);
+    int32_t* miss_idx = reinterpret_cast<int32_t*>(base + w.missidx_off);
+    int32_t* miss_rows = reinterpret_cast<int32_t*>(base + w.missrows_off);
+    int32_t* miss_count = reinterpret_cast<int32_t*>(base + w.misscount_off);
+    float* partial = reinterpret_cast<float*>(base + w.partial_off);
+    hipStream_t st = (hipStream_t)stream, side = (hipStream_t)m->miss_stream;
+    const h16* xh = reinterpret_cast<const h16*>(x);
+    const int slots = L->top_k + L->n_shared;
+    TaskMap map{};
+    map.task_table = task_table;
+    map.slots = slots;
+
+    if ((rc = layer_lists(L, w, base, xh, T, st))) return rc;
+    FLOE_HIP(hipStreamWaitEvent(st, (hipEvent_t)p->ev_prefetched, 0));
+    FLOE_HIP(launch_match_rows(idx, count, task_expert, L->s.f, slots, p->capacity_rows, p->row_of, p->pred_expert,
+                               p->pred_count, rows, miss_idx, miss_rows, miss_count, m->overflow,
+                               reinterpret_cast<PrefetchStat*>(prefetch_stats), w.n_tasks, st));
+    FLOE_HIP(hipEventRecord((hipEvent_t)m->ev_lists_ready, st));
+    FLOE_HIP(hipStreamWaitEvent(side, (hipEvent_t)m->ev_lists_ready, 0));
+    FLOE_LAUNCH(FLOE_KERNEL_STAGE, side,
+                launch_stage_tasks(task_table, L->s.d, L->s.f, miss_idx, miss_count, p->capacity_rows,
+                                   reinterpret_cast<h16*>(p->staging), nullptr, w.n_tasks, side, miss_rows));
+    FLOE_HIP(hipEventRecord((hipEvent_t)m->ev_staged, side));
+    FLOE_HIP(hipStreamWaitEvent(st, (hipEvent_t)m->ev_staged, 0));
+    FLOE_LAUNCH(FLOE_KERNEL_GATE_DOWN, st,
+                launch_gate_down(map, reinterpret_cast<const h16*>(p->staging), p->capacity_rows, xh, v, nullptr, idx, count,
+                                 task_weight, partial, L->s.d, L->s.f, w.n_tasks, w.nblk, st, rows));
     FLOE_LAUNCH(FLOE_KERNEL_COMBINE, st,
                 launch_combine(partial, L->s.d, T, slots, w.nblk, nullptr, reinterpret_cast<h16*>(y), st));
     if (stats) FLOE_HIP(launch_stats(task_expert, count, 0, task_weight, reinterpret_cast<SlotStat*>(stats), w.n_tasks, st));

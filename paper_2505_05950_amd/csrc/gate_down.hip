@@ -36,7 +36,8 @@ __global__ __launch_bounds__(256) void gate_down_kernel(TaskMap map, const h16* 
                                                         const uint32_t* __restrict__ mask_words,
                                                         int32_t* __restrict__ idx, int32_t* __restrict__ count,
                                                         const float* __restrict__ task_scale,
-                                                        float* __restrict__ partial, int f) {
+                                                        float* __restrict__ partial, int f,
+                                                        const int32_t* __restrict__ rows) {
     constexpr int d = 512 * NV;
     using Tile = GdTile<NV>;
     constexpr int BG = Tile::BG, B = Tile::B, VPR = Tile::VPR, RG = Tile::RG;
@@ -54,7 +55,9 @@ __global__ __launch_bounds__(256) void gate_down_kernel(TaskMap map, const h16* 
     const float* vt = v + (size_t)task * f;
     // staged: the task's selected chunks sit in rows 0..K-1 of its own slab of the staging buffer
     const bool staged = staged_base != nullptr;
-    const h16* gdp = staged ? staged_base + (size_t)task * gd_rows * 2 * d : e.gd;
+    // rows (staged only): row of the staging buffer that holds the k-th channel of the task's list, -1 = absent
+    const h16* gdp = staged ? (rows ? staged_base : staged_base + (size_t)task * gd_rows * 2 * d) : e.gd;
+    const int32_t* rw = rows ? rows + (size_t)task * f : nullptr;
 
     FLOE_TL(0);
     uint4 xr[NV];
@@ -110,7 +113,7 @@ __global__ __launch_bounds__(256) void gate_down_kernel(TaskMap map, const h16* 
         K = count[task];
     }
     FLOE_TL(1);
-    const int Kc = min(K, staged ? gd_rows : f);
+    const int Kc = min(K, (staged && !rows) ? gd_rows : f);
     const int per = (Kc + (int)gridDim.x - 1) / (int)gridDim.x;
     const int k0 = min(Kc, (int)blockIdx.x * per);
     const int k1 = min(Kc, k0 + per);
@@ -151,9 +154,11 @@ __global__ __launch_bounds__(256) void gate_down_kernel(TaskMap map, const h16* 
 #pragma unroll
             for (int i = 0; i < BG; ++i) {
                 const int c = b0 + wave + 4 * i;
-                const int j = c < n ? jl[c] : -1;
+                int j = c < n ? jl[c] : -1;
                 vj[i] = j >= 0 ? vt[j] : 0.0f;  // same address in every lane; needed only after the dot product
-                const size_t row = staged ? (size_t)(kc + c) : (size_t)(j < 0 ? 0 : j);
+                const int rr = (rw && j >= 0) ? rw[kc + c] : 0;
+                if (rr < 0) j = -1;  // the chunk is not in the staging buffer (overflow): the channel is left out
+                const size_t row = staged ? (rw ? (size_t)(rr < 0 ? 0 : rr) : (size_t)(kc + c)) : (size_t)(j < 0 ? 0 : j);
                 const uint4* gp = reinterpret_cast<const uint4*>(gdp + row * 2 * d);
 #pragma unroll
                 for (int r = 0; r < NV; ++r) gv[i][r] = j >= 0 ? gp[r * kWave + lane] : make_uint4(0u, 0u, 0u, 0u);
@@ -161,8 +166,10 @@ __global__ __launch_bounds__(256) void gate_down_kernel(TaskMap map, const h16* 
 #pragma unroll
             for (int cc = 0; cc < B; ++cc) {
                 const int c = b0 + cc;
-                const int j = c < n ? jl[c] : -1;
-                const size_t row = staged ? (size_t)(kc + c) : (size_t)(j < 0 ? 0 : j);
+                int j = c < n ? jl[c] : -1;
+                const int rr = (rw && j >= 0) ? rw[kc + c] : 0;
+                if (rr < 0) j = -1;
+                const size_t row = staged ? (rw ? (size_t)(rr < 0 ? 0 : rr) : (size_t)(kc + c)) : (size_t)(j < 0 ? 0 : j);
                 const uint4* dp = reinterpret_cast<const uint4*>(gdp + row * 2 * d + d);
 #pragma unroll
                 for (int r = 0; r < RG; ++r) {
@@ -184,7 +191,8 @@ __global__ __launch_bounds__(256) void gate_down_kernel(TaskMap map, const h16* 
                     g = dot2(xr[r].w, gv[i][r].w, g);
                 }
                 g = wave_allreduce_sum(g);
-                if (lane == 0) hl[wave + 4 * i] = (c < n && jl[c] >= 0) ? silu(g) * vj[i] * out_scale : 0.0f;
+                const bool present = c < n && jl[c] >= 0 && !(rw && rw[kc + c] < 0);
+                if (lane == 0) hl[wave + 4 * i] = present ? silu(g) * vj[i] * out_scale : 0.0f;
             }
             FLOE_TL(4);
             __syncthreads();
@@ -242,26 +250,28 @@ int gd_blocks(int n_tasks, int f) {
 template <int NV>
 static hipError_t launch_nv(const TaskMap& map, const h16* staged, int gd_rows, const h16* x, const float* v,
                             const uint32_t* mask_words, int32_t* idx, int32_t* count, const float* task_scale,
-                            float* partial, int f, int n_tasks, int nblk, hipStream_t stream) {
+                            float* partial, int f, int n_tasks, int nblk, const int32_t* rows, hipStream_t stream) {
     dim3 grid(nblk, n_tasks), block(256);
     if (mask_words)
         gate_down_kernel<NV, true><<<grid, block, 0, stream>>>(map, staged, gd_rows, x, v, mask_words, idx, count,
-                                                              task_scale, partial, f);
+                                                              task_scale, partial, f, nullptr);
     else
         gate_down_kernel<NV, false><<<grid, block, 0, stream>>>(map, staged, gd_rows, x, v, nullptr, idx, count,
-                                                               task_scale, partial, f);
+                                                               task_scale, partial, f, rows);
     return hipGetLastError();
 }
 
 hipError_t launch_gate_down(const TaskMap& map, const h16* staged, int gd_rows, const h16* x, const float* v,
                             const uint32_t* mask_words, int32_t* idx, int32_t* count, const float* task_scale,
-                            float* partial, int d, int f, int n_tasks, int nblk, hipStream_t stream) {
+                            float* partial, int d, int f, int n_tasks, int nblk, hipStream_t stream,
+                            const int32_t* rows) {
     if (n_tasks == 0) return hipSuccess;
+    if (rows && (mask_words || !staged)) return hipErrorInvalidValue;  // explicit rows go with a staged list
     if (mask_words && mask_words_per_task(f) > kMaxMaskWords) return hipErrorInvalidValue;
 #define FLOE_NV_CASE(N)                                                                                            \
     case N:                                                                                                        \
         return launch_nv<N>(map, staged, gd_rows, x, v, mask_words, idx, count, task_scale, partial, f, n_tasks, nblk, \
-                            stream);
+                            rows, stream);
     switch (d / 512) {
         FLOE_NV_CASE(1) FLOE_NV_CASE(2) FLOE_NV_CASE(3) FLOE_NV_CASE(4) FLOE_NV_CASE(5) FLOE_NV_CASE(6)
         FLOE_NV_CASE(7) FLOE_NV_CASE(8) FLOE_NV_CASE(9) FLOE_NV_CASE(10) FLOE_NV_CASE(11) FLOE_NV_CASE(12)

@@ -88,10 +88,12 @@ hipError_t launch_select(const float* v, int f, int n_tasks, const float* tau, i
 // S3 (compaction) + S4 + S5.  Index lists come either from mask_words (then idx/count are WRITTEN, both
 // may be nullptr) or, with mask_words == nullptr, from idx/count (read).  partial[task][blk][d].
 int gd_blocks(int n_tasks, int f);
-// staged: nullptr, or the staging buffer [n_tasks][gd_rows][2][d] whose row k of task q holds channel idx[q][k]
+// staged: nullptr, or the staging buffer [n_tasks][gd_rows][2][d] whose row k of task q holds channel idx[q][k];
+// with rows (staged lists only) the k-th channel of task q sits in row rows[q * f + k] of the whole buffer (-1: absent)
 hipError_t launch_gate_down(const TaskMap& map, const h16* staged, int gd_rows, const h16* x, const float* v,
                             const uint32_t* mask_words, int32_t* idx, int32_t* count, const float* task_scale,
-                            float* partial, int d, int f, int n_tasks, int nblk, hipStream_t stream);
+                            float* partial, int d, int f, int n_tasks, int nblk, hipStream_t stream,
+                            const int32_t* rows = nullptr);
 
 // S6 (and the "+=" of the one-expert entry points): reduce partial over blocks and slots.
 //   y_acc != nullptr: y_acc[t][i] += sum;   y_half != nullptr: y_half[t][i] = fp16(sum)
@@ -129,7 +131,27 @@ hipError_t launch_stage(const h16* host_gd_dev, int d, int f, const int32_t* idx
                         int capacity_rows, h16* dst, int32_t* overflow, hipStream_t stream);
 // all tasks of a layer at once: source matrix of task q = task_table[q].gd (device view of pinned host memory),
 // list idx[q][0..count[q]), destination dst[q][capacity_rows][2][d], overflow[q]
+// dst_rows != nullptr: chunk k of task q goes to row dst_rows[q * f + k] of the whole buffer (capacity_rows and
+// overflow are then not used: the rows were checked when they were assigned)
 hipError_t launch_stage_tasks(const DevExpert* task_table, int d, int f, const int32_t* idx, const int32_t* count,
-                              int capacity_rows, h16* dst, int32_t* overflow, int n_tasks, hipStream_t stream);
+                              int capacity_rows, h16* dst, int32_t* overflow, int n_tasks, hipStream_t stream,
+                              const int32_t* dst_rows = nullptr);
+
+// Prefetch bookkeeping (reuse of the hidden state before layer i for layer i + 1, Sec. 3.3):
+// after a predicted list has been staged: row_of[q][j] = k for j = idx[q][k], k < min(count[q], capacity), else -1;
+// pred_expert / pred_count receive the predicted expert and the number of rows staged.
+hipError_t launch_rowmap(const int32_t* idx, const int32_t* count, const int32_t* task_expert, int f, int capacity_rows,
+                         int32_t* row_of, int32_t* pred_expert, int32_t* pred_count, int n_tasks, hipStream_t stream);
+// per actual task q: find the predicted task of the same token with the same expert; rows[q][k] = staging row of
+// channel idx[q][k] (the predicted one, or a fresh row behind the predicted ones / in the spare slab n_tasks + q);
+// misses are listed in miss_idx[q][0..miss_count[q]) with their rows in miss_rows; stat[q] = {matched, predicted, hits, misses}
+struct PrefetchStat {
+    int32_t expert_predicted, predicted, hits, misses;
+};
+hipError_t launch_match_rows(const int32_t* idx, const int32_t* count, const int32_t* task_expert, int f, int slots,
+                             int capacity_rows, const int32_t* row_of, const int32_t* pred_expert,
+                             const int32_t* pred_count, int32_t* rows, int32_t* miss_idx, int32_t* miss_rows,
+                             int32_t* miss_count, int32_t* overflow, PrefetchStat* stat, int n_tasks,
+                             hipStream_t stream);
 
 }  // namespace floe

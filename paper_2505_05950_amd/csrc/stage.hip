@@ -41,22 +41,26 @@ __global__ __launch_bounds__(256) void stage_kernel(const uint4* __restrict__ sr
 __global__ __launch_bounds__(256) void stage_tasks_kernel(const DevExpert* __restrict__ task_table, int vec_per_chunk,
                                                           int f, const int32_t* __restrict__ idx,
                                                           const int32_t* __restrict__ count, int capacity_rows,
-                                                          uint4* __restrict__ dst, int32_t* __restrict__ overflow) {
+                                                          uint4* __restrict__ dst, int32_t* __restrict__ overflow,
+                                                          const int32_t* __restrict__ dst_rows) {
     const int task = blockIdx.y;
     const uint4* src = reinterpret_cast<const uint4*>(task_table[task].gd);
     const int32_t* it = idx + (size_t)task * f;
     uint4* out = dst + (size_t)task * capacity_rows * vec_per_chunk;
+    const int32_t* rw = dst_rows ? dst_rows + (size_t)task * f : nullptr;
     const int n = count[task];
-    const int K = min(n, capacity_rows);
-    if (overflow && blockIdx.x == 0 && threadIdx.x == 0) overflow[task] = n > capacity_rows ? 1 : 0;
+    const int K = rw ? min(n, f) : min(n, capacity_rows);
+    if (!rw && overflow && blockIdx.x == 0 && threadIdx.x == 0) overflow[task] = n > capacity_rows ? 1 : 0;
     const int lane = threadIdx.x & 63;
     const int gw = blockIdx.x * 4 + (threadIdx.x >> 6);
     const int nw = gridDim.x * 4;
     for (int k = gw; k < K; k += nw) {
         const int j = it[k];
         if ((unsigned)j >= (unsigned)f) continue;
+        const int r = rw ? rw[k] : k;
+        if (r < 0) continue;
         const uint4* s = src + (size_t)j * vec_per_chunk;
-        uint4* o = out + (size_t)k * vec_per_chunk;
+        uint4* o = (rw ? dst : out) + (size_t)r * vec_per_chunk;
         for (int i = lane; i < vec_per_chunk; i += 4 * kWave) {
             uint4 a = s[i];
             uint4 b = i + kWave < vec_per_chunk ? s[i + kWave] : a;
@@ -71,11 +75,12 @@ __global__ __launch_bounds__(256) void stage_tasks_kernel(const DevExpert* __res
 }
 
 hipError_t launch_stage_tasks(const DevExpert* task_table, int d, int f, const int32_t* idx, const int32_t* count,
-                              int capacity_rows, h16* dst, int32_t* overflow, int n_tasks, hipStream_t stream) {
+                              int capacity_rows, h16* dst, int32_t* overflow, int n_tasks, hipStream_t stream,
+                              const int32_t* dst_rows) {
     if (n_tasks == 0) return hipSuccess;
     const int nblk = kNumCU / n_tasks > 0 ? kNumCU / n_tasks : 1;
     stage_tasks_kernel<<<dim3(nblk, n_tasks), dim3(256), 0, stream>>>(task_table, d / 4, f, idx, count, capacity_rows,
-                                                                     reinterpret_cast<uint4*>(dst), overflow);
+                                                                     reinterpret_cast<uint4*>(dst), overflow, dst_rows);
     return hipGetLastError();
 }
 
