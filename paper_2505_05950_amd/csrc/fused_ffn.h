@@ -32,11 +32,10 @@
 
 namespace floe {
 
-constexpr int kFusedProducers = 4;
+constexpr int kFusedProducers = fused_producers;
 constexpr int kFusedCpp = 2;                                    // consumer waves per producer (queue entries dealt in turn)
 constexpr int kFusedConsumers = kFusedProducers * kFusedCpp;
 constexpr int kFusedThreads = (kFusedProducers + kFusedConsumers) * 64;
-static_assert(kFusedProducers * fused_passes_long == 112 && fused_producers == kFusedProducers, "launch.h states the block sizes");
 
 __device__ __forceinline__ int lds_peek(const int* p) { return *reinterpret_cast<const volatile int*>(p); }
 
@@ -44,7 +43,7 @@ __device__ __forceinline__ int lds_peek(const int* p) { return *reinterpret_cast
 // threshold from task_tau and its output scale from task_scale (nullptr = 1).
 // kPasses channels-per-wave passes per producer, kDepth of them in flight.  v_out (optional): v[task][f].
 template <int BITS, int UPC, bool G32, bool ROUTED, int kPasses, int kDepth>
-__global__ __launch_bounds__(kFusedThreads) void fused_ffn_kernel(TaskMap map, const h16* __restrict__ x, RouteArgs ro,
+__global__ __launch_bounds__(kFusedThreads, fused_wgs_per_cu) void fused_ffn_kernel(TaskMap map, const h16* __restrict__ x, RouteArgs ro,
                                                                   const float* __restrict__ task_tau,
                                                                   const float* __restrict__ task_scale, int f,
                                                                   int gshift, float* __restrict__ v_out,

@@ -19,7 +19,7 @@ int fused_passes(int d, int f, int n_tasks) {
     const int options[3] = {fused_passes_long, fused_passes_mid, fused_passes_short};
     int pick = fused_passes_short;
     for (int i = 0; i < 3; ++i) {
-        if ((long long)fused_blocks(d, f, options[i]) * n_tasks >= 200) {
+        if ((long long)fused_blocks(d, f, options[i]) * n_tasks >= 200 * fused_wgs_per_cu) {
             pick = options[i];
             break;
         }

@@ -30,7 +30,7 @@ struct GdTile {
     static constexpr int RG = (VPR + 255) / 256;        // down pieces per thread per channel
 };
 
-template <int NV, bool FROM_MASK>  // d = 512 * NV
+template <int NV, bool FROM_MASK, bool HAS_ROWS = false>  // d = 512 * NV
 __global__ __launch_bounds__(256) void gate_down_kernel(TaskMap map, const h16* __restrict__ staged_base, int gd_rows,
                                                         const h16* __restrict__ x, const float* __restrict__ v,
                                                         const uint32_t* __restrict__ mask_words,
@@ -56,8 +56,8 @@ __global__ __launch_bounds__(256) void gate_down_kernel(TaskMap map, const h16* 
     // staged: the task's selected chunks sit in rows 0..K-1 of its own slab of the staging buffer
     const bool staged = staged_base != nullptr;
     // rows (staged only): row of the staging buffer that holds the k-th channel of the task's list, -1 = absent
-    const h16* gdp = staged ? (rows ? staged_base : staged_base + (size_t)task * gd_rows * 2 * d) : e.gd;
-    const int32_t* rw = rows ? rows + (size_t)task * f : nullptr;
+    const h16* gdp = staged ? (HAS_ROWS ? staged_base : staged_base + (size_t)task * gd_rows * 2 * d) : e.gd;
+    const int32_t* rw = HAS_ROWS ? rows + (size_t)task * f : nullptr;
 
     FLOE_TL(0);
     uint4 xr[NV];
@@ -113,7 +113,7 @@ __global__ __launch_bounds__(256) void gate_down_kernel(TaskMap map, const h16* 
         K = count[task];
     }
     FLOE_TL(1);
-    const int Kc = min(K, (staged && !rows) ? gd_rows : f);
+    const int Kc = min(K, (staged && !HAS_ROWS) ? gd_rows : f);
     const int per = (Kc + (int)gridDim.x - 1) / (int)gridDim.x;
     const int k0 = min(Kc, (int)blockIdx.x * per);
     const int k1 = min(Kc, k0 + per);
@@ -156,9 +156,14 @@ __global__ __launch_bounds__(256) void gate_down_kernel(TaskMap map, const h16* 
                 const int c = b0 + wave + 4 * i;
                 int j = c < n ? jl[c] : -1;
                 vj[i] = j >= 0 ? vt[j] : 0.0f;  // same address in every lane; needed only after the dot product
-                const int rr = (rw && j >= 0) ? rw[kc + c] : 0;
-                if (rr < 0) j = -1;  // the chunk is not in the staging buffer (overflow): the channel is left out
-                const size_t row = staged ? (rw ? (size_t)(rr < 0 ? 0 : rr) : (size_t)(kc + c)) : (size_t)(j < 0 ? 0 : j);
+                size_t row;
+                if (HAS_ROWS) {
+                    const int rr = j >= 0 ? rw[kc + c] : -1;
+                    if (rr < 0) j = -1;  // the chunk is not in the staging buffer (overflow): the channel is left out
+                    row = (size_t)(rr < 0 ? 0 : rr);
+                } else {
+                    row = staged ? (size_t)(kc + c) : (size_t)(j < 0 ? 0 : j);
+                }
                 const uint4* gp = reinterpret_cast<const uint4*>(gdp + row * 2 * d);
 #pragma unroll
                 for (int r = 0; r < NV; ++r) gv[i][r] = j >= 0 ? gp[r * kWave + lane] : make_uint4(0u, 0u, 0u, 0u);
@@ -167,9 +172,14 @@ __global__ __launch_bounds__(256) void gate_down_kernel(TaskMap map, const h16* 
             for (int cc = 0; cc < B; ++cc) {
                 const int c = b0 + cc;
                 int j = c < n ? jl[c] : -1;
-                const int rr = (rw && j >= 0) ? rw[kc + c] : 0;
-                if (rr < 0) j = -1;
-                const size_t row = staged ? (rw ? (size_t)(rr < 0 ? 0 : rr) : (size_t)(kc + c)) : (size_t)(j < 0 ? 0 : j);
+                size_t row;
+                if (HAS_ROWS) {
+                    const int rr = j >= 0 ? rw[kc + c] : -1;
+                    if (rr < 0) j = -1;
+                    row = (size_t)(rr < 0 ? 0 : rr);
+                } else {
+                    row = staged ? (size_t)(kc + c) : (size_t)(j < 0 ? 0 : j);
+                }
                 const uint4* dp = reinterpret_cast<const uint4*>(gdp + row * 2 * d + d);
 #pragma unroll
                 for (int r = 0; r < RG; ++r) {
@@ -191,7 +201,8 @@ __global__ __launch_bounds__(256) void gate_down_kernel(TaskMap map, const h16* 
                     g = dot2(xr[r].w, gv[i][r].w, g);
                 }
                 g = wave_allreduce_sum(g);
-                const bool present = c < n && jl[c] >= 0 && !(rw && rw[kc + c] < 0);
+                bool present = c < n && jl[c] >= 0;
+                if (HAS_ROWS) present = present && rw[kc + c] >= 0;
                 if (lane == 0) hl[wave + 4 * i] = present ? silu(g) * vj[i] * out_scale : 0.0f;
             }
             FLOE_TL(4);
@@ -255,9 +266,12 @@ static hipError_t launch_nv(const TaskMap& map, const h16* staged, int gd_rows, 
     if (mask_words)
         gate_down_kernel<NV, true><<<grid, block, 0, stream>>>(map, staged, gd_rows, x, v, mask_words, idx, count,
                                                               task_scale, partial, f, nullptr);
+    else if (rows)
+        gate_down_kernel<NV, false, true><<<grid, block, 0, stream>>>(map, staged, gd_rows, x, v, nullptr, idx, count,
+                                                                     task_scale, partial, f, rows);
     else
         gate_down_kernel<NV, false><<<grid, block, 0, stream>>>(map, staged, gd_rows, x, v, nullptr, idx, count,
-                                                               task_scale, partial, f, rows);
+                                                               task_scale, partial, f, nullptr);
     return hipGetLastError();
 }
 

@@ -39,7 +39,8 @@ inline bool route_in_place_ok(int d, int bits, int group, int n_experts, int top
 // With `route` the workgroup also routes in place (shapes of route_in_place_ok); otherwise map / task_tau /
 // task_scale describe the tasks.  partial[task][blocks][d], wg_count[task][blocks] (selected channels per
 // workgroup), v_out (optional) [task][f].
-constexpr int fused_producers = 4;                          // producer waves per workgroup
+constexpr int fused_producers = 4;                          // producer waves per workgroup (+ 2 consumers each)
+constexpr int fused_wgs_per_cu = 1;                         // workgroups per compute unit the block length aims at
 constexpr int fused_passes_long = 28, fused_passes_mid = 14, fused_passes_short = 7;  // channel passes per producer wave
 constexpr int kFusedMaxTasks = 16;        // beyond these the partial results outgrow what the fusion saves
 constexpr int kFusedMaxWorkgroups = 2048;
