@@ -666,7 +666,8 @@ def bench_stack(args, np, torch, S, FL, dev):
 def bench_batch(args, np, torch, S, FL, dev):
     """Decode batches (each token routed on its own, own thresholds): BASELINE configs[2] at T = 1, 4, 16 and
     configs[4] (64 routed + 2 shared experts, d=2048, f=1408, INT3 group 32, top-6, 85 %) at T = 1, 8, 32.
-    Per-expert constant thresholds calibrated on 8 tokens; weights are cache-hot (one layer copy)."""
+    Per-expert constant thresholds calibrated on 8 tokens; one layer copy (what a call touches beyond T = 1 is larger
+    than the last-level cache anyway)."""
     K, W = max(20, args.steps // 4), max(5, args.warmup // 8)
     out = []
 
@@ -687,15 +688,29 @@ def bench_batch(args, np, torch, S, FL, dev):
 
     stream = torch.cuda.Stream()
     for name, cfg, d, f, bits, group, n, n_shared, top_k, renorm, pct, Ts in (
-            ("configs[2]", 3, 4096, 14336, 2, 64, 8, 0, 2, True, 90, (1, 4, 16)),
+            ("configs[2]", 3, 4096, 14336, 2, 64, 8, 0, 2, True, 90, (1, 4, 16, 64)),
             ("configs[4]", 5, 2048, 1408, 3, 32, 64, 2, 6, False, 85, (1, 8, 32))):
         L = make_layer(cfg, d, f, bits, group, n, n_shared, top_k, renorm, pct)
         for T in Ts:
             x = torch.from_numpy(S.tokens(SEED, cfg, T, d, layer=9)).to(dev)
             y = torch.empty((T, d), dtype=torch.float16, device=dev)
+            slots = top_k + n_shared
+            st = torch.zeros((T, slots, 4), dtype=torch.int32, device=dev)
+            FL.floe_moe_layer_decode(L, x, y, st)
+            torch.cuda.synchronize()
+            rec = st.cpu().numpy().reshape(T * slots, 4)
             ms = _graph_time(torch, stream, lambda i: FL.floe_moe_layer_decode(L, x, y), K, W)
-            out.append({"config": name, "T": T, "us_per_layer_call": round(ms * 1e3, 2), "us_per_layer_token": round(ms * 1e3 / T, 2)})
-            log(f"[bench] {name} T={T}: {ms * 1e3:.1f} us per layer call, {ms * 1e3 / T:.2f} us per layer-token")
+            # bytes the call has to read: the codes, scales and zeros of every expert that is used (once per token that
+            # uses it while tokens are handled one by one, once per expert when tokens are grouped: at least once per
+            # expert is what is counted), the [gate | down] chunks of every (token, slot), router, x, y
+            codes_meta = d * f * bits // 8 + 4 * f * (d // group)
+            used = len(set(rec[:, 0].tolist()))
+            nbytes = used * codes_meta + int(rec[:, 1].sum()) * 4 * d + n * d * 2 + T * d * 2 * 2
+            out.append({"config": name, "T": T, "us_per_layer_call": round(ms * 1e3, 2), "us_per_layer_token": round(ms * 1e3 / T, 2),
+                        "experts_used": used, "bytes_min": int(nbytes), "GBps": round(nbytes / ms / 1e6, 1),
+                        "frac_of_hbm_peak": round(nbytes / ms / 1e6 / HBM_PEAK_GBS, 4)})
+            log(f"[bench] {name} T={T}: {ms * 1e3:.1f} us per layer call, {ms * 1e3 / T:.2f} us per layer-token, "
+                f"{out[-1]['GBps']} GB/s over {nbytes / 1e6:.0f} MB")
         del L
     print(json.dumps({"metric": "us per MoE layer-token for decode batches", "value": out[0]["us_per_layer_token"], "unit": "us",
                       "n_gpus": 1, "higher_is_better": False, "data": "synthetic",
