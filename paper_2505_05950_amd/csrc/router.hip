@@ -11,43 +11,98 @@ namespace floe {
 
 constexpr int kMaxExperts = 1024;
 
-// All loads of a dot product are in flight together: a lane fetches its 16-byte pieces of x once
-// (up to 16 of them, d <= 8192) and of the current expert row, then reduces with packed dot products.
-__global__ __launch_bounds__(256) void router_kernel(RouterArgs a) {
+// Softmax + top-k for n <= 64 experts on one wave (lane e holds expert e).  Same expf, the same ascending sum and the
+// same tie rule (lower id) as route_select, so both give the same bits.
+__device__ __forceinline__ void route_select_wave64(float logit, int lane, int n, int top_k, int renormalize, int* sel_id,
+                                                    float* sel_w) {
+    const bool live = lane < n;
+    float mx = live ? logit : -INFINITY;
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o, kWave));
+    const float p = live ? expf(logit - mx) : 0.0f;
+    float sum = 0.0f;
+    for (int e = 0; e < n; ++e) sum += __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, p), e));
+    float cur = live ? p : -3.0f;
+    float sel = 0.0f, my_w = 0.0f;
+    int my_id = 0;
+    for (int r = 0; r < top_k; ++r) {
+        float bv = cur;
+        int bi = lane;
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) {
+            const float ov = __shfl_xor(bv, o, kWave);
+            const int oi = __shfl_xor(bi, o, kWave);
+            if (ov > bv || (ov == bv && oi < bi)) { bv = ov; bi = oi; }
+        }
+        const float pw = bv / sum;
+        if (lane == r) { my_w = pw; my_id = bi; }
+        sel += pw;
+        if (lane == bi) cur = -2.0f;  // taken
+    }
+    if (lane < top_k) {
+        sel_id[lane] = my_id;
+        sel_w[lane] = renormalize ? my_w / sel : my_w;
+    }
+}
+
+// One workgroup of 16 waves per token.  A wave takes experts wave, wave + 16, ... and keeps kInFlight rows in flight
+// at a time (all 16-byte pieces of a row and of x requested before the packed dot products run), so a layer with
+// 64 experts costs two round trips to memory, not sixteen.  NV = d / 512 pieces per lane.
+template <int NV>
+__global__ __launch_bounds__(1024) void router_kernel(RouterArgs a) {
+    constexpr int kInFlight = NV <= 2 ? 4 : (NV <= 4 ? 2 : 1);
     __shared__ float prob[kMaxExperts];
     __shared__ int sel_id[64];
     __shared__ float sel_w[64];
     const int t = blockIdx.x;
     const int tid = threadIdx.x;
     const int wave = tid >> 6, lane = tid & 63;
-    const int d = a.d;
+    constexpr int d = NV * 512;
     const int slots = a.top_k + a.n_shared;
     const h16* xt = a.x + (size_t)t * d;
-    const int nvec = d / 512;  // 16-byte pieces per lane (d % 512 == 0, d <= 8192)
     if (a.top_k > 0) {
-        uint4 xv[16];
+        uint4 xv[NV];
         const uint4* xp = reinterpret_cast<const uint4*>(xt);
 #pragma unroll
-        for (int r = 0; r < 16; ++r) xv[r] = r < nvec ? xp[r * kWave + lane] : make_uint4(0u, 0u, 0u, 0u);
-        for (int e = wave; e < a.n_experts; e += 4) {
-            const uint4* wp = reinterpret_cast<const uint4*>(a.router_cm + (size_t)e * d);
-            uint4 w[16];
+        for (int r = 0; r < NV; ++r) xv[r] = xp[r * kWave + lane];
+        for (int e0 = wave; e0 < a.n_experts; e0 += 16 * kInFlight) {
+            uint4 w[kInFlight][NV];
 #pragma unroll
-            for (int r = 0; r < 16; ++r) w[r] = r < nvec ? wp[r * kWave + lane] : make_uint4(0u, 0u, 0u, 0u);
-            float acc = 0.0f;
+            for (int q = 0; q < kInFlight; ++q) {
+                const int e = e0 + 16 * q < a.n_experts ? e0 + 16 * q : e0;
+                const uint4* wp = reinterpret_cast<const uint4*>(a.router_cm + (size_t)e * d);
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                acc = dot2(xv[r].x, w[r].x, acc);
-                acc = dot2(xv[r].y, w[r].y, acc);
-                acc = dot2(xv[r].z, w[r].z, acc);
-                acc = dot2(xv[r].w, w[r].w, acc);
+                for (int r = 0; r < NV; ++r) w[q][r] = wp[r * kWave + lane];
             }
-            acc = wave_allreduce_sum(acc);
-            if (lane == 0) prob[e] = acc;
+#pragma unroll
+            for (int q = 0; q < kInFlight; ++q) {
+                float acc = 0.0f;
+#pragma unroll
+                for (int r = 0; r < NV; ++r) {
+                    acc = dot2(xv[r].x, w[q][r].x, acc);
+                    acc = dot2(xv[r].y, w[q][r].y, acc);
+                    acc = dot2(xv[r].z, w[q][r].z, acc);
+                    acc = dot2(xv[r].w, w[q][r].w, acc);
+                }
+                acc = wave_allreduce_sum(acc);
+                if (lane == 0 && e0 + 16 * q < a.n_experts) prob[e0 + 16 * q] = acc;
+            }
         }
     }
     __syncthreads();
-    if (tid == 0) route_select(prob, a.n_experts, a.top_k, a.n_shared, a.renormalize, sel_id, sel_w);
+    if (a.n_experts <= 64) {
+        if (wave == 0) {
+            if (a.top_k > 0)
+                route_select_wave64(lane < a.n_experts ? prob[lane] : 0.0f, lane, a.n_experts, a.top_k, a.renormalize,
+                                    sel_id, sel_w);
+            if (lane < a.n_shared) {
+                sel_id[a.top_k + lane] = a.n_experts + lane;
+                sel_w[a.top_k + lane] = 1.0f;
+            }
+        }
+    } else if (tid == 0) {
+        route_select(prob, a.n_experts, a.top_k, a.n_shared, a.renormalize, sel_id, sel_w);
+    }
     __syncthreads();
     // one thread per slot resolves the expert: its pointers, weight and threshold go to the task table
     if (tid < slots) {
@@ -62,32 +117,46 @@ __global__ __launch_bounds__(256) void router_kernel(RouterArgs a) {
 
 hipError_t launch_router(const RouterArgs& a, int T, hipStream_t stream) {
     if (T == 0) return hipSuccess;
-    router_kernel<<<dim3(T), dim3(256), 0, stream>>>(a);
+#define FLOE_ROUTER_NV(N) \
+    case N: router_kernel<N><<<dim3(T), dim3(1024), 0, stream>>>(a); break;
+    switch (a.d / 512) {
+        FLOE_ROUTER_NV(1) FLOE_ROUTER_NV(2) FLOE_ROUTER_NV(3) FLOE_ROUTER_NV(4) FLOE_ROUTER_NV(5) FLOE_ROUTER_NV(6)
+        FLOE_ROUTER_NV(7) FLOE_ROUTER_NV(8) FLOE_ROUTER_NV(9) FLOE_ROUTER_NV(10) FLOE_ROUTER_NV(11) FLOE_ROUTER_NV(12)
+        FLOE_ROUTER_NV(13) FLOE_ROUTER_NV(14) FLOE_ROUTER_NV(15) FLOE_ROUTER_NV(16)
+        default: return hipErrorInvalidValue;
+    }
+#undef FLOE_ROUTER_NV
     return hipGetLastError();
 }
 
-__global__ void stats_kernel(const int32_t* task_expert, const int32_t* count, int count_parts,
-                             const float* task_weight, SlotStat* stats, int n_tasks) {
-    const int q = blockIdx.x * blockDim.x + threadIdx.x;
-    if (q >= n_tasks) return;
-    SlotStat s;
-    s.expert = task_expert[q];
+// one wave per task: the lanes share the per-workgroup counts of a fused launch
+__global__ __launch_bounds__(256) void stats_kernel(const int32_t* task_expert, const int32_t* count, int count_parts,
+                                                    const float* task_weight, SlotStat* stats, int n_tasks) {
+    const int q = blockIdx.x * 4 + (threadIdx.x >> 6);
+    const int lane = threadIdx.x & 63;
+    if (q >= n_tasks) return;  // wave-uniform
+    int c = 0;
     if (count_parts > 0) {
-        int c = 0;
-        for (int b = 0; b < count_parts; ++b) c += count[(size_t)q * count_parts + b];
-        s.count = c;
+        for (int b = lane; b < count_parts; b += kWave) c += count[(size_t)q * count_parts + b];
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) c += __shfl_xor(c, o, kWave);
     } else {
-        s.count = count[q];
+        c = count[q];
     }
-    s.weight = task_weight[q];
-    s.pad = 0;
-    stats[q] = s;
+    if (lane == 0) {
+        SlotStat s;
+        s.expert = task_expert[q];
+        s.count = c;
+        s.weight = task_weight[q];
+        s.pad = 0;
+        stats[q] = s;
+    }
 }
 
 hipError_t launch_stats(const int32_t* task_expert, const int32_t* count, int count_parts, const float* task_weight,
                         SlotStat* stats, int n_tasks, hipStream_t stream) {
     if (n_tasks == 0) return hipSuccess;
-    stats_kernel<<<dim3((n_tasks + 255) / 256), dim3(256), 0, stream>>>(task_expert, count, count_parts, task_weight,
+    stats_kernel<<<dim3((n_tasks + 3) / 4), dim3(256), 0, stream>>>(task_expert, count, count_parts, task_weight,
                                                                         stats, n_tasks);
     return hipGetLastError();
 }
