@@ -13,31 +13,46 @@ constexpr int kMaxExperts = 1024;
 
 // Softmax + top-k for n <= 64 experts on one wave (lane e holds expert e).  Same expf, the same ascending sum and the
 // same tie rule (lower id) as route_select, so both give the same bits.
+__device__ __forceinline__ float lane_f(float v, int l) {
+    return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), l));
+}
 __device__ __forceinline__ void route_select_wave64(float logit, int lane, int n, int top_k, int renormalize, int* sel_id,
                                                     float* sel_w) {
     const bool live = lane < n;
-    float mx = live ? logit : -INFINITY;
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o, kWave));
+    // maximum: inside the rows of 16 on the DPP path, then over the four rows through scalar registers
+    float mx = row16_allreduce_max(live ? logit : -INFINITY);
+    mx = fmaxf(fmaxf(lane_f(mx, 0), lane_f(mx, 16)), fmaxf(lane_f(mx, 32), lane_f(mx, 48)));
     const float p = live ? expf(logit - mx) : 0.0f;
     float sum = 0.0f;
-    for (int e = 0; e < n; ++e) sum += __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, p), e));
+    for (int e = 0; e < n; ++e) sum += lane_f(p, e);
     float cur = live ? p : -3.0f;
     float sel = 0.0f, my_w = 0.0f;
     int my_id = 0;
     for (int r = 0; r < top_k; ++r) {
+        // arg-max with ties to the lower id: (value, id) pairs rotate around each row of 16, then the four row
+        // winners (in ascending id order, so a strict comparison keeps the lower id) meet in scalar registers
         float bv = cur;
         int bi = lane;
+#define FLOE_ARGMAX_STEP(CTRL)                                               \
+    {                                                                        \
+        const float ov = dpp_movf<CTRL>(bv);                                 \
+        const int oi = dpp_movi<CTRL>(bi);                                   \
+        if (ov > bv || (ov == bv && oi < bi)) { bv = ov; bi = oi; }          \
+    }
+        FLOE_ARGMAX_STEP(0x128) FLOE_ARGMAX_STEP(0x124) FLOE_ARGMAX_STEP(0x122) FLOE_ARGMAX_STEP(0x121)
+#undef FLOE_ARGMAX_STEP
+        float wv = lane_f(bv, 0);
+        int wi = __builtin_amdgcn_readlane(bi, 0);
 #pragma unroll
-        for (int o = 32; o > 0; o >>= 1) {
-            const float ov = __shfl_xor(bv, o, kWave);
-            const int oi = __shfl_xor(bi, o, kWave);
-            if (ov > bv || (ov == bv && oi < bi)) { bv = ov; bi = oi; }
+        for (int row = 1; row < 4; ++row) {
+            const float ov = lane_f(bv, 16 * row);
+            const int oi = __builtin_amdgcn_readlane(bi, 16 * row);
+            if (ov > wv) { wv = ov; wi = oi; }
         }
-        const float pw = bv / sum;
-        if (lane == r) { my_w = pw; my_id = bi; }
+        const float pw = wv / sum;
+        if (lane == r) { my_w = pw; my_id = wi; }
         sel += pw;
-        if (lane == bi) cur = -2.0f;  // taken
+        if (lane == wi) cur = -2.0f;  // taken
     }
     if (lane < top_k) {
         sel_id[lane] = my_id;

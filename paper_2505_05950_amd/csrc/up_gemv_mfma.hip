@@ -399,13 +399,29 @@ __global__ __launch_bounds__(kMfmaThreads) void up_gemv_mfma_kernel(const DevExp
 __global__ __launch_bounds__(1024) void group_tokens_kernel(const int32_t* __restrict__ task_expert, int n_tasks,
                                                             int n_all, int chunk, TokenGroup* __restrict__ groups,
                                                             int32_t* __restrict__ n_groups) {
+    constexpr int kTile = 4096;  // task ids pass through LDS in tiles, so a thread's scan costs LDS reads only
     __shared__ int first_group[1024 + 64 + 1];
+    __shared__ int tile[kTile];
     const int tid = threadIdx.x;
-    for (int e = tid; e < n_all; e += blockDim.x) {
-        int cnt = 0;
-        for (int q = 0; q < n_tasks; ++q) cnt += task_expert[q] == e;
-        first_group[e + 1] = (cnt + chunk - 1) / chunk;
+    // n_all <= 1088 (1024 routed + 64 shared): a thread owns expert tid and, if there are that many, tid + 1024
+    int cnt[2] = {0, 0};
+    for (int base = 0; base < n_tasks; base += kTile) {
+        const int n = min(kTile, n_tasks - base);
+        __syncthreads();
+        for (int i = tid; i < n; i += blockDim.x) tile[i] = task_expert[base + i];
+        __syncthreads();
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            const int e = tid + 1024 * h;
+            if (e < n_all) {
+#pragma unroll 16
+                for (int i = 0; i < n; ++i) cnt[h] += tile[i] == e;
+            }
+        }
     }
+#pragma unroll
+    for (int h = 0; h < 2; ++h)
+        if (tid + 1024 * h < n_all) first_group[tid + 1024 * h + 1] = (cnt[h] + chunk - 1) / chunk;
     __syncthreads();
     if (tid == 0) {
         first_group[0] = 0;
@@ -413,14 +429,31 @@ __global__ __launch_bounds__(1024) void group_tokens_kernel(const int32_t* __res
         n_groups[0] = first_group[n_all];
     }
     __syncthreads();
-    for (int e = tid; e < n_all; e += blockDim.x) {
-        int gi = first_group[e], k = 0;
-        for (int q = 0; q < n_tasks; ++q) {
-            if (task_expert[q] != e) continue;
-            if (k == 0) { groups[gi].expert = e; groups[gi].n = 0; }
-            groups[gi].task[k] = q;
-            groups[gi].n = ++k;
-            if (k == chunk) { ++gi; k = 0; }
+    int gi[2], k[2] = {0, 0};
+#pragma unroll
+    for (int h = 0; h < 2; ++h) gi[h] = tid + 1024 * h < n_all ? first_group[tid + 1024 * h] : 0;
+    for (int base = 0; base < n_tasks; base += kTile) {
+        const int n = min(kTile, n_tasks - base);
+        __syncthreads();
+        for (int i = tid; i < n; i += blockDim.x) tile[i] = task_expert[base + i];
+        __syncthreads();
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            const int e = tid + 1024 * h;
+            if (e >= n_all) continue;
+            for (int i0 = 0; i0 < n; i0 += 16) {
+                int own[16];  // sixteen LDS reads in flight, then the (rare) matches in order
+#pragma unroll
+                for (int j = 0; j < 16; ++j) own[j] = tile[min(i0 + j, n - 1)];
+#pragma unroll
+                for (int j = 0; j < 16; ++j) {
+                    if (own[j] != e || i0 + j >= n) continue;
+                    if (k[h] == 0) { groups[gi[h]].expert = e; groups[gi[h]].n = 0; }
+                    groups[gi[h]].task[k[h]] = base + i0 + j;
+                    groups[gi[h]].n = ++k[h];
+                    if (k[h] == chunk) { ++gi[h]; k[h] = 0; }
+                }
+            }
         }
     }
 }
