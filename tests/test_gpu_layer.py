@@ -130,6 +130,12 @@ def test_layer_small_batches_through_the_fused_kernel():
     _run_layer_case(27, 3, 4096, 200, 3, 128, 4, 0, 2, True, 1, 50)
 
 
+def test_layer_with_more_than_64_experts_takes_the_serial_top_k():
+    # the router kernel picks on one wave up to 64 experts and serially beyond; both batch sizes (fused / per-task kernels)
+    _run_layer_case(28, 5, 1024, 320, 2, 64, 80, 1, 4, False, 2, 70)
+    _run_layer_case(29, 5, 1024, 320, 4, 32, 70, 0, 3, True, 9, 60)
+
+
 def test_layer_batches_through_the_matrix_core_gemv():
     """Decode batches group the tokens of an expert (chunks of 16) and run S2 on the matrix cores:
     INT4 / INT2, groups of 32 and 64, more than 16 tokens per expert, ragged f."""
