@@ -544,7 +544,6 @@ int floe_moe_layer_decode_offloaded(const floe_layer* L, const floe_offload* o, 
     DevExpert* task_table = reinterpret_cast<DevExpert*>(base + w.table_off);
     int32_t* task_expert = reinterpret_cast<int32_t*>(base + w.expert_off);
     float* task_weight = reinterpret_cast<float*>(base + w.weight_off);
-    float* task_tau = reinterpret_cast<float*>(base + w.tau_off);
     int32_t* count = reinterpret_cast<int32_t*>(base + w.count_off);
     float* v = reinterpret_cast<float*>(base + w.v_off);
     int32_t* idx = reinterpret_cast<int32_t*>(base + w.idx_off);
