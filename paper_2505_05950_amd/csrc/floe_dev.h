@@ -27,6 +27,24 @@ struct TaskMap {
     int32_t slots;                // tasks per token; token of task q is q / slots
 };
 
+// Pointers that a kernel reads out of a table (HBM or LDS) carry no address space for the compiler, which then
+// emits FLAT loads: those also count against the LDS counter, so every wait for an LDS result would wait for the
+// weight loads in flight.  All matrices of an expert live in global memory; these loads say so.
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+#define FLOE_GLOBAL __attribute__((address_space(1)))
+__device__ __forceinline__ uint4 gload16(const void* p) {
+    const u32x4 q = *(const FLOE_GLOBAL u32x4*)p;
+    return make_uint4(q.x, q.y, q.z, q.w);
+}
+__device__ __forceinline__ uint2 gload8(const void* p) {
+    const u32x2 q = *(const FLOE_GLOBAL u32x2*)p;
+    return make_uint2(q.x, q.y);
+}
+__device__ __forceinline__ uint32_t gload4(const void* p) { return *(const FLOE_GLOBAL uint32_t*)p; }
+__device__ __forceinline__ uint32_t gload2(const void* p) { return *(const FLOE_GLOBAL uint16_t*)p; }
+__device__ __forceinline__ float gloadf(const void* p) { return *(const FLOE_GLOBAL float*)p; }
+
 __device__ __forceinline__ DevExpert task_expert_of(const TaskMap& m, int task) {
     if (m.task_table == nullptr) return m.single;
     return m.task_table[task];

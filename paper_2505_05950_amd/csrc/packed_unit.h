@@ -12,15 +12,14 @@ __device__ __forceinline__ void load_unit(const uint32_t* __restrict__ codes, si
     constexpr int W = PackedTraits<BITS>::kWords;
     const uint32_t* p = codes + unit_index * W;
     if (BITS == 2) {
-        const uint4 q = *reinterpret_cast<const uint4*>(p);
+        const uint4 q = gload16(p);
         cw[0] = q.x; cw[1] = q.y; cw[2] = q.z; cw[3] = q.w;
     } else if (BITS == 4) {
-        const uint4 q0 = reinterpret_cast<const uint4*>(p)[0], q1 = reinterpret_cast<const uint4*>(p)[1];
+        const uint4 q0 = gload16(p), q1 = gload16(p + 4);
         cw[0] = q0.x; cw[1] = q0.y; cw[2] = q0.z; cw[3] = q0.w;
         cw[4] = q1.x; cw[5] = q1.y; cw[6] = q1.z; cw[7] = q1.w;
     } else {  // 24 bytes, 8-byte aligned
-        const uint2 q0 = reinterpret_cast<const uint2*>(p)[0], q1 = reinterpret_cast<const uint2*>(p)[1],
-                    q2 = reinterpret_cast<const uint2*>(p)[2];
+        const uint2 q0 = gload8(p), q1 = gload8(p + 2), q2 = gload8(p + 4);
         cw[0] = q0.x; cw[1] = q0.y; cw[2] = q1.x; cw[3] = q1.y; cw[4] = q2.x; cw[5] = q2.y;
     }
 }
@@ -33,12 +32,12 @@ struct UnitLoad {  // one pass of a lane: the unit's code words and its scale / 
         load_unit<BITS>(e.codes, (size_t)j * UPC + u, cw);
         if (G32) {
             const size_t mi = (size_t)j * G + 2 * u;  // even index: 4-byte aligned
-            s = *reinterpret_cast<const uint32_t*>(e.scale + mi);
-            z = *reinterpret_cast<const uint32_t*>(e.zero + mi);
+            s = gload4(e.scale + mi);
+            z = gload4(e.zero + mi);
         } else {
             const size_t mi = (size_t)j * G + ((u * 64) >> gshift);
-            s = *reinterpret_cast<const uint16_t*>(e.scale + mi);
-            z = *reinterpret_cast<const uint16_t*>(e.zero + mi);
+            s = gload2(e.scale + mi);
+            z = gload2(e.zero + mi);
         }
     }
 };
