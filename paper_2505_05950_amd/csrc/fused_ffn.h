@@ -37,7 +37,13 @@ constexpr int kFusedCpp = 2;                                    // consumer wave
 constexpr int kFusedConsumers = kFusedProducers * kFusedCpp;
 constexpr int kFusedThreads = (kFusedProducers + kFusedConsumers) * 64;
 
-__device__ __forceinline__ int lds_peek(const int* p) { return *reinterpret_cast<const volatile int*>(p); }
+// Queue words are read and written with volatile accesses that are typed as LDS: a volatile access through a generic
+// pointer becomes a FLAT instruction with system scope, which ticks the vector-memory counter as well and makes the
+// producer wait for its code loads whenever it pushes an entry.
+#define FLOE_LDS __attribute__((address_space(3)))
+__device__ __forceinline__ int lds_peek(const int* p) { return *(const volatile FLOE_LDS int*)p; }
+__device__ __forceinline__ void lds_poke(int* p, int v) { *(volatile FLOE_LDS int*)p = v; }
+__device__ __forceinline__ void lds_poke(float* p, float v) { *(volatile FLOE_LDS float*)p = v; }
 
 // ROUTED: the workgroup routes in place (INT2, <= 16 experts); otherwise the task's expert comes from `map`, its
 // threshold from task_tau and its output scale from task_scale (nullptr = 1).
@@ -175,8 +181,8 @@ __global__ __launch_bounds__(kFusedThreads, fused_wgs_per_cu) void fused_ffn_ker
                     if (lane == bit) {
                         // the same lane writes both words; LDS keeps a wave's accesses in order, so whoever sees
                         // the channel id also sees the value
-                        *reinterpret_cast<volatile float*>(&qh[wave][k]) = part * wgt;
-                        *reinterpret_cast<volatile int*>(&qj[wave][k]) = j;
+                        lds_poke(&qh[wave][k], part * wgt);
+                        lds_poke(&qj[wave][k], j);
                     }
                     ++k;
                 }
@@ -184,7 +190,7 @@ __global__ __launch_bounds__(kFusedThreads, fused_wgs_per_cu) void fused_ffn_ker
             }
         }
         if (lane == 0) {
-            *reinterpret_cast<volatile int*>(&done[wave]) = 1;  // after the last push, in program order
+            lds_poke(&done[wave], 1);  // after the last push, in program order
             atomicAdd(&n_sel, k);
         }
         FLOE_TL(5);
