@@ -202,18 +202,21 @@ __global__ __launch_bounds__(kFusedThreads, fused_wgs_per_cu) void fused_ffn_ker
 #pragma unroll
         for (int i = 0; i < 8 * NV; ++i) acc[i] = 0.0f;
         int k = c % kFusedCpp;
-        for (;;) {
-            int j = __builtin_amdgcn_readfirstlane(lds_peek(&qj[qc][k < kQ ? k : kQ - 1]));
-            if (k >= kQ) break;  // the queue cannot hold more than its producer has channels
-            if (j < 0) {
-                if (__builtin_amdgcn_readfirstlane(lds_peek(&done[qc])) == 0) {
-                    __builtin_amdgcn_s_sleep(8);
-                    continue;
-                }
-                // the flag is raised after the last push: look once more, then the queue is known to be empty
+        while (k < kQ) {  // the queue cannot hold more than its producer has channels
+            // The wait is a loop of its own that touches no accumulator: as a second way back to the head of the
+            // outer loop it made the compiler copy all of them (64 moves) on every empty poll.
+            int j;
+            for (;;) {
                 j = __builtin_amdgcn_readfirstlane(lds_peek(&qj[qc][k]));
-                if (j < 0) break;
+                if (j >= 0) break;
+                if (__builtin_amdgcn_readfirstlane(lds_peek(&done[qc])) != 0) {
+                    // the flag is raised after the last push: look once more, then the queue is known to be empty
+                    j = __builtin_amdgcn_readfirstlane(lds_peek(&qj[qc][k]));
+                    break;
+                }
+                __builtin_amdgcn_s_sleep(8);
             }
+            if (j < 0) break;
             const float h0 = __builtin_bit_cast(float, __builtin_amdgcn_readfirstlane(lds_peek(reinterpret_cast<const int*>(&qh[qc][k]))));
             const uint4* gp = reinterpret_cast<const uint4*>(e.gd + (size_t)j * 2 * d);
             uint4 gv[NV], dv[NV];
