@@ -83,15 +83,6 @@ __global__ __launch_bounds__(kFusedThreads, fused_wgs_per_cu) void fused_ffn_ker
 
     const bool producer = wave < kFusedProducers;
     const int u = lane % UPC, sub = lane / UPC;
-    uint32_t raw[32];  // producer: this lane's 64 activations (the unit it owns in every channel)
-    if (producer) {
-        const uint4* xq = reinterpret_cast<const uint4*>(xt + u * 64);
-#pragma unroll
-        for (int r = 0; r < 8; ++r) {
-            const uint4 q = xq[r];
-            raw[4 * r + 0] = q.x; raw[4 * r + 1] = q.y; raw[4 * r + 2] = q.z; raw[4 * r + 3] = q.w;
-        }
-    }
     DevExpert e;
     float tau;
     Pick16 pick{};
@@ -132,6 +123,15 @@ __global__ __launch_bounds__(kFusedThreads, fused_wgs_per_cu) void fused_ffn_ker
 #pragma unroll
         for (int p = 0; p < kDepth; ++p) ld[p].issue(e, channel_of(p), u, G, gshift);
         FLOE_TL(3);
+
+        // This lane's 64 activations (the unit it owns in every channel), from the copy in LDS: read from memory,
+        // the 128-byte stride between lanes made 512 cache-line requests per wave, all workgroups on the same lines.
+        uint32_t raw[32];
+#pragma unroll
+        for (int r = 0; r < 8; ++r) {
+            const uint4 q = xlds[u * 8 + r];
+            raw[4 * r + 0] = q.x; raw[4 * r + 1] = q.y; raw[4 * r + 2] = q.z; raw[4 * r + 3] = q.w;
+        }
 
         float wgt = 1.0f;
         if (ROUTED) {

@@ -137,7 +137,8 @@ __device__ __forceinline__ void route_logits_to_lds(const h16* __restrict__ xt, 
         uint4 w[2][NVR], xl[2][NVR];
 #pragma unroll
         for (int q = 0; q < 2; ++q) {
-            const int it = it0 + q * NW < n_items ? it0 + q * NW : it0;
+            const int it = it0 + q * NW;
+            if (it >= n_items) break;  // wave-uniform
             const int ex = it / kParts, part = it % kParts;
             const uint4* wq = reinterpret_cast<const uint4*>(ro.router_cm + (size_t)ex * D);
 #pragma unroll
@@ -148,6 +149,7 @@ __device__ __forceinline__ void route_logits_to_lds(const h16* __restrict__ xt, 
         }
 #pragma unroll
         for (int q = 0; q < 2; ++q) {
+            if (it0 + q * NW >= n_items) break;
             float acc = 0.0f;
 #pragma unroll
             for (int r = 0; r < NVR; ++r) {
