@@ -298,11 +298,12 @@ hipError_t launch_gate_down(const TaskMap& map, const h16* staged, int gd_rows, 
 // ---------------------------------------------------------------------------------------------------
 // S6: sum the partial results of every (slot, block) of a token, fold into y_acc and / or round to fp16.
 // A workgroup owns 32 output columns of one token: 8 threads (one float4 each) cover the columns,
-// the 32 thread rows split the partials between them (eight loads in flight each) and meet in LDS.
+// the 32 thread rows split the partials between them (eight loads in flight each); the sums meet by lane
+// exchange inside a wave and in LDS across the four waves (a fixed order, so the result is reproducible).
 // ---------------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void combine_kernel(const float* __restrict__ partial, int d, int per_token,
                                                       float* __restrict__ y_acc, h16* __restrict__ y_half) {
-    __shared__ float4 red[32][8];
+    __shared__ float4 red[4][8];
     const int t = blockIdx.y;
     const int cg = threadIdx.x & 7, pg = threadIdx.x >> 3;
     const int c4 = blockIdx.x * 8 + cg;  // column / 4   (d % 32 == 0)
@@ -318,11 +319,19 @@ __global__ __launch_bounds__(256) void combine_kernel(const float* __restrict__ 
 #pragma unroll
         for (int i = 0; i < 8; ++i) { s.x += a[i].x; s.y += a[i].y; s.z += a[i].z; s.w += a[i].w; }
     }
-    red[pg][cg] = s;
+    // the eight thread rows of a wave meet by lane exchange (lane = row * 8 + column group), the four waves in LDS
+#pragma unroll
+    for (int o = 8; o < 64; o <<= 1) {
+        s.x += __shfl_xor(s.x, o, kWave);
+        s.y += __shfl_xor(s.y, o, kWave);
+        s.z += __shfl_xor(s.z, o, kWave);
+        s.w += __shfl_xor(s.w, o, kWave);
+    }
+    if ((pg & 7) == 0) red[pg >> 3][cg] = s;
     __syncthreads();
     if (pg != 0) return;
 #pragma unroll
-    for (int r = 1; r < 32; ++r) {
+    for (int r = 1; r < 4; ++r) {
         const float4 a = red[r][cg];
         s.x += a.x; s.y += a.y; s.z += a.z; s.w += a.w;
     }
