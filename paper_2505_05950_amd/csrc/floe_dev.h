@@ -43,6 +43,7 @@ __device__ __forceinline__ uint2 gload8(const void* p) {
 }
 __device__ __forceinline__ uint32_t gload4(const void* p) { return *(const FLOE_GLOBAL uint32_t*)p; }
 __device__ __forceinline__ uint32_t gload2(const void* p) { return *(const FLOE_GLOBAL uint16_t*)p; }
+__device__ __forceinline__ _Float16 gloadh(const void* p) { return *(const FLOE_GLOBAL _Float16*)p; }
 __device__ __forceinline__ float gloadf(const void* p) { return *(const FLOE_GLOBAL float*)p; }
 
 __device__ __forceinline__ DevExpert task_expert_of(const TaskMap& m, int task) {

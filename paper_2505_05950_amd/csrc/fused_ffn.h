@@ -45,6 +45,26 @@ __device__ __forceinline__ int lds_peek(const int* p) { return *(const volatile 
 __device__ __forceinline__ void lds_poke(int* p, int v) { *(volatile FLOE_LDS int*)p = v; }
 __device__ __forceinline__ void lds_poke(float* p, float v) { *(volatile FLOE_LDS float*)p = v; }
 
+// Codes that go from memory straight into LDS (global_load_lds_dwordx4: lane l's 16 bytes land at base + 16 l, no
+// register is held while the load is in flight, so a wave can keep many more passes on their way).  The compiler
+// knows no finer rule for such a load than "wait for all of them before any LDS read that may touch the same
+// array", which would serialise the pipeline; the read-back is therefore issued here by hand, after a wait that
+// names how many younger vector-memory operations may still be outstanding.
+template <int N>
+__device__ __forceinline__ void wait_vm_all_but() {  // s_waitcnt vmcnt(N) only (gfx9 encoding: bits 3:0 and 15:14)
+    static_assert(N >= 0 && N < 64, "vmcnt has six bits");
+    __builtin_amdgcn_s_waitcnt((N & 15) | (7 << 4) | (15 << 8) | ((N >> 4) << 14));
+}
+__device__ __forceinline__ void dma16_to_lds(const void* src, void* lds_wave_base) {
+    __builtin_amdgcn_global_load_lds((const FLOE_GLOBAL void*)src, (FLOE_LDS void*)lds_wave_base, 16, 0, 0);
+}
+__device__ __forceinline__ uint4 lds_read16_now(const void* lds_ptr) {
+    u32x4 q;
+    const uint32_t a = (uint32_t)(uintptr_t)(const FLOE_LDS void*)lds_ptr;
+    asm volatile("ds_read_b128 %0, %1\n\ts_waitcnt lgkmcnt(0)" : "=v"(q) : "v"(a) : "memory");
+    return make_uint4(q.x, q.y, q.z, q.w);
+}
+
 // ROUTED: the workgroup routes in place (INT2, <= 16 experts); otherwise the task's expert comes from `map`, its
 // threshold from task_tau and its output scale from task_scale (nullptr = 1).
 // kPasses channels-per-wave passes per producer, kDepth of them in flight.  v_out (optional): v[task][f].
@@ -119,9 +139,26 @@ __global__ __launch_bounds__(kFusedThreads, fused_wgs_per_cu) void fused_ffn_ker
             const int j = jw + p * CPW + sub;
             return j < f ? j : f - 1;  // keep the address in bounds; a clamped lane's result is not used
         };
+        // INT2: the codes of a pass travel straight into LDS, into the two result slabs of this producer's own
+        // consumers (unused until those have seen the producer's flag); only scale and zero take registers.
+        constexpr bool kDma = BITS == 2;
+        unsigned char* stage = reinterpret_cast<unsigned char*>(&yred[kFusedCpp * wave][0]);
+        static_assert(!kDma || kDepth * 1024 <= kFusedCpp * d * 4, "the staging ring must fit the two slabs");
         UnitLoad<BITS, UPC, G32> ld[kDepth];
+        auto issue = [&](int slot, int p) {
+            const int j = channel_of(p);
+            if constexpr (kDma) {
+                dma16_to_lds(e.codes + ((size_t)j * UPC + u) * 4, stage + slot * 1024);
+                ld[slot].issue_meta(e, j, u, G, gshift);
+            } else {
+                ld[slot].issue(e, j, u, G, gshift);
+            }
+        };
 #pragma unroll
-        for (int p = 0; p < kDepth; ++p) ld[p].issue(e, channel_of(p), u, G, gshift);
+        for (int p = 0; p < kDepth; ++p) {
+            issue(p, p);
+            __builtin_amdgcn_sched_barrier(0);  // the waits below count requests in exactly this order
+        }
         FLOE_TL(3);
 
         // This lane's 64 activations (the unit it owns in every channel), from the copy in LDS: read from memory,
@@ -168,8 +205,30 @@ __global__ __launch_bounds__(kFusedThreads, fused_wgs_per_cu) void fused_ffn_ker
                 const int p = p0 + i;
                 if (kPasses % kDepth != 0 && p >= kPasses) break;  // last, shorter round (wave-uniform)
                 const int j = jw + p * CPW + sub;
+                if constexpr (kDma) {
+                    // Pass p's codes have landed once only the requests made after them are outstanding: three per
+                    // pass (codes, scale, zero) and kDepth - 1 passes behind it.  That count is the same in every
+                    // round because the last round keeps requesting (see below).  More may be outstanding - a
+                    // store of v, say - which only makes the wait longer than needed.
+                    wait_vm_all_but<3 * (kDepth - 1)>();
+                    const uint4 q = lds_read16_now(stage + i * 1024 + lane * 16);
+                    ld[i].cw[0] = q.x; ld[i].cw[1] = q.y; ld[i].cw[2] = q.z; ld[i].cw[3] = q.w;
+                }
+                // scale and zero stay untouched until here (otherwise their unpacking is hoisted out of the loop for
+                // the first round, and with it a wait for every load of that round)
+                if constexpr (G32) asm volatile("" : "+v"(ld[i].s), "+v"(ld[i].z));
+                else asm volatile("" : "+v"(ld[i].sh), "+v"(ld[i].zh));
                 float part = unit_value<BITS, UPC, G32>(ld[i], xs, Xoff, Xg, magic);
-                if (p + kDepth < kPasses) ld[i].issue(e, channel_of(p + kDepth), u, G, gshift);
+                if constexpr (kDma) {
+                    // In the last round there is nothing left to request; the slot asks for the final pass again
+                    // (a cache hit that nobody reads) so that every round has the same, unconditional sequence of
+                    // requests: with a condition here the compiler has to assume that no request follows and makes
+                    // each round wait for all of its loads at once.
+                    const int pn = p + kDepth < kPasses ? p + kDepth : kPasses - 1;
+                    issue(i, pn);
+                } else {
+                    if (p + kDepth < kPasses) issue(i, p + kDepth);
+                }
                 part = group_reduce_sum_to_last<UPC>(part) * inv_p;
                 const bool mine = u == UPC - 1 && j < f;
                 if (v_out && mine) v_out[(size_t)task * f + j] = part;
@@ -189,6 +248,7 @@ __global__ __launch_bounds__(kFusedThreads, fused_wgs_per_cu) void fused_ffn_ker
                 __builtin_amdgcn_sched_barrier(0);  // keep the request for pass p + kDepth where it is
             }
         }
+        if constexpr (kDma) wait_vm_all_but<0>();  // the ring lies in the consumers' result slabs: nothing may land later
         if (lane == 0) {
             lds_poke(&done[wave], 1);  // after the last push, in program order
             atomicAdd(&n_sel, k);
@@ -279,9 +339,11 @@ template <int BITS, int UPC, bool G32>
 static hipError_t fused_launch_shape(const FusedArgs& a, int gshift, hipStream_t stream) {
     const dim3 grid(fused_blocks(a.d, a.f, a.passes), a.n_tasks), block(kFusedThreads);
     const RouteArgs ro = a.route ? *a.route : RouteArgs{};
-    constexpr int kDepth = BITS == 2 ? 7 : 4;  // passes in flight per producer wave (registers: 6 / 8 / 10 per pass)
+    // passes in flight per producer wave: INT2 stages its codes in LDS (2 registers per pass, the ring limited by
+    // the two result slabs it borrows: 8 d bytes); INT3 / INT4 hold them in registers (8 / 10 per pass)
+    constexpr int kDepth = BITS == 2 ? (UPC >= 32 ? 14 : 8) : 4;
 #define FLOE_FUSED_GO(ROUTED, P)                                                                                 \
-    fused_ffn_kernel<BITS, UPC, G32, ROUTED, P, kDepth><<<grid, block, 0, stream>>>(a.map, a.x, ro, a.task_tau,   \
+    fused_ffn_kernel<BITS, UPC, G32, ROUTED, P, (kDepth < P ? kDepth : P)><<<grid, block, 0, stream>>>(a.map, a.x, ro, a.task_tau,   \
                                                                                     a.task_scale, a.f, gshift,    \
                                                                                     a.v_out, a.partial, a.wg_count)
 #define FLOE_FUSED_PASSES(ROUTED)                                               \

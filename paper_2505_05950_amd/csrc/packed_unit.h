@@ -27,17 +27,22 @@ __device__ __forceinline__ void load_unit(const uint32_t* __restrict__ codes, si
 template <int BITS, int UPC, bool G32>
 struct UnitLoad {  // one pass of a lane: the unit's code words and its scale / zero
     uint32_t cw[PackedTraits<BITS>::kWords];
-    uint32_t s, z;  // one fp16 (groups >= 64) or two (groups of 32)
+    uint32_t s, z;  // groups of 32: the unit's two scales / zeros
+    h16 sh, zh;     // larger groups: its one scale / zero, kept as a half (a 16-bit load leaves the rest of the
+                    // register alone, so widening it to 32 bits would be an instruction that waits for the load)
     __device__ __forceinline__ void issue(const DevExpert& e, int j, int u, int G, int gshift) {
         load_unit<BITS>(e.codes, (size_t)j * UPC + u, cw);
+        issue_meta(e, j, u, G, gshift);
+    }
+    __device__ __forceinline__ void issue_meta(const DevExpert& e, int j, int u, int G, int gshift) {
         if (G32) {
             const size_t mi = (size_t)j * G + 2 * u;  // even index: 4-byte aligned
             s = gload4(e.scale + mi);
             z = gload4(e.zero + mi);
         } else {
             const size_t mi = (size_t)j * G + ((u * 64) >> gshift);
-            s = gload2(e.scale + mi);
-            z = gload2(e.zero + mi);
+            sh = gloadh(e.scale + mi);
+            zh = gloadh(e.zero + mi);
         }
     }
 };
@@ -53,7 +58,7 @@ __device__ __forceinline__ float unit_value(const UnitLoad<BITS, UPC, G32>& L, c
         const h16x2 s2 = as_h2(L.s), z2 = as_h2(L.z);
         return (float)s2.x * fmaf(-(float)z2.x, Xg[0], dot0 - Xoff[0]) + (float)s2.y * fmaf(-(float)z2.y, Xg[1], dot1 - Xoff[1]);
     }
-    const float sc = (float)as_h2(L.s).x, z = (float)as_h2(L.z).x;
+    const float sc = (float)L.sh, z = (float)L.zh;
     return sc * fmaf(-z, Xg[0] + Xg[1], (dot0 + dot1) - (Xoff[0] + Xoff[1]));
 }
 
