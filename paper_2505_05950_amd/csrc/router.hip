@@ -62,19 +62,27 @@ __device__ __forceinline__ void route_select_wave64(float logit, int lane, int n
 
 // One workgroup of 16 waves per token.  A wave takes experts wave, wave + 16, ... and keeps kInFlight rows in flight
 // at a time (all 16-byte pieces of a row and of x requested before the packed dot products run), so a layer with
-// 64 experts costs two round trips to memory, not sixteen.  NV = d / 512 pieces per lane.
+// 64 experts of d <= 2048 costs one round trip to memory, not sixteen.  NV = d / 512 pieces per lane.
 template <int NV>
 __global__ __launch_bounds__(1024) void router_kernel(RouterArgs a) {
-    constexpr int kInFlight = NV <= 2 ? 4 : (NV <= 4 ? 2 : 1);
+    constexpr int kInFlight = NV <= 4 ? 4 : (NV <= 8 ? 2 : 1);
     __shared__ float prob[kMaxExperts];
     __shared__ int sel_id[64];
     __shared__ float sel_w[64];
+    __shared__ DevExpert tab[kMaxExperts + 64];
+    __shared__ float taus[kMaxExperts + 64];
     const int t = blockIdx.x;
     const int tid = threadIdx.x;
     const int wave = tid >> 6, lane = tid & 63;
     constexpr int d = NV * 512;
     const int slots = a.top_k + a.n_shared;
     const h16* xt = a.x + (size_t)t * d;
+    // every expert's table entry and threshold travel beside the router rows, so that resolving the picks costs
+    // no further round trip to memory
+    for (int e = tid; e < a.n_experts + a.n_shared; e += 1024) {
+        tab[e] = a.table[e];
+        taus[e] = a.tau[(size_t)t * a.tau_stride_t + e];
+    }
     if (a.top_k > 0) {
         uint4 xv[NV];
         const uint4* xp = reinterpret_cast<const uint4*>(xt);
@@ -125,8 +133,8 @@ __global__ __launch_bounds__(1024) void router_kernel(RouterArgs a) {
         const int q = t * slots + tid;
         a.task_expert[q] = e;
         a.task_weight[q] = sel_w[tid];
-        a.task_tau[q] = a.tau[(size_t)t * a.tau_stride_t + e];
-        a.task_table[q] = a.table[e];
+        a.task_tau[q] = taus[e];
+        a.task_table[q] = tab[e];
     }
 }
 
