@@ -55,14 +55,26 @@ __device__ __forceinline__ void wait_vm_all_but() {  // s_waitcnt vmcnt(N) only 
     static_assert(N >= 0 && N < 64, "vmcnt has six bits");
     __builtin_amdgcn_s_waitcnt((N & 15) | (7 << 4) | (15 << 8) | ((N >> 4) << 14));
 }
+// A lane's unit of 64 codes travels in kPieces loads of 16 bytes; piece k of all 64 lanes lands contiguously at
+// slot + k * 1024.  kPieces = 0: the width keeps its codes in registers.  Only INT2 is staged: INT4 (two pieces per
+// unit) measured slower that way (16.8 against 15.9 us per expert at 90 %), INT3 units are 24 bytes, 8-byte aligned.
+template <int BITS> struct StageTraits;
+template <> struct StageTraits<2> { static constexpr int kPieces = 1, kPieceBytes = 16; };
+template <> struct StageTraits<3> { static constexpr int kPieces = 0, kPieceBytes = 16; };
+template <> struct StageTraits<4> { static constexpr int kPieces = 0, kPieceBytes = 16; };
+template <int BITS> constexpr int stage_slot_bytes() { return StageTraits<BITS>::kPieces * StageTraits<BITS>::kPieceBytes * 64; }
+template <int BITS> constexpr bool staged_codes() { return StageTraits<BITS>::kPieces > 0; }
+
 __device__ __forceinline__ void dma16_to_lds(const void* src, void* lds_wave_base) {
     __builtin_amdgcn_global_load_lds((const FLOE_GLOBAL void*)src, (FLOE_LDS void*)lds_wave_base, 16, 0, 0);
 }
-__device__ __forceinline__ uint4 lds_read16_now(const void* lds_ptr) {
+// read a lane's piece back at once (the wait for the LDS result is part of the statement: the compiler does not
+// know that a load is outstanding)
+__device__ __forceinline__ void lds_read_now(const void* lds_ptr, uint32_t (&w)[4]) {
     u32x4 q;
     const uint32_t a = (uint32_t)(uintptr_t)(const FLOE_LDS void*)lds_ptr;
     asm volatile("ds_read_b128 %0, %1\n\ts_waitcnt lgkmcnt(0)" : "=v"(q) : "v"(a) : "memory");
-    return make_uint4(q.x, q.y, q.z, q.w);
+    w[0] = q.x; w[1] = q.y; w[2] = q.z; w[3] = q.w;
 }
 
 // ROUTED: the workgroup routes in place (INT2, <= 16 experts); otherwise the task's expert comes from `map`, its
@@ -139,16 +151,22 @@ __global__ __launch_bounds__(kFusedThreads, fused_wgs_per_cu) void fused_ffn_ker
             const int j = jw + p * CPW + sub;
             return j < f ? j : f - 1;  // keep the address in bounds; a clamped lane's result is not used
         };
-        // INT2: the codes of a pass travel straight into LDS, into the two result slabs of this producer's own
-        // consumers (unused until those have seen the producer's flag); only scale and zero take registers.
-        constexpr bool kDma = BITS == 2;
+        // The codes of a pass travel straight into LDS, into the two result slabs of this producer's own consumers
+        // (unused until those have seen the producer's flag); only scale and zero take registers.
+        using St = StageTraits<BITS>;
+        constexpr bool kStaged = staged_codes<BITS>();
+        constexpr int kSlot = stage_slot_bytes<BITS>();
+        constexpr int kVmPerPass = St::kPieces + 2;  // requests per pass: the pieces, scale, zero
         unsigned char* stage = reinterpret_cast<unsigned char*>(&yred[kFusedCpp * wave][0]);
-        static_assert(!kDma || kDepth * 1024 <= kFusedCpp * d * 4, "the staging ring must fit the two slabs");
+        static_assert(!kStaged || kDepth * kSlot <= kFusedCpp * d * 4, "the staging ring must fit the two slabs");
+        static_assert(!kStaged || kVmPerPass * (kDepth - 1) < 64, "the wait counts outstanding requests in six bits");
         UnitLoad<BITS, UPC, G32> ld[kDepth];
         auto issue = [&](int slot, int p) {
             const int j = channel_of(p);
-            if constexpr (kDma) {
-                dma16_to_lds(e.codes + ((size_t)j * UPC + u) * 4, stage + slot * 1024);
+            if constexpr (kStaged) {
+                const unsigned char* src = reinterpret_cast<const unsigned char*>(e.codes) + ((size_t)j * UPC + u) * (BITS * 8);
+#pragma unroll
+                for (int pc = 0; pc < St::kPieces; ++pc) dma16_to_lds(src + pc * 16, stage + slot * kSlot + pc * 1024);
                 ld[slot].issue_meta(e, j, u, G, gshift);
             } else {
                 ld[slot].issue(e, j, u, G, gshift);
@@ -205,21 +223,26 @@ __global__ __launch_bounds__(kFusedThreads, fused_wgs_per_cu) void fused_ffn_ker
                 const int p = p0 + i;
                 if (kPasses % kDepth != 0 && p >= kPasses) break;  // last, shorter round (wave-uniform)
                 const int j = jw + p * CPW + sub;
-                if constexpr (kDma) {
-                    // Pass p's codes have landed once only the requests made after them are outstanding: three per
-                    // pass (codes, scale, zero) and kDepth - 1 passes behind it.  That count is the same in every
-                    // round because the last round keeps requesting (see below).  More may be outstanding - a
-                    // store of v, say - which only makes the wait longer than needed.
-                    wait_vm_all_but<3 * (kDepth - 1)>();
-                    const uint4 q = lds_read16_now(stage + i * 1024 + lane * 16);
-                    ld[i].cw[0] = q.x; ld[i].cw[1] = q.y; ld[i].cw[2] = q.z; ld[i].cw[3] = q.w;
+                // Pass p's codes have landed once only the requests made after them are outstanding: kVmPerPass per
+                // pass, kDepth - 1 passes behind it.  That count is the same in every round because the last round
+                // keeps requesting (see below).  More may be outstanding - a store of v, say - which only makes the
+                // wait longer than needed.
+                if constexpr (kStaged) {
+                    wait_vm_all_but<kVmPerPass * (kDepth - 1)>();
+#pragma unroll
+                    for (int pc = 0; pc < St::kPieces; ++pc) {
+                        uint32_t w[4];
+                        lds_read_now(stage + i * kSlot + pc * 1024 + lane * 16, w);
+#pragma unroll
+                        for (int q = 0; q < 4; ++q) ld[i].cw[pc * 4 + q] = w[q];
+                    }
                 }
                 // scale and zero stay untouched until here (otherwise their unpacking is hoisted out of the loop for
                 // the first round, and with it a wait for every load of that round)
                 if constexpr (G32) asm volatile("" : "+v"(ld[i].s), "+v"(ld[i].z));
                 else asm volatile("" : "+v"(ld[i].sh), "+v"(ld[i].zh));
                 float part = unit_value<BITS, UPC, G32>(ld[i], xs, Xoff, Xg, magic);
-                if constexpr (kDma) {
+                if constexpr (kStaged) {
                     // In the last round there is nothing left to request; the slot asks for the final pass again
                     // (a cache hit that nobody reads) so that every round has the same, unconditional sequence of
                     // requests: with a condition here the compiler has to assume that no request follows and makes
@@ -248,7 +271,7 @@ __global__ __launch_bounds__(kFusedThreads, fused_wgs_per_cu) void fused_ffn_ker
                 __builtin_amdgcn_sched_barrier(0);  // keep the request for pass p + kDepth where it is
             }
         }
-        if constexpr (kDma) wait_vm_all_but<0>();  // the ring lies in the consumers' result slabs: nothing may land later
+        if constexpr (kStaged) wait_vm_all_but<0>();  // the ring lies in the consumers' result slabs: nothing may land later
         if (lane == 0) {
             lds_poke(&done[wave], 1);  // after the last push, in program order
             atomicAdd(&n_sel, k);
@@ -339,9 +362,11 @@ template <int BITS, int UPC, bool G32>
 static hipError_t fused_launch_shape(const FusedArgs& a, int gshift, hipStream_t stream) {
     const dim3 grid(fused_blocks(a.d, a.f, a.passes), a.n_tasks), block(kFusedThreads);
     const RouteArgs ro = a.route ? *a.route : RouteArgs{};
-    // passes in flight per producer wave: INT2 stages its codes in LDS (2 registers per pass, the ring limited by
-    // the two result slabs it borrows: 8 d bytes); INT3 / INT4 hold them in registers (8 / 10 per pass)
-    constexpr int kDepth = BITS == 2 ? (UPC >= 32 ? 14 : 8) : 4;
+    // passes in flight per producer wave: INT2 stages 14 KB of codes in LDS, as far as the ring fits the two result
+    // slabs it borrows (8 d bytes); INT3 and INT4 hold 4 passes in registers (8 / 10 per pass)
+    constexpr int kWant = BITS == 2 ? 14 : 7;
+    constexpr int kFit = staged_codes<BITS>() ? kFusedCpp * UPC * 64 * 4 / stage_slot_bytes<BITS>() : 4;
+    constexpr int kDepth = staged_codes<BITS>() ? (kWant < kFit ? kWant : kFit) : 4;
 #define FLOE_FUSED_GO(ROUTED, P)                                                                                 \
     fused_ffn_kernel<BITS, UPC, G32, ROUTED, P, (kDepth < P ? kDepth : P)><<<grid, block, 0, stream>>>(a.map, a.x, ro, a.task_tau,   \
                                                                                     a.task_scale, a.f, gshift,    \
