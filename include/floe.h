@@ -22,7 +22,8 @@
  *  - Quantized up projection: codes uint32 [f][d*bits/32], a little-endian bit stream per channel
  *    (code i at bits [bits*i, bits*i+bits)); scale, zero fp16 [f][d/group]; groups run along d.
  *    w_hat = (code - zero) * scale.
- *  - Supported shapes: bits in {2,3,4}; group a power of two in [32, 256]; d % 512 == 0, d <= 8192,
+ *  - Supported shapes: bits in {1,2,3,4,8} (the widths of the sensitivity study in Sec. 3.2.2; 2, 3 and 4 have
+ *    tuned kernels, 1 and 8 run the generic ones); group a power of two in [32, 256]; d % 512 == 0, d <= 8192,
  *    d % group == 0; 1 <= f <= 2^20; 0 <= T <= 4096.  Anything else returns an error code and
  *    enqueues nothing.
  *  - Return value: FLOE_OK (0) or a negative floe_status.  No exceptions, no errno.
@@ -44,7 +45,7 @@ typedef enum {
     FLOE_OK = 0,
     FLOE_EINVAL = -1,       /* NULL pointer, negative size, misaligned buffer */
     FLOE_ESHAPE = -2,       /* d % group != 0, (group*bits) % 32 != 0, d % 512 != 0 ... */
-    FLOE_EUNSUPPORTED = -3, /* bits not in {2,3,4}, group not in {32,64,128,256}, d > 8192 ... */
+    FLOE_EUNSUPPORTED = -3, /* bits not in {1,2,3,4,8}, group not in {32,64,128,256}, d > 8192 ... */
     FLOE_EWORKSPACE = -4,   /* workspace_bytes smaller than the matching *_workspace_bytes() */
     FLOE_EHIP = -5          /* a HIP runtime call failed (see floe_last_hip_error) */
 } floe_status;

@@ -83,7 +83,8 @@ uint16_t float_to_half(float x) { return double_to_half((double)x); }
 
 bool shape_ok(int f, int d, int bits, int group) {
     if (f < 0 || d <= 0 || group <= 0) return false;
-    if (bits != 2 && bits != 3 && bits != 4) return false;
+    // the widths of the paper's sensitivity study (Sec. 3.2.2: INT8, INT4, INT3, INT2, INT1); the arithmetic is the same
+    if (bits != 1 && bits != 2 && bits != 3 && bits != 4 && bits != 8) return false;
     if (d % group != 0) return false;
     if ((group * bits) % 32 != 0) return false;
     return true;

@@ -61,7 +61,7 @@ bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) %
 int check_shape(const floe_shape* s) {
     if (!s) return FLOE_EINVAL;
     if (s->d <= 0 || s->f <= 0 || s->group <= 0) return FLOE_EINVAL;
-    if (s->bits != 2 && s->bits != 3 && s->bits != 4) return FLOE_EUNSUPPORTED;
+    if (s->bits != 1 && s->bits != 2 && s->bits != 3 && s->bits != 4 && s->bits != 8) return FLOE_EUNSUPPORTED;
     if (s->group != 32 && s->group != 64 && s->group != 128 && s->group != 256) return FLOE_EUNSUPPORTED;
     if (s->d % s->group != 0) return FLOE_ESHAPE;
     if ((s->group * s->bits) % 32 != 0) return FLOE_ESHAPE;

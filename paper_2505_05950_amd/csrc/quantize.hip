@@ -111,6 +111,8 @@ hipError_t launch_quantize(const h16* w, uint32_t* codes, h16* scale, h16* zero,
     if (f == 0) return hipSuccess;
     dim3 grid(f), block(256);
     switch (bits) {
+        case 1: quantize_kernel<1><<<grid, block, 0, stream>>>(w, codes, scale, zero, d, group); break;
+        case 8: quantize_kernel<8><<<grid, block, 0, stream>>>(w, codes, scale, zero, d, group); break;
         case 2: quantize_kernel<2><<<grid, block, 0, stream>>>(w, codes, scale, zero, d, group); break;
         case 3: quantize_kernel<3><<<grid, block, 0, stream>>>(w, codes, scale, zero, d, group); break;
         default: quantize_kernel<4><<<grid, block, 0, stream>>>(w, codes, scale, zero, d, group); break;

@@ -318,6 +318,8 @@ hipError_t launch_up_gemv(const TaskMap& map, const h16* x, const RouteArgs* rou
     if (route != nullptr) return hipErrorInvalidValue;  // in-place routing exists only in the packed INT2 kernel
     dim3 grid((f + 31) / 32, n_tasks);
     switch (bits) {
+        case 1: up_gemv_generic_kernel<1><<<grid, block, 0, stream>>>(map, x, v, task_tau, mask_words, d, f, gshift); break;
+        case 8: up_gemv_generic_kernel<8><<<grid, block, 0, stream>>>(map, x, v, task_tau, mask_words, d, f, gshift); break;
         case 2: up_gemv_generic_kernel<2><<<grid, block, 0, stream>>>(map, x, v, task_tau, mask_words, d, f, gshift); break;
         case 3: up_gemv_generic_kernel<3><<<grid, block, 0, stream>>>(map, x, v, task_tau, mask_words, d, f, gshift); break;
         default: up_gemv_generic_kernel<4><<<grid, block, 0, stream>>>(map, x, v, task_tau, mask_words, d, f, gshift); break;

@@ -112,6 +112,12 @@ def test_layer_only_shared_experts():
     _run_layer_case(12, 5, 1024, 512, 4, 64, 0, 2, 0, False, 3, 70)
 
 
+def test_layer_with_the_other_widths_of_the_sensitivity_study():
+    # INT8 and INT1 (Sec. 3.2.2 compares INT8 ... INT1): same path through the generic kernels
+    _run_layer_case(14, 3, 1024, 640, 8, 64, 4, 0, 2, True, 2, 80)
+    _run_layer_case(15, 3, 2048, 512, 1, 64, 4, 1, 2, False, 3, 60)
+
+
 def test_layer_top_k_equals_all_experts():
     _run_layer_case(13, 3, 1024, 768, 2, 64, 4, 0, 4, True, 2, 50)
 

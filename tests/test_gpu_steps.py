@@ -26,6 +26,7 @@ def _gc():
     (2, 64, 1024, 257), (2, 64, 4096, 96), (2, 128, 2048, 33), (2, 32, 512, 64), (2, 256, 1536, 17),
     (3, 32, 2048, 65), (3, 64, 4096, 40), (3, 128, 1024, 9),
     (4, 32, 512, 31), (4, 64, 4096, 48), (4, 256, 2560, 12), (2, 64, 8192, 8),
+    (1, 64, 4096, 40), (1, 32, 1024, 33), (8, 64, 4096, 24), (8, 128, 1536, 19),   # the other widths of the sensitivity study
 ])
 def test_quantize_bit_exact(bits, group, d, f):
     G = _gc()
@@ -67,6 +68,10 @@ def test_quantize_config1_shape_bit_exact():
     (4, 32, 1024, 65, 2),
     (4, 32, 512, 64, 5),        # generic path (d = 512)
     (3, 64, 2560, 41, 1),       # generic path
+    (1, 64, 4096, 130, 2),      # INT1 and INT8 run the generic kernels
+    (1, 32, 1024, 70, 1),
+    (8, 64, 4096, 99, 1),
+    (8, 128, 2048, 65, 3),
 ])
 def test_up_gemv_matches_oracle(bits, group, d, f, T):
     G = _gc()
@@ -180,6 +185,8 @@ def test_gate_down_on_oracle_lists(d, f, bits, group, T, pct):
     (2048, 1408, 3, 32, 3, [85, 85, 60]),           # config 5 expert
     (1536, 515, 4, 64, 2, [90, 70]),
     (4096, 2000, 2, 128, 2, [90, 80]),
+    (2048, 600, 1, 64, 2, [80, 50]),                # INT1 and INT8 (generic kernels)
+    (1024, 900, 8, 32, 2, [90, 70]),
 ])
 def test_expert_ffn_sparse_matches_oracle(d, f, bits, group, T, pcts):
     G = _gc()

@@ -65,7 +65,7 @@ def test_degenerate_group_is_exact():
     assert np.array_equal(O.dequantize(codes, scale, zero, 32, 4, 8), w.astype(np.float32))
 
 
-@pytest.mark.parametrize("bits,group", [(2, 16), (2, 64), (3, 32), (3, 64), (4, 8), (4, 64)])
+@pytest.mark.parametrize("bits,group", [(2, 16), (2, 64), (3, 32), (3, 64), (4, 8), (4, 64), (1, 32), (1, 64), (8, 4), (8, 64)])
 def test_packing_is_little_endian_bitstream(bits, group):
     # weights that sit exactly on the quantization grid: level * 0.5 with both end levels present in
     # every group, so scale = 0.5, zero = 0 and code == level by construction
@@ -85,7 +85,7 @@ def test_packing_is_little_endian_bitstream(bits, group):
 
 
 # ---------------------------------------------------------------- quantizer: properties on workload-like data
-@pytest.mark.parametrize("bits,group", [(2, 64), (3, 32), (4, 64)])
+@pytest.mark.parametrize("bits,group", [(2, 64), (3, 32), (4, 64), (1, 64), (8, 64)])
 def test_roundtrip_bound_and_end_codes(bits, group):
     d, f = 512, 96
     w = S.normal_f16(S.stream_key(3, 99, S.KIND_W_UP, 0, bits), (f, d), S.W_SIGMA)
@@ -146,7 +146,7 @@ def test_compression_arithmetic():
 
 
 # ---------------------------------------------------------------- dequant GEMV
-@pytest.mark.parametrize("bits,group", [(2, 64), (3, 32), (4, 64)])
+@pytest.mark.parametrize("bits,group", [(2, 64), (3, 32), (4, 64), (1, 128), (8, 32)])
 def test_up_gemv_is_plain_matvec_on_dequantized_matrix(bits, group):
     d, f = 768, 40
     w = S.normal_f16(S.stream_key(6, 99, S.KIND_W_UP, 0, bits), (f, d), S.W_SIGMA)
