@@ -394,34 +394,36 @@ __global__ __launch_bounds__(kMfmaThreads) void up_gemv_mfma_kernel(const DevExp
 
 // ---------------------------------------------------------------------------------------------------
 // Grouping: for every expert the ascending list of tasks (token, slot) routed to it, cut into chunks of
-// `chunk` tasks.  One workgroup; thread e owns expert e.  Deterministic (ascending expert, ascending task).
+// `chunk` tasks.  One workgroup of 16 waves; a wave owns experts wave, wave + 16, ... and walks the task list
+// 64 tasks at a time: the lanes compare, a ballot gives the matches and a lane's place among them.
+// Deterministic (ascending expert, ascending task).  The task ids pass through LDS in tiles.
 // ---------------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(1024) void group_tokens_kernel(const int32_t* __restrict__ task_expert, int n_tasks,
                                                             int n_all, int chunk, TokenGroup* __restrict__ groups,
                                                             int32_t* __restrict__ n_groups) {
-    constexpr int kTile = 4096;  // task ids pass through LDS in tiles, so a thread's scan costs LDS reads only
-    __shared__ int first_group[1024 + 64 + 1];
+    constexpr int kTile = 4096;
+    constexpr int kWaves = 16;
+    __shared__ int first_group[1024 + 64 + 1];  // n_all <= 1088 (1024 routed + 64 shared)
+    __shared__ int count[1024 + 64];
     __shared__ int tile[kTile];
     const int tid = threadIdx.x;
-    // n_all <= 1088 (1024 routed + 64 shared): a thread owns expert tid and, if there are that many, tid + 1024
-    int cnt[2] = {0, 0};
+    const int wave = tid >> 6, lane = tid & 63;
+    const unsigned long long below = (1ull << lane) - 1ull;
+    // pass 1: tasks per expert
+    for (int e = tid; e < n_all; e += 1024) count[e] = 0;
     for (int base = 0; base < n_tasks; base += kTile) {
         const int n = min(kTile, n_tasks - base);
         __syncthreads();
-        for (int i = tid; i < n; i += blockDim.x) tile[i] = task_expert[base + i];
+        for (int i = tid; i < n; i += 1024) tile[i] = task_expert[base + i];
         __syncthreads();
-#pragma unroll
-        for (int h = 0; h < 2; ++h) {
-            const int e = tid + 1024 * h;
-            if (e < n_all) {
-#pragma unroll 16
-                for (int i = 0; i < n; ++i) cnt[h] += tile[i] == e;
-            }
+        for (int e = wave; e < n_all; e += kWaves) {
+            int c = 0;
+            for (int i0 = 0; i0 < n; i0 += kWave) c += __popcll(__ballot(i0 + lane < n && tile[i0 + lane] == e));
+            if (lane == 0) count[e] += c;  // only this wave touches count[e]
         }
     }
-#pragma unroll
-    for (int h = 0; h < 2; ++h)
-        if (tid + 1024 * h < n_all) first_group[tid + 1024 * h + 1] = (cnt[h] + chunk - 1) / chunk;
+    __syncthreads();
+    for (int e = tid; e < n_all; e += 1024) first_group[e + 1] = (count[e] + chunk - 1) / chunk;
     __syncthreads();
     if (tid == 0) {
         first_group[0] = 0;
@@ -429,31 +431,34 @@ __global__ __launch_bounds__(1024) void group_tokens_kernel(const int32_t* __res
         n_groups[0] = first_group[n_all];
     }
     __syncthreads();
-    int gi[2], k[2] = {0, 0};
-#pragma unroll
-    for (int h = 0; h < 2; ++h) gi[h] = tid + 1024 * h < n_all ? first_group[tid + 1024 * h] : 0;
+    // group headers
+    for (int e = wave; e < n_all; e += kWaves) {
+        const int g0 = first_group[e], ng = first_group[e + 1] - g0, c = count[e];
+        for (int g = lane; g < ng; g += kWave) {
+            groups[g0 + g].expert = e;
+            groups[g0 + g].n = min(chunk, c - g * chunk);
+        }
+    }
+    // pass 2: the tasks, in ascending order, into their chunks
     for (int base = 0; base < n_tasks; base += kTile) {
         const int n = min(kTile, n_tasks - base);
         __syncthreads();
-        for (int i = tid; i < n; i += blockDim.x) tile[i] = task_expert[base + i];
+        for (int i = tid; i < n; i += 1024) tile[i] = task_expert[base + i];
         __syncthreads();
-#pragma unroll
-        for (int h = 0; h < 2; ++h) {
-            const int e = tid + 1024 * h;
-            if (e >= n_all) continue;
-            for (int i0 = 0; i0 < n; i0 += 16) {
-                int own[16];  // sixteen LDS reads in flight, then the (rare) matches in order
-#pragma unroll
-                for (int j = 0; j < 16; ++j) own[j] = tile[min(i0 + j, n - 1)];
-#pragma unroll
-                for (int j = 0; j < 16; ++j) {
-                    if (own[j] != e || i0 + j >= n) continue;
-                    if (k[h] == 0) { groups[gi[h]].expert = e; groups[gi[h]].n = 0; }
-                    groups[gi[h]].task[k[h]] = base + i0 + j;
-                    groups[gi[h]].n = ++k[h];
-                    if (k[h] == chunk) { ++gi[h]; k[h] = 0; }
+        for (int e = wave; e < n_all; e += kWaves) {
+            // position of the first task of this tile among the expert's tasks: what earlier tiles held (count[] is
+            // re-used as that running position; the totals went into the headers)
+            int k = base == 0 ? 0 : count[e];
+            for (int i0 = 0; i0 < n; i0 += kWave) {
+                const bool match = i0 + lane < n && tile[i0 + lane] == e;
+                const unsigned long long m = __ballot(match);
+                if (match) {
+                    const int pos = k + __popcll(m & below);
+                    groups[first_group[e] + pos / chunk].task[pos % chunk] = base + i0 + lane;
                 }
+                k += __popcll(m);
             }
+            if (lane == 0) count[e] = k;
         }
     }
 }
