@@ -301,3 +301,23 @@ def test_offloaded_layer_matches_resident_layer_and_oracle():
                     sel = O.select(v, float(tau[t, e]))[:cap]
                     acc += ref["weights"][t, s_] * O.sparse_ffn(experts_np[e][3], x[t], v, sel)[1]
                 assert G.rel_err(y[t].cpu().numpy().astype(np.float64), acc) <= G.Y_TIGHT
+
+
+def test_layer_randomized_shapes():
+    """Seeded sweep over shapes, widths, routing and sparsity levels (every dispatch branch several times over)."""
+    import random
+    rng = random.Random(20250505)
+    for i in range(24):
+        d = rng.choice([1024, 2048, 4096, 4096])
+        bits = rng.choice([2, 2, 2, 3, 4])
+        group = rng.choice([32, 64, 64, 128])
+        f = rng.choice([rng.randint(120, 400), rng.randint(400, 1800)]) if d == 4096 else rng.randint(120, 2500)
+        n = rng.randint(2, 16)
+        n_shared = rng.choice([0, 0, 1, 2])
+        top_k = rng.randint(1, min(n, 6))
+        renorm = rng.choice([True, False])
+        T = rng.choice([1, 1, 2, 3, 5, 8])
+        pct = rng.choice([0, 50, 80, 90, 95])
+        print(f"case {i}: d={d} f={f} bits={bits} group={group} n={n}+{n_shared} top{top_k} renorm={renorm} T={T} pct={pct}",
+              flush=True)
+        _run_layer_case(2000 + i, 3, d, f, bits, group, n, n_shared, top_k, renorm, T, pct)
