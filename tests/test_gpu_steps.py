@@ -215,6 +215,21 @@ def test_expert_ffn_sparse_matches_oracle(d, f, bits, group, T, pcts):
             assert np.all(np.abs(y[t] - y_ref) <= G.Y_BAR * np.abs(y_ref).max() + slack)
 
 
+def test_expert_ffn_randomized_shapes():
+    """Seeded sweep of the one-expert entry point over shapes, widths, batch sizes and sparsity levels."""
+    import random
+    rng = random.Random(505950)
+    for i in range(16):
+        d = rng.choice([1024, 2048, 4096, 1536])
+        bits = rng.choice([2, 2, 3, 4])
+        group = rng.choice([32, 64, 128])
+        f = rng.randint(120, 1500) if d >= 2048 else rng.randint(120, 3000)
+        T = rng.choice([1, 1, 2, 4, 7, 16, 20])
+        pcts = [rng.choice([0, 50, 80, 90, 95]) for _ in range(T)]
+        print(f"case {i}: d={d} f={f} bits={bits} group={group} T={T} pcts={pcts}", flush=True)
+        test_expert_ffn_sparse_matches_oracle(d, f, bits, group, T, pcts)
+
+
 @pytest.mark.parametrize("d,f,bits,group,T", [(4096, 530, 2, 64, 3), (2048, 1000, 3, 32, 2), (1024, 300, 4, 128, 17),
                                               (512, 400, 2, 64, 2)])
 def test_expert_ffn_without_a_list_gives_the_same_result(d, f, bits, group, T):
