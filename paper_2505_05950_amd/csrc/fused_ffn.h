@@ -102,7 +102,7 @@ __global__ __launch_bounds__(kFusedThreads, fused_wgs_per_cu) void fused_ffn_ker
     __shared__ float yred[kFusedConsumers][d];
     __shared__ uint4 xlds[d / 8];               // the token, for the consumers' gate dot products
     const int tid = threadIdx.x;
-    const int wave = tid >> 6, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;  // the wave index as a scalar
     const int task = blockIdx.y;
     const int t = task / map.slots;
     const int slot = task - t * map.slots;
@@ -114,7 +114,7 @@ __global__ __launch_bounds__(kFusedThreads, fused_wgs_per_cu) void fused_ffn_ker
     FLOE_TL(0);
 
     const bool producer = wave < kFusedProducers;
-    const int u = lane % UPC, sub = lane / UPC;
+    const int u = lane % UPC, sub = CPW == 1 ? 0 : lane / UPC;
     DevExpert e;
     float tau;
     Pick16 pick{};
