@@ -161,13 +161,17 @@ __global__ __launch_bounds__(kFusedThreads, fused_wgs_per_cu) void fused_ffn_ker
         static_assert(!kStaged || kDepth * kSlot <= kFusedCpp * d * 4, "the staging ring must fit the two slabs");
         static_assert(!kStaged || kVmPerPass * (kDepth - 1) < 64, "the wait counts outstanding requests in six bits");
         UnitLoad<BITS, UPC, G32> ld[kDepth];
+        // the lane's part of the three addresses of a pass; the channel's part is a scalar at d = 4096
+        const unsigned char* lane_codes = reinterpret_cast<const unsigned char*>(e.codes) + (size_t)u * (BITS * 8);
+        const h16* lane_scale = e.scale + (G32 ? 2 * u : (u * 64) >> gshift);
+        const h16* lane_zero = e.zero + (G32 ? 2 * u : (u * 64) >> gshift);
         auto issue = [&](int slot, int p) {
             const int j = channel_of(p);
             if constexpr (kStaged) {
-                const unsigned char* src = reinterpret_cast<const unsigned char*>(e.codes) + ((size_t)j * UPC + u) * (BITS * 8);
+                const unsigned char* src = lane_codes + (size_t)j * (UPC * BITS * 8);
 #pragma unroll
                 for (int pc = 0; pc < St::kPieces; ++pc) dma16_to_lds(src + pc * 16, stage + slot * kSlot + pc * 1024);
-                ld[slot].issue_meta(e, j, u, G, gshift);
+                ld[slot].issue_meta_at(lane_scale, lane_zero, (size_t)j * G);
             } else {
                 ld[slot].issue(e, j, u, G, gshift);
             }

@@ -34,6 +34,17 @@ struct UnitLoad {  // one pass of a lane: the unit's code words and its scale / 
         load_unit<BITS>(e.codes, (size_t)j * UPC + u, cw);
         issue_meta(e, j, u, G, gshift);
     }
+    // the same with the lane's part of the address precomputed: lane_scale / lane_zero point at the lane's entry of
+    // channel 0 and row is the channel's offset in entries (a scalar where the channel is the same for every lane)
+    __device__ __forceinline__ void issue_meta_at(const h16* lane_scale, const h16* lane_zero, size_t row) {
+        if (G32) {
+            s = gload4(lane_scale + row);
+            z = gload4(lane_zero + row);
+        } else {
+            sh = gloadh(lane_scale + row);
+            zh = gloadh(lane_zero + row);
+        }
+    }
     __device__ __forceinline__ void issue_meta(const DevExpert& e, int j, int u, int G, int gshift) {
         if (G32) {
             const size_t mi = (size_t)j * G + 2 * u;  // even index: 4-byte aligned

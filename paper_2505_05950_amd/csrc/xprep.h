@@ -98,30 +98,18 @@ template <int BITS>
 __device__ __forceinline__ float half_unit_dot(const uint32_t* cw, const uint32_t (&xs)[32], int h, uint32_t magic) {
     float dot = 0.0f;
     if (BITS == 2) {
-        // the two words of the half feed accumulators of their own, turn and turn about: a dot product that
-        // continues the sum of the instruction right before it has to wait for that result
-        const uint32_t W0 = cw[2 * h], a0 = W0 << 4, b0 = W0 >> 6;
-        const uint32_t W1 = cw[2 * h + 1], a1 = W1 << 4, b1 = W1 >> 6;
-        const uint32_t* x0 = &xs[16 * h];
-        const uint32_t* x1 = &xs[16 * h + 8];
-        float dot1 = 0.0f;
-        dot = dot2(x0[0], and_or(a0, 0x00300030u, magic), dot);
-        dot1 = dot2(x1[0], and_or(a1, 0x00300030u, magic), dot1);
-        dot = dot2(x0[1], and_or(a0, 0x00C000C0u, magic), dot);
-        dot1 = dot2(x1[1], and_or(a1, 0x00C000C0u, magic), dot1);
-        dot = dot2(x0[2], and_or(W0, 0x00300030u, magic), dot);
-        dot1 = dot2(x1[2], and_or(W1, 0x00300030u, magic), dot1);
-        dot = dot2(x0[3], and_or(W0, 0x00C000C0u, magic), dot);
-        dot1 = dot2(x1[3], and_or(W1, 0x00C000C0u, magic), dot1);
-        dot = dot2(x0[4], and_or(W0, 0x03000300u, magic), dot);
-        dot1 = dot2(x1[4], and_or(W1, 0x03000300u, magic), dot1);
-        dot = dot2(x0[5], and_or(b0, 0x00300030u, magic), dot);
-        dot1 = dot2(x1[5], and_or(b1, 0x00300030u, magic), dot1);
-        dot = dot2(x0[6], and_or(b0, 0x00C000C0u, magic), dot);
-        dot1 = dot2(x1[6], and_or(b1, 0x00C000C0u, magic), dot1);
-        dot = dot2(x0[7], and_or(b0, 0x03000300u, magic), dot);
-        dot1 = dot2(x1[7], and_or(b1, 0x03000300u, magic), dot1);
-        dot += dot1;
+#pragma unroll
+        for (int w = 2 * h; w < 2 * h + 2; ++w) {
+            const uint32_t W = cw[w], a = W << 4, b = W >> 6;
+            dot = dot2(xs[8 * w + 0], and_or(a, 0x00300030u, magic), dot);
+            dot = dot2(xs[8 * w + 1], and_or(a, 0x00C000C0u, magic), dot);
+            dot = dot2(xs[8 * w + 2], and_or(W, 0x00300030u, magic), dot);
+            dot = dot2(xs[8 * w + 3], and_or(W, 0x00C000C0u, magic), dot);
+            dot = dot2(xs[8 * w + 4], and_or(W, 0x03000300u, magic), dot);
+            dot = dot2(xs[8 * w + 5], and_or(b, 0x00300030u, magic), dot);
+            dot = dot2(xs[8 * w + 6], and_or(b, 0x00C000C0u, magic), dot);
+            dot = dot2(xs[8 * w + 7], and_or(b, 0x03000300u, magic), dot);
+        }
     } else if (BITS == 4) {
 #pragma unroll
         for (int w = 4 * h; w < 4 * h + 4; ++w) {
