@@ -68,14 +68,14 @@ template <int BITS> constexpr bool staged_codes() { return StageTraits<BITS>::kP
 __device__ __forceinline__ void dma16_to_lds(const void* src, void* lds_wave_base) {
     __builtin_amdgcn_global_load_lds((const FLOE_GLOBAL void*)src, (FLOE_LDS void*)lds_wave_base, 16, 0, 0);
 }
-// read a lane's piece back at once (the wait for the LDS result is part of the statement: the compiler does not
-// know that a load is outstanding)
-__device__ __forceinline__ void lds_read_now(const void* lds_ptr, uint32_t (&w)[4]) {
-    u32x4 q;
+// Read a lane's piece back.  The compiler does not know that this LDS read exists (it would make it wait for every
+// direct-to-LDS load), so request and arrival are two statements, one pass apart: nothing may touch the registers
+// between them, which the second statement enforces by taking them as in/out operands.
+__device__ __forceinline__ void lds_piece_request(const void* lds_ptr, u32x4& q) {
     const uint32_t a = (uint32_t)(uintptr_t)(const FLOE_LDS void*)lds_ptr;
-    asm volatile("ds_read_b128 %0, %1\n\ts_waitcnt lgkmcnt(0)" : "=v"(q) : "v"(a) : "memory");
-    w[0] = q.x; w[1] = q.y; w[2] = q.z; w[3] = q.w;
+    asm volatile("ds_read_b128 %0, %1" : "=v"(q) : "v"(a) : "memory");
 }
+__device__ __forceinline__ void lds_piece_arrived(u32x4& q) { asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(q) : : "memory"); }
 
 // ROUTED: the workgroup routes in place (INT2, <= 16 experts); otherwise the task's expert comes from `map`, its
 // threshold from task_tau and its output scale from task_scale (nullptr = 1).
@@ -160,6 +160,7 @@ __global__ __launch_bounds__(kFusedThreads, fused_wgs_per_cu) void fused_ffn_ker
         unsigned char* stage = reinterpret_cast<unsigned char*>(&yred[kFusedCpp * wave][0]);
         static_assert(!kStaged || kDepth * kSlot <= kFusedCpp * d * 4, "the staging ring must fit the two slabs");
         static_assert(!kStaged || kVmPerPass * (kDepth - 1) < 64, "the wait counts outstanding requests in six bits");
+        static_assert(!kStaged || St::kPieces == 1, "one piece per pass is read back ahead");
         UnitLoad<BITS, UPC, G32> ld[kDepth];
         // the lane's part of the three addresses of a pass; the channel's part is a scalar at d = 4096
         const unsigned char* lane_codes = reinterpret_cast<const unsigned char*>(e.codes) + (size_t)u * (BITS * 8);
@@ -220,6 +221,15 @@ __global__ __launch_bounds__(kFusedThreads, fused_wgs_per_cu) void fused_ffn_ker
         FLOE_TL(4);
 
         int k = 0;  // entries pushed so far (wave-uniform)
+        // Staged codes come back from LDS one pass ahead.  A pass's codes have landed once only the requests made
+        // after them are outstanding: kVmPerPass per pass, and kDepth - 1 passes are behind pass p at its own turn,
+        // kDepth - 2 behind pass p + 1 at that time.  The counts are the same in every round because the last round
+        // keeps requesting (see below).  More may be outstanding - a store of v, say - which only makes a wait longer.
+        u32x4 cw_next;
+        if constexpr (kStaged) {
+            wait_vm_all_but<kVmPerPass * (kDepth - 1)>();
+            lds_piece_request(stage + lane * 16, cw_next);
+        }
 #pragma unroll 1
         for (int p0 = 0; p0 < kPasses; p0 += kDepth) {
 #pragma unroll
@@ -227,18 +237,12 @@ __global__ __launch_bounds__(kFusedThreads, fused_wgs_per_cu) void fused_ffn_ker
                 const int p = p0 + i;
                 if (kPasses % kDepth != 0 && p >= kPasses) break;  // last, shorter round (wave-uniform)
                 const int j = jw + p * CPW + sub;
-                // Pass p's codes have landed once only the requests made after them are outstanding: kVmPerPass per
-                // pass, kDepth - 1 passes behind it.  That count is the same in every round because the last round
-                // keeps requesting (see below).  More may be outstanding - a store of v, say - which only makes the
-                // wait longer than needed.
                 if constexpr (kStaged) {
-                    wait_vm_all_but<kVmPerPass * (kDepth - 1)>();
-#pragma unroll
-                    for (int pc = 0; pc < St::kPieces; ++pc) {
-                        uint32_t w[4];
-                        lds_read_now(stage + i * kSlot + pc * 1024 + lane * 16, w);
-#pragma unroll
-                        for (int q = 0; q < 4; ++q) ld[i].cw[pc * 4 + q] = w[q];
+                    lds_piece_arrived(cw_next);
+                    ld[i].cw[0] = cw_next.x; ld[i].cw[1] = cw_next.y; ld[i].cw[2] = cw_next.z; ld[i].cw[3] = cw_next.w;
+                    if constexpr (kDepth >= 2) {  // (past the last pass this reads a slot that nobody uses)
+                        wait_vm_all_but<kVmPerPass * (kDepth - 2)>();
+                        lds_piece_request(stage + ((i + 1) % kDepth) * kSlot + lane * 16, cw_next);
                     }
                 }
                 // scale and zero stay untouched until here (otherwise their unpacking is hoisted out of the loop for
@@ -275,6 +279,7 @@ __global__ __launch_bounds__(kFusedThreads, fused_wgs_per_cu) void fused_ffn_ker
                 __builtin_amdgcn_sched_barrier(0);  // keep the request for pass p + kDepth where it is
             }
         }
+        if constexpr (kStaged) lds_piece_arrived(cw_next);  // the read-ahead of the last pass: its registers are free only now
         if constexpr (kStaged) wait_vm_all_but<0>();  // the ring lies in the consumers' result slabs: nothing may land later
         if (lane == 0) {
             lds_poke(&done[wave], 1);  // after the last push, in program order
