@@ -31,7 +31,7 @@ CONFIG_ID, SEED = 3, 0
 N_TOKENS = 16          # distinct decode tokens the steps cycle through
 # HBM bytes per launch of each kernel for THIS workload, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs scaled by
 # a plain 256 MiB copy (profiles/layer_decode_config3_T1_hbm_traffic.md); hardware counters cannot be read from here
-MEASURED_TRAFFIC_BYTES = {"fused_ffn": 88.86e6, "combine": 4.25e6}
+MEASURED_TRAFFIC_BYTES = {"fused_ffn": 88.85e6, "combine": 4.25e6}
 
 
 def log(*a):
