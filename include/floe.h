@@ -177,7 +177,8 @@ typedef struct {
 
 size_t floe_layer_table_bytes(const floe_layer* L);
 /* Copies the experts' device pointers into dev_table (dev, 256-byte aligned, floe_layer_table_bytes()).
- * Synchronises `stream` before returning (the host array may be freed afterwards). One-time set-up. */
+ * Every expert's up_codes, up_scale, up_zero and gd must be 16-byte aligned (FLOE_EINVAL otherwise).
+ * Synchronises `stream` before returning; L->experts is not read by any later call and may be freed. One-time set-up. */
 int floe_layer_build_table(const floe_layer* L, void* dev_table, size_t bytes, void* stream);
 
 size_t floe_layer_workspace_bytes(const floe_layer* L, int T);

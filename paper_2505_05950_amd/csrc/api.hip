@@ -375,7 +375,10 @@ int floe_layer_build_table(const floe_layer* L, void* dev_table, size_t bytes, v
         const floe_expert& e = L->experts[i];
         if (e.s.d != L->s.d || e.s.f != L->s.f || e.s.bits != L->s.bits || e.s.group != L->s.group) return FLOE_ESHAPE;
         if (!e.up_codes || !e.up_scale || !e.up_zero || !e.gd) return FLOE_EINVAL;
-        if (!aligned(e.up_codes, 16) || !aligned(e.gd, 16)) return FLOE_EINVAL;
+        // the batch kernels fetch scales and zeros with 16-byte loads: checked here, once, for every expert, so that
+        // no decode call has to look at the host array again
+        if (!aligned(e.up_codes, 16) || !aligned(e.gd, 16) || !aligned(e.up_scale, 16) || !aligned(e.up_zero, 16))
+            return FLOE_EINVAL;
         if (e.gd_is_staged || e.gd_rows != e.s.f) return FLOE_EINVAL;
         host[i].codes = e.up_codes;
         host[i].scale = reinterpret_cast<const h16*>(e.up_scale);
@@ -428,8 +431,7 @@ int floe_moe_layer_decode(const floe_layer* L, const floe_half* x, int T, floe_h
     map.slots = slots;
     const bool mask_ok = mask_path_ok(L->s.f);
     const bool batch_mfma = T >= 2 && mfma_grouped_shape(L->s.d, L->s.bits, L->s.group) &&
-                            mfma_batch_pays(L->n_experts + L->n_shared, w.n_tasks) &&
-                            aligned(L->experts ? L->experts[0].up_scale : nullptr, 16);
+                            mfma_batch_pays(L->n_experts + L->n_shared, w.n_tasks);
     int nblk = w.nblk, count_parts = 0;
     if (w.fused_passes && !batch_mfma) {
         // small batch: [(router +) up GEMV + selection + gate/down on the workgroup's own channels] -> [combine];

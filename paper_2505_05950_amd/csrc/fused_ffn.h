@@ -340,6 +340,13 @@ __global__ __launch_bounds__(kFusedThreads, fused_wgs_per_cu) void fused_ffn_ker
             }
             k += kFusedCpp;
         }
+        // The producer's staging ring lies in this consumer's result slab.  A consumer that left the loop because its
+        // queue was full to capacity (every channel of the block selected) has not seen the producer's flag yet, and
+        // direct-to-LDS loads of the producer may still be on their way: the slab is written only after the flag,
+        // which the producer raises behind its last wait.
+        if constexpr (staged_codes<BITS>()) {
+            while (__builtin_amdgcn_readfirstlane(lds_peek(&done[qc])) == 0) __builtin_amdgcn_s_sleep(1);
+        }
         // lane owns columns [(r * 64 + lane) * 8, + 8)
 #pragma unroll
         for (int r = 0; r < NV; ++r) {

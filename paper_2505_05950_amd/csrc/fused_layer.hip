@@ -1,7 +1,21 @@
 // Host side of the fused small-batch kernel: block-size choice and dispatch on the bit width.
 #include "launch.h"
 
+#include <atomic>
+
 namespace floe {
+
+int num_cus() {
+    constexpr int kMaxDevices = 64, kDefault = 256;
+    static std::atomic<int> cached[kMaxDevices];  // 0 = not asked yet
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return kDefault;
+    int n = cached[dev].load(std::memory_order_relaxed);
+    if (n > 0) return n;
+    if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) n = kDefault;
+    cached[dev].store(n, std::memory_order_relaxed);
+    return n;
+}
 
 hipError_t launch_fused_int2(const FusedArgs& a, hipStream_t stream);
 hipError_t launch_fused_int3(const FusedArgs& a, hipStream_t stream);

@@ -251,7 +251,7 @@ extern "C" int floe_debug_set_timeline_gate_down(unsigned long long* p) {
 
 int gd_blocks(int n_tasks, int f) {
     if (n_tasks <= 0) return 1;
-    int nblk = kNumCU / n_tasks;
+    int nblk = num_cus() / n_tasks;
     nblk = nblk < 1 ? 1 : nblk;
     const int by_f = (f + 3) / 4;  // a workgroup should have at least a few channels to look at
     nblk = nblk > by_f ? by_f : nblk;

@@ -11,7 +11,9 @@
 
 namespace floe {
 
-constexpr int kNumCU = 256;  // MI355X
+// Compute units of the current device (read once per device from its properties; 256 on an MI355X, which is also
+// what the host-side size queries assume when no device is usable).
+int num_cus();
 
 // true when the packed-fp16 kernel applies to this shape (otherwise the generic kernel runs)
 inline bool packed_fast_shape(int d, int bits, int group) {

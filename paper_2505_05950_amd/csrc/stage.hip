@@ -78,7 +78,7 @@ hipError_t launch_stage_tasks(const DevExpert* task_table, int d, int f, const i
                               int capacity_rows, h16* dst, int32_t* overflow, int n_tasks, hipStream_t stream,
                               const int32_t* dst_rows) {
     if (n_tasks == 0) return hipSuccess;
-    const int nblk = kNumCU / n_tasks > 0 ? kNumCU / n_tasks : 1;
+    const int nblk = num_cus() / n_tasks > 0 ? num_cus() / n_tasks : 1;
     stage_tasks_kernel<<<dim3(nblk, n_tasks), dim3(256), 0, stream>>>(task_table, d / 4, f, idx, count, capacity_rows,
                                                                      reinterpret_cast<uint4*>(dst), overflow, dst_rows);
     return hipGetLastError();
@@ -87,7 +87,7 @@ hipError_t launch_stage_tasks(const DevExpert* task_table, int d, int f, const i
 hipError_t launch_stage(const h16* host_gd_dev, int d, int f, const int32_t* idx, const int32_t* count, int capacity_rows,
                         h16* dst, int32_t* overflow, hipStream_t stream) {
     const int vec_per_chunk = d / 4;  // 2 * d halves = 4 * d bytes = d / 4 uint4
-    stage_kernel<<<dim3(kNumCU), dim3(256), 0, stream>>>(reinterpret_cast<const uint4*>(host_gd_dev), vec_per_chunk, f,
+    stage_kernel<<<dim3(num_cus()), dim3(256), 0, stream>>>(reinterpret_cast<const uint4*>(host_gd_dev), vec_per_chunk, f,
                                                          idx, count, capacity_rows, reinterpret_cast<uint4*>(dst),
                                                          overflow);
     return hipGetLastError();

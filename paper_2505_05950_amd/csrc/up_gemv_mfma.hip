@@ -17,6 +17,8 @@
 //   acc += s * (2^k C - z * Xg), with the channel's (s, z) in the lane and the tokens' group sums Xg in
 //   LDS.  A lane ends up holding v for one channel and four tokens; the comparison with each token's
 //   threshold is a wave ballot whose 16-bit pieces are the mask bits the gate/down kernel compacts.
+#include <atomic>
+
 #include "floe_dev.h"
 #include "launch.h"
 
@@ -482,12 +484,16 @@ static hipError_t launch_mfma_inst(int max_groups, hipStream_t stream, const Dev
     // channels per wave = 16 * TILES: code blocks are double-buffered and all scales / zeros sit in registers
     constexpr int TILES = (BITS == 4 && G32) ? 1 : 2;
     constexpr size_t lds = (size_t)UPC * 8 * NTPAD * 16 + (size_t)UPC * (G32 ? 2 : 1) * NTPAD * 4;
-    static bool attr_set = false;
-    if (!attr_set) {
+    // the attribute belongs to the function on one device: set once per device, from whichever thread comes first
+    constexpr int kMaxDevices = 64;
+    static std::atomic<bool> attr_set[kMaxDevices];
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+    if (!attr_set[dev].load(std::memory_order_acquire)) {
         hipError_t rc = hipFuncSetAttribute(reinterpret_cast<const void*>(&up_gemv_mfma_kernel<BITS, UPC, G32, NTPAD, TILES>),
                                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (rc != hipSuccess) return rc;
-        attr_set = true;
+        attr_set[dev].store(true, std::memory_order_release);
     }
     const int ch_per_wg = 8 * 16 * TILES;
     const dim3 grid((f + ch_per_wg - 1) / ch_per_wg, max_groups);

@@ -65,6 +65,40 @@ def test_degenerate_group_is_exact():
     assert np.array_equal(O.dequantize(codes, scale, zero, 32, 4, 8), w.astype(np.float32))
 
 
+def test_group_whose_step_is_below_the_smallest_normal_half_is_degenerate():
+    """Second degenerate branch of the quantizer (Sec. 3.2.2 reading: a group whose step (max - min) / qmax falls
+    below 2^-14, the smallest normal binary16, is stored as scale 1, zero = fp16(-min), codes 0).  Expected values
+    written out by hand; the boundary step 2^-14 itself is still an ordinary group."""
+    # INT2 (qmax 3), group 16: min = -0.25, max = -0.25 + 2^-13 (its fp16 neighbour): step 2^-13 / 3 = 4.07e-5 < 6.10e-5
+    w = np.full((3, 16), -0.25, dtype=np.float16)
+    w[0, 5] = np.float16(-0.25 + 2.0 ** -13)
+    assert float(w[0, 5]) == -0.2498779296875          # exactly representable, so max != min
+    # row 1, the boundary: values 0 and 3 * 2^-14: step exactly 2^-14 -> scale 0x0400, zero -0.0, codes 0, 2 and 3
+    w[1, :] = 0.0
+    w[1, 2] = np.float16(3 * 2.0 ** -14)
+    w[1, 9] = np.float16(2 * 2.0 ** -14)
+    # row 2, INT2 again: 0 and 2^-15 (a subnormal half): step 2^-15 / 3, far below -> degenerate with zero = -0.0
+    w[2, :] = 0.0
+    w[2, 0] = np.float16(2.0 ** -15)
+    codes, scale, zero = O.quantize(w, 2, 16)
+    sc, zr = scale.view(np.uint16), zero.view(np.uint16)
+    assert sc[0, 0] == 0x3C00 and zr[0, 0] == 0x3400 and codes[0, 0] == 0          # scale 1, zero +0.25, codes 0
+    assert sc[1, 0] == 0x0400 and zr[1, 0] == 0x8000                              # 2^-14; zero = (-0) / scale = -0.0
+    assert int(codes[1, 0]) == (3 << (2 * 2)) | (2 << (2 * 9))                     # code 3 at i = 2, code 2 at i = 9
+    assert sc[2, 0] == 0x3C00 and zr[2, 0] == 0x8000 and codes[2, 0] == 0          # scale 1, zero -0.0, codes 0
+    w_hat = O.dequantize(codes, scale, zero, 16, 2, 16)
+    assert np.all(w_hat[0] == np.float32(-0.25))                                  # the whole group collapses onto min
+    assert np.array_equal(w_hat[1], w[1].astype(np.float32))
+    assert np.all(w_hat[2] == 0.0)
+    # INT4 (qmax 15): 0 and 15 * 2^-15 -> step 2^-15 (subnormal) -> degenerate; 0 and 15 * 2^-14 -> ordinary, codes 0 / 15
+    w4 = np.zeros((2, 8), dtype=np.float16)
+    w4[0, 3] = np.float16(15 * 2.0 ** -15)
+    w4[1, 3] = np.float16(15 * 2.0 ** -14)
+    c4, s4, z4 = O.quantize(w4, 4, 8)
+    assert s4.view(np.uint16)[0, 0] == 0x3C00 and c4[0, 0] == 0
+    assert s4.view(np.uint16)[1, 0] == 0x0400 and int(c4[1, 0]) == 15 << (4 * 3)
+
+
 @pytest.mark.parametrize("bits,group", [(2, 16), (2, 64), (3, 32), (3, 64), (4, 8), (4, 64), (1, 32), (1, 64), (8, 4), (8, 64)])
 def test_packing_is_little_endian_bitstream(bits, group):
     # weights that sit exactly on the quantization grid: level * 0.5 with both end levels present in
