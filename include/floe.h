@@ -191,6 +191,22 @@ size_t floe_layer_workspace_bytes(const floe_layer* L, int T);
 int floe_moe_layer_decode(const floe_layer* L, const floe_half* x, int T, floe_half* y, floe_slot_stat* stats,
                           void* workspace, size_t workspace_bytes, void* stream);
 
+/*
+ * The same layer decode for callers that cannot allocate device memory or have no workspace to hand over: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Inputs, outputs, results and
+ * error codes are those of floe_moe_layer_decode; the workspace is a scratch array of FLOE_STATIC_SCRATCH_BYTES
+ * that is part of the library's device image (each GPU the library runs on holds one copy until the process ends).
+ * The call allocates and frees nothing.  Limit: floe_layer_workspace_bytes(L, T) must not exceed
+ * FLOE_STATIC_SCRATCH_BYTES (ask that function: a Mixtral-shaped layer, d=4096 f=14336 top-2, needs 4.2 MiB per
+ * token at T <= 3 and fits again, with other kernels, from T = 9 to about T = 48), otherwise FLOE_EWORKSPACE is
+ * returned and nothing is enqueued.  All calls on one GPU share the array: calls that overlap
+ * on one GPU (two streams, two threads) race; calls on one stream are ordered and safe.  No kernel relies on what
+ * an earlier call left in the array.
+ */
+#define FLOE_STATIC_SCRATCH_BYTES ((size_t)16 << 20)
+int floe_moe_layer_decode_static(const floe_layer* L, const floe_half* x, int T, floe_half* y, floe_slot_stat* stats,
+                                 void* stream);
+
 /* ------------------------------------------------------------------------------------------------
  * One MoE layer in the offloaded setting (Sec. 3.1, Fig. 1(c); Sec. 3.4.2): the quantized up projections
  * and the router are resident in HBM, the gate/down matrices stay in pinned host memory and only the

@@ -8,7 +8,8 @@ from .binding import (  # noqa: F401
     FloeError, Expert, Layer, lib_path, load,
     floe_quantize_expert, floe_up_gemv, floe_select_channels, floe_gate_down_sparse,
     floe_expert_ffn_sparse, floe_expert_workspace_bytes, floe_layer_build_table, floe_layer_table_bytes,
-    floe_layer_workspace_bytes, floe_moe_layer_decode, floe_moe_layer_decode_offloaded, floe_moe_layer_prefetch,
+    floe_layer_workspace_bytes, floe_moe_layer_decode, floe_moe_layer_decode_static, STATIC_SCRATCH_BYTES,
+    floe_moe_layer_decode_offloaded, floe_moe_layer_prefetch,
     floe_moe_layer_decode_prefetched, Prefetch, MissPath, PREFETCH_STAT_DTYPE, floe_stage_channels, floe_status_string,
     words_per_channel, SLOT_STAT_DTYPE, floe_profile_kernel, KERNEL_IDS,
 )

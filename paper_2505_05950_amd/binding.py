@@ -88,6 +88,7 @@ def load():
     lib.floe_layer_workspace_bytes.restype = sz
     lib.floe_layer_workspace_bytes.argtypes = [C.POINTER(_Layer), i32]
     lib.floe_moe_layer_decode.argtypes = [C.POINTER(_Layer), vp, i32, vp, vp, vp, sz, vp]
+    lib.floe_moe_layer_decode_static.argtypes = [C.POINTER(_Layer), vp, i32, vp, vp, vp]
     lib.floe_moe_layer_decode_offloaded.argtypes = [C.POINTER(_Layer), C.POINTER(_Offload), vp, i32, vp, vp, vp, sz, vp]
     lib.floe_moe_layer_prefetch.argtypes = [C.POINTER(_Layer), C.POINTER(_Prefetch), vp, i32, vp, sz, vp]
     lib.floe_moe_layer_decode_prefetched.argtypes = [C.POINTER(_Layer), C.POINTER(_Prefetch), C.POINTER(_MissPath), vp, i32,
@@ -298,6 +299,16 @@ def floe_moe_layer_decode(L: Layer, x: torch.Tensor, y: torch.Tensor = None, sta
     wp, wn = _aligned_ptr(workspace)
     _check(load().floe_moe_layer_decode(C.byref(L._c), _ptr(x), T, _ptr(y), _ptr(stats), wp, wn, _stream(stream)),
            "floe_moe_layer_decode")
+    return y
+
+
+STATIC_SCRATCH_BYTES = 16 << 20
+
+
+def floe_moe_layer_decode_static(L: Layer, x: torch.Tensor, y: torch.Tensor, stats: torch.Tensor = None, stream=None):
+    """floe_moe_layer_decode on the library's own scratch array; y must be supplied (nothing is allocated here)."""
+    _check(load().floe_moe_layer_decode_static(C.byref(L._c), _ptr(x), x.shape[0], _ptr(y), _ptr(stats), _stream(stream)),
+           "floe_moe_layer_decode_static")
     return y
 
 
