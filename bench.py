@@ -29,9 +29,27 @@ HBM_PEAK_GBS = 8000.0
 D, F_INT, BITS, GROUP, N_EXPERTS, TOP_K, PCT = 4096, 14336, 2, 64, 8, 2, 90
 CONFIG_ID, SEED = 3, 0
 N_TOKENS = 16          # distinct decode tokens the steps cycle through
-# HBM bytes per launch of each kernel for THIS workload, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs scaled by
-# a plain 256 MiB copy (profiles/layer_decode_config3_T1_hbm_traffic.md); hardware counters cannot be read from here
-MEASURED_TRAFFIC_BYTES = {"fused_ffn": 88.85e6, "combine": 4.25e6}
+TRAFFIC_PROFILE = os.path.join("profiles", "layer_decode_config3_T1_hbm_traffic.md")
+
+
+def measured_traffic():
+    """HBM bytes per launch of each kernel of THIS workload as the committed rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
+    summary states them (hardware counters cannot be read from inside this process).  Returns ({kernel: bytes}, note);
+    the note names the file and the kernel-source state it was taken at, so a reader can tell whether it is current."""
+    path = os.path.join(ROOT, TRAFFIC_PROFILE)
+    out, note = {}, None
+    try:
+        for line in open(path):
+            cells = [c.strip() for c in line.split("|")]
+            if len(cells) > 7 and cells[1].startswith("fused_ffn_kernel"):
+                out["fused_ffn"] = float(cells[6]) * 1e6
+            elif len(cells) > 7 and cells[1].startswith("combine_kernel"):
+                out["combine"] = float(cells[6]) * 1e6
+            elif line.lower().startswith("kernel sources at"):
+                note = line.strip()
+    except (OSError, ValueError):
+        return {}, None
+    return out, f"{TRAFFIC_PROFILE}" + (f" ({note})" if note else "")
 
 
 def log(*a):
@@ -69,6 +87,9 @@ def main():
                          "batch: decode batches of configs[2] (T=1,4,16) and configs[4] (T=1,8,32)")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run a plain 256 MiB device copy five times (reference for hardware-counter runs)")
+    ap.add_argument("--batch-cases", default="", help="batch workload only: cases to run as config:T,... "
+                                                      "(e.g. 2:16,4:32; empty = all)")
+    ap.add_argument("--union-kernels", type=int, default=0, help="floe_tuning(FLOE_TUNE_UNION_KERNELS): 0 = library default")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0)
     args = ap.parse_args()
@@ -85,6 +106,8 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     dev = torch.device("cuda:0")
     FL.load()
+    if args.union_kernels:
+        FL.floe_tuning(FL.TUNE_UNION_KERNELS, args.union_kernels)
     K, W, R = args.steps, args.warmup, max(1, args.copies)
     if args.workload == "expert":
         return bench_expert(args, np, torch, S, FL, dev)
@@ -187,6 +210,39 @@ def main():
     ms_per_step = ms_total / K
     us_per_layer_token = ms_per_step * 1e3      # T = 1
 
+    # spread of the same metric: the K steps again in chunks of 10 consecutive steps, every chunk timed on its own
+    # (a second pass: the value above stays the plain total over K steps)
+    chunk = 10
+    n_chunks = max(1, K // chunk)
+    chunk_us = []
+    with torch.cuda.stream(stream):
+        graphs = []
+        if args.launch == "graph":
+            for c in range(n_chunks):
+                g = torch.cuda.CUDAGraph()
+                with torch.cuda.graph(g, stream=stream):
+                    for i in range(chunk):
+                        step(W + c * chunk + i)
+                graphs.append(g)
+            for g in graphs:
+                g.replay()
+            stream.synchronize()
+        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n_chunks)]
+        for c in range(n_chunks):
+            evs[c][0].record(stream)
+            if graphs:
+                graphs[c].replay()
+            else:
+                for i in range(chunk):
+                    step(W + c * chunk + i)
+            evs[c][1].record(stream)
+        stream.synchronize()
+        chunk_us = [a.elapsed_time(b) * 1e3 / chunk for a, b in evs]
+        del graphs
+    spread = {"median": round(float(np.median(chunk_us)), 3), "p10": round(float(np.percentile(chunk_us, 10)), 3),
+              "p90": round(float(np.percentile(chunk_us, 90)), 3),
+              "over": f"{n_chunks} chunks of {chunk} consecutive steps, each replayed and timed on its own"}
+
     # ---------------------------------------------------------------- per-kernel durations (HIP events)
     # A pair of events around one kernel reads the kernel's duration plus a fixed cost o of the two markers.
     # In the timed graph the kernels of a step run back to back (each waits for the one before it), so a
@@ -194,7 +250,7 @@ def main():
     # With --launch stream there is no such step time, and o comes from a copy kernel instead: a bracket around
     # one launch reads t + o, one around nine launches 9t + o.
     # (At T = 1 the layer is two kernels: router, up GEMV, selection and gate/down in one, then the combine.)
-    raw = {}
+    raw, raw_spread = {}, {}
     with torch.cuda.stream(stream):
         for name in ("fused_ffn", "combine"):
             pairs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(K)]
@@ -207,7 +263,9 @@ def main():
                 step(W + i)
             FL.floe_profile_kernel("none")
             stream.synchronize()
-            raw[name] = float(np.mean([a.elapsed_time(b) for a, b in pairs])) * 1e3
+            reads = [a.elapsed_time(b) * 1e3 for a, b in pairs]
+            raw[name] = float(np.mean(reads))
+            raw_spread[name] = [float(np.median(reads)), float(np.percentile(reads, 10)), float(np.percentile(reads, 90))]
         if args.launch == "graph":
             bracket_us = (sum(raw.values()) - ms_per_step * 1e3) / len(raw)
         else:
@@ -242,12 +300,14 @@ def main():
     bytes_combine = TOP_K * 4 * D + 2 * D
     bytes_step = bytes_fused + bytes_combine
     kernel_bytes = {"fused_ffn": bytes_fused, "combine": bytes_combine}
+    traffic, traffic_note = measured_traffic()
     dominant = max(per_kernel, key=lambda n: per_kernel[n])
     dom_gbs = kernel_bytes[dominant] / (per_kernel[dominant] * 1e-6) / 1e9
     kernels = {n: {"us": round(per_kernel[n], 3), "algorithmic_bytes": int(kernel_bytes[n]),
-                   "GBps": round(kernel_bytes[n] / (per_kernel[n] * 1e-6) / 1e9, 1)} for n in per_kernel}
+                   "GBps": round(kernel_bytes[n] / (per_kernel[n] * 1e-6) / 1e9, 1),
+                   "us_median_p10_p90": [round(v - bracket_us, 3) for v in raw_spread[n]]} for n in per_kernel}
     roofline = {"bound": "hbm", "kernel": dominant, "achieved": round(dom_gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                "frac": round(dom_gbs / HBM_PEAK_GBS, 4), "traffic": MEASURED_TRAFFIC_BYTES.get(dominant),
+                "frac": round(dom_gbs / HBM_PEAK_GBS, 4), "traffic": traffic.get(dominant), "traffic_source": traffic_note,
                 "kernel_us": round(per_kernel[dominant], 3), "kernels": kernels,
                 "layer_bytes": int(bytes_step),
                 "layer_frac": round(bytes_step / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
@@ -297,15 +357,16 @@ def main():
                    "launch": args.launch, "layer_copies_rotated": R, "tokens_cycled": N_TOKENS,
                    "mean_selected_channels": round(float(Ks.mean()), 1),
                    "quantize_ms_per_expert": round(float(np.mean(q_ms[1:])), 3),
-                   "wall_ms_per_step": round(t_wall * 1e3 / K, 6)},
+                   "wall_ms_per_step": round(t_wall * 1e3 / K, 6), "us_per_step_spread": spread},
         "roofline": roofline,
         "cpu_baseline": cpu,
     }
     print(json.dumps(out), flush=True)
 
 
-def _graph_time(torch, stream, fn, K, W):
-    """W warm-up calls, then K calls replayed from one HIP graph; returns ms per call."""
+def _graph_time(torch, stream, fn, K, W, reps=1, spread=None):
+    """W warm-up calls, then K calls replayed from one HIP graph (reps timed replays); returns the mean ms per call and
+    fills `spread` (median, p10, p90 over the replays) when given."""
     with torch.cuda.stream(stream):
         for i in range(W):
             fn(i)
@@ -316,12 +377,19 @@ def _graph_time(torch, stream, fn, K, W):
                 fn(W + i)
         g.replay()
         stream.synchronize()
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record(stream)
-        g.replay()
-        e1.record(stream)
-        torch.cuda.synchronize()
-    return e0.elapsed_time(e1) / K
+        reads = []
+        for _ in range(reps):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(stream)
+            g.replay()
+            e1.record(stream)
+            torch.cuda.synchronize()
+            reads.append(e0.elapsed_time(e1) / K)
+    if spread is not None:
+        import numpy as np
+        spread.update({"median": float(np.median(reads)), "p10": float(np.percentile(reads, 10)),
+                       "p90": float(np.percentile(reads, 90)), "replays": reps})
+    return reads[0] if reps == 1 else float(sum(reads) / len(reads))
 
 
 def bench_expert(args, np, torch, S, FL, dev):
@@ -667,7 +735,7 @@ def bench_batch(args, np, torch, S, FL, dev):
     """Decode batches (each token routed on its own, own thresholds): BASELINE configs[2] at T = 1, 4, 16 and
     configs[4] (64 routed + 2 shared experts, d=2048, f=1408, INT3 group 32, top-6, 85 %) at T = 1, 8, 32.
     Per-expert constant thresholds calibrated on 8 tokens; one layer copy (what a call touches beyond T = 1 is larger
-    than the last-level cache anyway)."""
+    than the last-level cache anyway).  Fractions are over the algorithmic bytes: rows counted once per expert."""
     K, W = max(20, args.steps // 4), max(5, args.warmup // 8)
     out = []
 
@@ -690,6 +758,10 @@ def bench_batch(args, np, torch, S, FL, dev):
     for name, cfg, d, f, bits, group, n, n_shared, top_k, renorm, pct, Ts in (
             ("configs[2]", 3, 4096, 14336, 2, 64, 8, 0, 2, True, 90, (1, 4, 16, 64)),
             ("configs[4]", 5, 2048, 1408, 3, 32, 64, 2, 6, False, 85, (1, 8, 32))):
+        want = [c.split(":") for c in args.batch_cases.split(",") if c]
+        Ts = [T for T in Ts if not want or [name[8], str(T)] in want]
+        if not Ts:
+            continue
         L = make_layer(cfg, d, f, bits, group, n, n_shared, top_k, renorm, pct)
         for T in Ts:
             x = torch.from_numpy(S.tokens(SEED, cfg, T, d, layer=9)).to(dev)
@@ -699,18 +771,33 @@ def bench_batch(args, np, torch, S, FL, dev):
             FL.floe_moe_layer_decode(L, x, y, st)
             torch.cuda.synchronize()
             rec = st.cpu().numpy().reshape(T * slots, 4)
-            ms = _graph_time(torch, stream, lambda i: FL.floe_moe_layer_decode(L, x, y), K, W)
-            # bytes the call has to read: the codes, scales and zeros of every expert that is used (once per token that
-            # uses it while tokens are handled one by one, once per expert when tokens are grouped: at least once per
-            # expert is what is counted), the [gate | down] chunks of every (token, slot), router, x, y
+            sp = {}
+            ms = _graph_time(torch, stream, lambda i: FL.floe_moe_layer_decode(L, x, y), K, W, reps=5, spread=sp)
+            # Algorithmic bytes of the call: the codes, scales and zeros of every expert that is used, once; per expert
+            # the [gate | down] chunks of the UNION of the channels its tokens select, once (a row serves every token
+            # whose mask holds it); router, x, y.  The unions come from this run's own routing (stats) and the masks
+            # |v| > tau of the same tokens (dense v per expert from floe_up_gemv: harness work, not timed).
             codes_meta = d * f * bits // 8 + 4 * f * (d // group)
-            used = len(set(rec[:, 0].tolist()))
-            nbytes = used * codes_meta + int(rec[:, 1].sum()) * 4 * d + n * d * 2 + T * d * 2 * 2
+            by_expert = {}
+            for q in range(T * slots):
+                by_expert.setdefault(int(rec[q, 0]), []).append(q // slots)
+            union_rows = 0
+            for e, toks in by_expert.items():
+                ex = L.experts[e]
+                v = FL.floe_up_gemv(ex.up_codes, ex.up_scale, ex.up_zero, x[toks].contiguous(), d, bits, group)
+                union_rows += int(((v.abs() > L.tau[e]).any(dim=0)).sum().item())
+            used = len(by_expert)
+            requested_rows = int(rec[:, 1].sum())
+            fixed = used * codes_meta + n * d * 2 + T * d * 2 * 2
+            nbytes = fixed + union_rows * 4 * d
             out.append({"config": name, "T": T, "us_per_layer_call": round(ms * 1e3, 2), "us_per_layer_token": round(ms * 1e3 / T, 2),
-                        "experts_used": used, "bytes_min": int(nbytes), "GBps": round(nbytes / ms / 1e6, 1),
-                        "frac_of_hbm_peak": round(nbytes / ms / 1e6 / HBM_PEAK_GBS, 4)})
+                        "us_per_layer_call_median_p10_p90": [round(sp[k] * 1e3, 2) for k in ("median", "p10", "p90")],
+                        "experts_used": used, "rows_union": union_rows, "rows_requested": requested_rows,
+                        "algorithmic_bytes": int(nbytes), "bytes_requested": int(fixed + requested_rows * 4 * d),
+                        "GBps": round(nbytes / ms / 1e6, 1), "frac_of_hbm_peak": round(nbytes / ms / 1e6 / HBM_PEAK_GBS, 4)})
             log(f"[bench] {name} T={T}: {ms * 1e3:.1f} us per layer call, {ms * 1e3 / T:.2f} us per layer-token, "
-                f"{out[-1]['GBps']} GB/s over {nbytes / 1e6:.0f} MB")
+                f"{out[-1]['GBps']} GB/s over {nbytes / 1e6:.0f} MB (union of selected rows per expert; "
+                f"{(fixed + requested_rows * 4 * d) / 1e6:.0f} MB if every (token, slot) read its own rows)")
         del L
     print(json.dumps({"metric": "us per MoE layer-token for decode batches", "value": out[0]["us_per_layer_token"], "unit": "us",
                       "n_gpus": 1, "higher_is_better": False, "data": "synthetic",

@@ -82,6 +82,24 @@ typedef enum {
 } floe_kernel_id;
 int floe_profile_kernel(int kernel_id, void* start_event, void* stop_event);
 
+/*
+ * Tuning switch (no part of the method; every setting gives results within the same parity bars).
+ *   FLOE_TUNE_UNION_KERNELS  how Alg. 1 steps 4-5 run for decode batches (more than 16 (token, slot) pairs), where
+ *                            the tokens of an expert select overlapping rows:
+ *                            0 = one workgroup set per (token, slot), launched in expert order on XCD-aligned channel
+ *                                blocks, so that a row several tokens selected is fetched from HBM once and served to
+ *                                the others by the L2 (default; the fastest measured at the sparsity levels of
+ *                                Sec. 3.2.1);
+ *                            1 = per expert group, the union of the selected rows read once, gate and down
+ *                                projections on the matrix cores (dense token x row tiles);
+ *                            2 = per expert group, the union of the selected rows read once into a ring in LDS, one
+ *                                wave per token.
+ * Process-wide.  Workspace sizes depend on it: do not change it between a *_workspace_bytes query and the decode
+ * call that uses the workspace.  Unknown key or value: FLOE_EINVAL.
+ */
+typedef enum { FLOE_TUNE_UNION_KERNELS = 1 } floe_tuning_key;
+int floe_tuning(int key, int value);
+
 /* ------------------------------------------------------------------------------------------------
  * S0 -- Sec. 3.2.2.  Asymmetric uniform group quantizer, bit-exact with this definition in IEEE
  * binary32 (one rounding per operation, no fused multiply-add), qmax = 2^bits - 1:

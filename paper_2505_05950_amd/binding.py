@@ -75,6 +75,7 @@ def load():
     lib.floe_last_hip_error.restype = i32
     lib.floe_abi_version.restype = i32
     lib.floe_profile_kernel.argtypes = [i32, vp, vp]
+    lib.floe_tuning.argtypes = [i32, i32]
     lib.floe_quantize_expert.argtypes = [C.POINTER(_Shape), vp, vp, vp, vp, vp]
     lib.floe_up_gemv.argtypes = [C.POINTER(_Shape), vp, vp, vp, vp, i32, vp, vp]
     lib.floe_select_channels.argtypes = [vp, i32, i32, vp, vp, vp, vp]
@@ -113,6 +114,14 @@ def floe_profile_kernel(kernel: str, start_event=None, stop_event=None):
     a = None if start_event is None else C.c_void_p(start_event.cuda_event)
     b = None if stop_event is None else C.c_void_p(stop_event.cuda_event)
     _check(load().floe_profile_kernel(kid, a, b), "floe_profile_kernel")
+
+
+TUNE_UNION_KERNELS = 1
+
+
+def floe_tuning(key: int, value: int):
+    """Process-wide tuning switch (see include/floe.h); Layer objects cache workspaces, so set it before building them."""
+    _check(load().floe_tuning(int(key), int(value)), "floe_tuning")
 
 
 def words_per_channel(d: int, bits: int) -> int:

@@ -114,9 +114,13 @@ bool mask_path_ok(int f) { return mask_words_per_task(f) <= 2048; }
 
 // workspace of the layer: per-task table, counts, mask words, v, idx, partial
 struct LayerWs {
-    size_t table_off, expert_off, weight_off, tau_off, count_off, mask_off, groups_off, ngroups_off, v_off, idx_off,
-        rows_off, missidx_off, missrows_off, misscount_off, partial_off, total;
+    size_t table_off, expert_off, weight_off, tau_off, count_off, mask_off, groups_off, ngroups_off, order_off, v_off, idx_off,
+        rows_off, missidx_off, missrows_off, misscount_off, urow_off, ucount_off, hbuf_off, partial_off, total;
     int n_tasks, nblk, nblk_fused, fused_passes;
+    bool batch_mfma;  // tokens of an expert share one pass over its codes (matrix-core up GEMV)
+    bool use_union;   // batches: one read of every row an expert group selected (gate_down_union.hip)
+    int chunk;        // tasks per token group
+    UnionPlan up;
 };
 LayerWs layer_ws(const floe_layer* L, int T) {
     LayerWs w;
@@ -125,16 +129,26 @@ LayerWs layer_ws(const floe_layer* L, int T) {
     w.nblk = gd_blocks(w.n_tasks, L->s.f);
     w.fused_passes = packed_fast_shape(L->s.d, L->s.bits, L->s.group) ? fused_passes(L->s.d, L->s.f, w.n_tasks) : 0;
     w.nblk_fused = w.fused_passes ? fused_blocks(L->s.d, L->s.f, w.fused_passes) : 0;
-    const int nblk_alloc = w.nblk > w.nblk_fused ? w.nblk : w.nblk_fused;
+    const int n_all = L->n_experts + L->n_shared;
+    w.chunk = mfma_chunk(n_all, w.n_tasks);
+    w.up = union_plan(L->s.d, L->s.f, w.n_tasks, n_all, w.chunk);
+    w.batch_mfma = T >= 2 && mfma_grouped_shape(L->s.d, L->s.bits, L->s.group) && mfma_batch_pays(n_all, w.n_tasks);
+    w.use_union = union_mode() != 0 && !L->gd_on_host && T >= 2 && (!w.fused_passes || w.batch_mfma) &&
+                  mask_path_ok(L->s.f) && union_shape_ok(L->s.d, L->s.f, w.up);
+    int nblk_alloc = w.nblk > w.nblk_fused ? w.nblk : w.nblk_fused;
+    if (w.use_union && w.up.nblk_down > nblk_alloc) nblk_alloc = w.up.nblk_down;
+    int count_parts = w.nblk_fused > 1 ? w.nblk_fused : 1;
+    if (w.use_union && w.up.nblk_gate > count_parts) count_parts = w.up.nblk_gate;
     size_t o = 0;
     w.table_off = o;  o += align_up((size_t)w.n_tasks * sizeof(DevExpert));
     w.expert_off = o; o += align_up((size_t)w.n_tasks * 4);
     w.weight_off = o; o += align_up((size_t)w.n_tasks * 4);
     w.tau_off = o;    o += align_up((size_t)w.n_tasks * 4);
-    w.count_off = o;  o += align_up((size_t)w.n_tasks * (w.nblk_fused > 1 ? w.nblk_fused : 1) * 4);
+    w.count_off = o;  o += align_up((size_t)w.n_tasks * count_parts * 4);
     w.mask_off = o;   o += align_up((size_t)w.n_tasks * mask_words_per_task(L->s.f) * 4);
     w.groups_off = o; o += align_up((size_t)mfma_max_groups(L->n_experts + L->n_shared, w.n_tasks) * sizeof(TokenGroup));
     w.ngroups_off = o; o += align_up(4);
+    w.order_off = o;   o += align_up((size_t)w.n_tasks * 4);
     w.v_off = o;      o += align_up((size_t)w.n_tasks * L->s.f * 4);
     w.idx_off = o;    o += align_up((size_t)w.n_tasks * L->s.f * 4);
     // host-resident gate/down: row map and miss lists of the prefetched decode
@@ -143,6 +157,10 @@ LayerWs layer_ws(const floe_layer* L, int T) {
     w.missidx_off = o;   o += per_list;
     w.missrows_off = o;  o += per_list;
     w.misscount_off = o; o += L->gd_on_host ? align_up((size_t)w.n_tasks * 4) : 0;
+    const size_t gblocks = w.use_union ? (size_t)w.up.max_groups * w.up.nblk_gate : 0;
+    w.urow_off = o;   o += w.use_union ? align_up(gblocks * w.up.cap * 4) : 0;
+    w.ucount_off = o; o += w.use_union ? align_up(gblocks * 4) : 0;
+    w.hbuf_off = o;   o += w.use_union ? align_up(gblocks * (w.up.cap / 16) * 64 * sizeof(uint4)) : 0;
     w.partial_off = o; o += align_up((size_t)w.n_tasks * nblk_alloc * L->s.d * 4);
     w.total = o;
     return w;
@@ -233,6 +251,16 @@ int floe_profile_kernel(int kernel_id, void* start_event, void* stop_event) {
     g_hook.start = (hipEvent_t)start_event;
     g_hook.stop = (hipEvent_t)stop_event;
     return FLOE_OK;
+}
+
+int floe_tuning(int key, int value) {
+    switch (key) {
+        case FLOE_TUNE_UNION_KERNELS:
+            if (value < 0 || value > 2) return FLOE_EINVAL;
+            set_union_mode(value);
+            return FLOE_OK;
+        default: return FLOE_EINVAL;
+    }
 }
 
 int floe_quantize_expert(const floe_shape* s, const floe_half* w_up_cm, uint32_t* codes, floe_half* scale,
@@ -430,8 +458,7 @@ int floe_moe_layer_decode(const floe_layer* L, const floe_half* x, int T, floe_h
     map.task_table = task_table;
     map.slots = slots;
     const bool mask_ok = mask_path_ok(L->s.f);
-    const bool batch_mfma = T >= 2 && mfma_grouped_shape(L->s.d, L->s.bits, L->s.group) &&
-                            mfma_batch_pays(L->n_experts + L->n_shared, w.n_tasks);
+    const bool batch_mfma = w.batch_mfma;
     int nblk = w.nblk, count_parts = 0;
     if (w.fused_passes && !batch_mfma) {
         // small batch: [(router +) up GEMV + selection + gate/down on the workgroup's own channels] -> [combine];
@@ -465,6 +492,45 @@ int floe_moe_layer_decode(const floe_layer* L, const floe_half* x, int T, floe_h
         FLOE_LAUNCH(FLOE_KERNEL_FUSED_FFN, st, launch_fused(a, L->s.bits, st));
         nblk = w.nblk_fused;
         count_parts = w.nblk_fused;
+    } else if (w.use_union) {
+        // decode batch: [router] -> [token groups per expert] -> [up GEMV + mask bits] -> [gate on the union of the
+        // group's rows] -> [down]; every selected row is read once per expert group
+        RouterArgs ra;
+        ra.router_cm = reinterpret_cast<const h16*>(L->router_cm);
+        ra.x = xh;
+        ra.tau = L->tau;
+        ra.tau_stride_t = L->tau_stride_t;
+        ra.n_experts = L->n_experts; ra.top_k = L->top_k; ra.n_shared = L->n_shared; ra.renormalize = L->renormalize;
+        ra.d = L->s.d;
+        ra.table = static_cast<const DevExpert*>(L->dev_table);
+        ra.task_table = task_table;
+        ra.task_expert = task_expert; ra.task_weight = task_weight; ra.task_tau = task_tau;
+        FLOE_LAUNCH(FLOE_KERNEL_ROUTER, st, launch_router(ra, T, st));
+        TokenGroup* groups = reinterpret_cast<TokenGroup*>(base + w.groups_off);
+        int32_t* n_groups = reinterpret_cast<int32_t*>(base + w.ngroups_off);
+        const int n_all = L->n_experts + L->n_shared;
+        FLOE_HIP(launch_group_tokens(task_expert, w.n_tasks, n_all, w.chunk, groups, n_groups, st));
+        if (batch_mfma)
+            FLOE_LAUNCH(FLOE_KERNEL_UP_GEMV, st,
+                        launch_up_gemv_grouped(static_cast<const DevExpert*>(L->dev_table), groups, n_groups,
+                                               w.up.max_groups, w.chunk, xh, slots, v, task_tau, mask, L->s.d, L->s.f,
+                                               L->s.bits, L->s.group, st));
+        else
+            FLOE_LAUNCH(FLOE_KERNEL_UP_GEMV, st,
+                        launch_up_gemv(map, xh, nullptr, v, task_tau, mask, L->s.d, L->s.f, L->s.bits, L->s.group,
+                                       w.n_tasks, st));
+        UnionArgs ua{};
+        ua.table = static_cast<const DevExpert*>(L->dev_table);
+        ua.groups = groups; ua.n_groups = n_groups; ua.x = xh; ua.v = v; ua.mask_words = mask;
+        ua.task_scale = task_weight; ua.count = count; ua.partial = partial;
+        ua.urow = reinterpret_cast<int32_t*>(base + w.urow_off);
+        ua.ucount = reinterpret_cast<int32_t*>(base + w.ucount_off);
+        ua.hbuf = reinterpret_cast<uint4*>(base + w.hbuf_off);
+        ua.slots = slots; ua.f = L->s.f; ua.nt = w.up.nt; ua.cap = w.up.cap;
+        ua.nblk_gate = w.up.nblk_gate; ua.nblk_down = w.up.nblk_down;
+        FLOE_LAUNCH(FLOE_KERNEL_GATE_DOWN, st, launch_gate_down_union(ua, w.up, L->s.d, st));
+        nblk = w.up.nblk_down;
+        count_parts = w.up.nblk_gate;
     } else if (mask_ok && !batch_mfma &&
                route_in_place_ok(L->s.d, L->s.bits, L->s.group, L->n_experts, L->top_k, L->n_shared)) {
         // larger batches of shapes without a matrix-core path: [router + up GEMV + mask] -> [compaction + gate/down]
@@ -494,27 +560,32 @@ int floe_moe_layer_decode(const floe_layer* L, const floe_half* x, int T, floe_h
         ra.task_table = task_table;
         ra.task_expert = task_expert; ra.task_weight = task_weight; ra.task_tau = task_tau;
         FLOE_LAUNCH(FLOE_KERNEL_ROUTER, st, launch_router(ra, T, st));
+        // batches: the gate/down workgroups are launched in expert order (tasks that share an expert run side by side
+        // and share its rows in the L2)
+        TokenGroup* groups = reinterpret_cast<TokenGroup*>(base + w.groups_off);
+        int32_t* n_groups = reinterpret_cast<int32_t*>(base + w.ngroups_off);
+        // (only where the grouping kernel runs anyway: on its own it costs what the sharing saves)
+        int32_t* order = (mask_ok && batch_mfma && w.n_tasks > kFusedMaxTasks) ? reinterpret_cast<int32_t*>(base + w.order_off) : nullptr;
+        const int n_all = L->n_experts + L->n_shared;
+        const int chunk = mfma_chunk(n_all, w.n_tasks);
+        if (order || (mask_ok && batch_mfma))
+            FLOE_HIP(launch_group_tokens(task_expert, w.n_tasks, n_all, chunk, groups, n_groups, st, order));
         if (mask_ok && batch_mfma) {
             // decode batch: tokens routed to the same expert share one pass over its codes (matrix cores)
-            TokenGroup* groups = reinterpret_cast<TokenGroup*>(base + w.groups_off);
-            int32_t* n_groups = reinterpret_cast<int32_t*>(base + w.ngroups_off);
-            const int n_all = L->n_experts + L->n_shared;
-            const int chunk = mfma_chunk(n_all, w.n_tasks);
-            FLOE_HIP(launch_group_tokens(task_expert, w.n_tasks, n_all, chunk, groups, n_groups, st));
             FLOE_LAUNCH(FLOE_KERNEL_UP_GEMV, st,
                         launch_up_gemv_grouped(static_cast<const DevExpert*>(L->dev_table), groups, n_groups,
                                                mfma_max_groups(n_all, w.n_tasks), chunk, xh, slots, v, task_tau,
                                                mask, L->s.d, L->s.f, L->s.bits, L->s.group, st));
             FLOE_LAUNCH(FLOE_KERNEL_GATE_DOWN, st,
                         launch_gate_down(map, nullptr, L->s.f, xh, v, mask, nullptr, count, task_weight, partial, L->s.d,
-                                         L->s.f, w.n_tasks, w.nblk, st));
+                                         L->s.f, w.n_tasks, w.nblk, st, nullptr, order));
         } else if (mask_ok) {
             FLOE_LAUNCH(FLOE_KERNEL_UP_GEMV, st,
                         launch_up_gemv(map, xh, nullptr, v, task_tau, mask, L->s.d, L->s.f, L->s.bits, L->s.group,
                                        w.n_tasks, st));
             FLOE_LAUNCH(FLOE_KERNEL_GATE_DOWN, st,
                         launch_gate_down(map, nullptr, L->s.f, xh, v, mask, nullptr, count, task_weight, partial, L->s.d,
-                                         L->s.f, w.n_tasks, w.nblk, st));
+                                         L->s.f, w.n_tasks, w.nblk, st, nullptr, order));
         } else {
             FLOE_LAUNCH(FLOE_KERNEL_UP_GEMV, st,
                         launch_up_gemv(map, xh, nullptr, v, nullptr, nullptr, L->s.d, L->s.f, L->s.bits,

@@ -37,7 +37,8 @@ __global__ __launch_bounds__(256) void gate_down_kernel(TaskMap map, const h16* 
                                                         int32_t* __restrict__ idx, int32_t* __restrict__ count,
                                                         const float* __restrict__ task_scale,
                                                         float* __restrict__ partial, int f,
-                                                        const int32_t* __restrict__ rows) {
+                                                        const int32_t* __restrict__ rows,
+                                                        const int32_t* __restrict__ order) {
     constexpr int d = 512 * NV;
     using Tile = GdTile<NV>;
     constexpr int BG = Tile::BG, B = Tile::B, VPR = Tile::VPR, RG = Tile::RG;
@@ -48,7 +49,11 @@ __global__ __launch_bounds__(256) void gate_down_kernel(TaskMap map, const h16* 
     __shared__ float hl[B];
     const int tid = threadIdx.x;
     const int wave = tid >> 6, lane = tid & 63;
-    const int task = blockIdx.y;
+    // order (batches): row y of the grid works on task order[y]; the tasks are sorted by expert, so the workgroups that
+    // run at the same time belong to few experts, and with a block count that is a multiple of the number of XCDs the
+    // workgroups of one channel range sit on one XCD: a row that several tokens selected is fetched from HBM once and
+    // served to the others by that XCD's L2
+    const int task = order ? order[blockIdx.y] : blockIdx.y;
     const int t = task / map.slots;
     const DevExpert e = task_expert_of(map, task);
     const float out_scale = task_scale ? task_scale[task] : 1.0f;
@@ -253,6 +258,9 @@ int gd_blocks(int n_tasks, int f) {
     if (n_tasks <= 0) return 1;
     int nblk = num_cus() / n_tasks;
     nblk = nblk < 1 ? 1 : nblk;
+    // batches: a multiple of the 8 XCDs, so that block b of every task runs on
+    // XCD b % 8 (workgroups go to the XCDs in turn) and tasks that share an expert share its rows in that XCD's L2
+    if (n_tasks > kFusedMaxTasks) nblk = (nblk + 7) / 8 * 8;
     const int by_f = (f + 3) / 4;  // a workgroup should have at least a few channels to look at
     nblk = nblk > by_f ? by_f : nblk;
     return nblk < 1 ? 1 : nblk;
@@ -261,31 +269,32 @@ int gd_blocks(int n_tasks, int f) {
 template <int NV>
 static hipError_t launch_nv(const TaskMap& map, const h16* staged, int gd_rows, const h16* x, const float* v,
                             const uint32_t* mask_words, int32_t* idx, int32_t* count, const float* task_scale,
-                            float* partial, int f, int n_tasks, int nblk, const int32_t* rows, hipStream_t stream) {
+                            float* partial, int f, int n_tasks, int nblk, const int32_t* rows, const int32_t* order,
+                            hipStream_t stream) {
     dim3 grid(nblk, n_tasks), block(256);
     if (mask_words)
         gate_down_kernel<NV, true><<<grid, block, 0, stream>>>(map, staged, gd_rows, x, v, mask_words, idx, count,
-                                                              task_scale, partial, f, nullptr);
+                                                              task_scale, partial, f, nullptr, order);
     else if (rows)
         gate_down_kernel<NV, false, true><<<grid, block, 0, stream>>>(map, staged, gd_rows, x, v, nullptr, idx, count,
-                                                                     task_scale, partial, f, rows);
+                                                                     task_scale, partial, f, rows, order);
     else
         gate_down_kernel<NV, false><<<grid, block, 0, stream>>>(map, staged, gd_rows, x, v, nullptr, idx, count,
-                                                               task_scale, partial, f, nullptr);
+                                                               task_scale, partial, f, nullptr, order);
     return hipGetLastError();
 }
 
 hipError_t launch_gate_down(const TaskMap& map, const h16* staged, int gd_rows, const h16* x, const float* v,
                             const uint32_t* mask_words, int32_t* idx, int32_t* count, const float* task_scale,
                             float* partial, int d, int f, int n_tasks, int nblk, hipStream_t stream,
-                            const int32_t* rows) {
+                            const int32_t* rows, const int32_t* order) {
     if (n_tasks == 0) return hipSuccess;
     if (rows && (mask_words || !staged)) return hipErrorInvalidValue;  // explicit rows go with a staged list
     if (mask_words && mask_words_per_task(f) > kMaxMaskWords) return hipErrorInvalidValue;
 #define FLOE_NV_CASE(N)                                                                                            \
     case N:                                                                                                        \
         return launch_nv<N>(map, staged, gd_rows, x, v, mask_words, idx, count, task_scale, partial, f, n_tasks, nblk, \
-                            rows, stream);
+                            rows, order, stream);
     switch (d / 512) {
         FLOE_NV_CASE(1) FLOE_NV_CASE(2) FLOE_NV_CASE(3) FLOE_NV_CASE(4) FLOE_NV_CASE(5) FLOE_NV_CASE(6)
         FLOE_NV_CASE(7) FLOE_NV_CASE(8) FLOE_NV_CASE(9) FLOE_NV_CASE(10) FLOE_NV_CASE(11) FLOE_NV_CASE(12)

@@ -79,7 +79,7 @@ inline int mfma_max_groups(int n_all, int n_tasks) {
 // grouping pays once experts see about two tokens each; below that the per-token kernels read the same bytes
 inline bool mfma_batch_pays(int n_all, int n_tasks) { return n_tasks >= 2 * n_all; }
 hipError_t launch_group_tokens(const int32_t* task_expert, int n_tasks, int n_all, int chunk, TokenGroup* groups,
-                               int32_t* n_groups, hipStream_t stream);
+                               int32_t* n_groups, hipStream_t stream, int32_t* order = nullptr);
 hipError_t launch_up_gemv_grouped(const DevExpert* table, const TokenGroup* groups, const int32_t* n_groups,
                                   int max_groups, int chunk, const h16* x, int slots, float* v, const float* task_tau,
                                   uint32_t* mask_words, int d, int f, int bits, int group, hipStream_t stream);
@@ -96,7 +96,37 @@ int gd_blocks(int n_tasks, int f);
 hipError_t launch_gate_down(const TaskMap& map, const h16* staged, int gd_rows, const h16* x, const float* v,
                             const uint32_t* mask_words, int32_t* idx, int32_t* count, const float* task_scale,
                             float* partial, int d, int f, int n_tasks, int nblk, hipStream_t stream,
-                            const int32_t* rows = nullptr);
+                            const int32_t* rows = nullptr, const int32_t* order = nullptr);
+
+// S4 + S5 for decode batches on the matrix cores, one read of every row that any token of an expert group selected
+// (gate_down_union.hip).  The groups are those of launch_group_tokens; mask_words / v come from the GEMV kernels.
+struct UnionPlan {
+    int nblk_gate, nblk_down;  // channel blocks of the gate kernel; the down kernel takes nblk_gate / nblk_down of them each
+    int cap;                   // rows a gate block can hold (a multiple of 16)
+    int nt;                    // token rows kept in LDS: 8 or 16 (the group chunk)
+    int max_groups;
+    bool matrix_cores, fused;  // which kernels run (union_mode)
+};
+int union_mode();
+void set_union_mode(int m);
+struct UnionArgs {
+    const DevExpert* table;
+    const TokenGroup* groups;
+    const int32_t* n_groups;
+    const h16* x;
+    const float* v;               // [n_tasks][f]
+    const uint32_t* mask_words;   // [n_tasks][words]
+    const float* task_scale;      // [n_tasks] or nullptr
+    int32_t* count;               // [n_tasks][nblk_gate] selected channels per (task, gate block), or nullptr
+    float* partial;               // [n_tasks][nblk_down][d]
+    int32_t* urow;                // [max_groups][nblk_gate][cap] union rows, ascending
+    int32_t* ucount;              // [max_groups][nblk_gate]
+    uint4* hbuf;                  // [max_groups][nblk_gate][cap / 16][64] h fragments (hi, lo) in lane order
+    int32_t slots, f, nt, cap, nblk_gate, nblk_down;
+};
+UnionPlan union_plan(int d, int f, int n_tasks, int n_all, int chunk);
+bool union_shape_ok(int d, int f, const UnionPlan& p);
+hipError_t launch_gate_down_union(const UnionArgs& a, const UnionPlan& p, int d, hipStream_t stream);
 
 // S6 (and the "+=" of the one-expert entry points): reduce partial over blocks and slots.
 //   y_acc != nullptr: y_acc[t][i] += sum;   y_half != nullptr: y_half[t][i] = fp16(sum)

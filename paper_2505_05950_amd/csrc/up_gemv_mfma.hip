@@ -227,7 +227,11 @@ __global__ __launch_bounds__(kMfmaThreads) void up_gemv_mfma_kernel(const DevExp
     // quarters (v_permlane32_swap + v_permlane16_swap) hands every quarter ITS word of each unit.
     // Scales and zeros are fetched the same way (quarter g holds those of block 4Q+g) and passed to the
     // other quarters with ds_bpermute when their block comes up.
-    const int ch0 = (blockIdx.x * 8 + wave) * (16 * TILES);
+    // The workgroup walks the channel blocks blockIdx.x, blockIdx.x + gridDim.x, ...: the activation fragments above are
+    // prepared once and serve all of them (with one workgroup per block their preparation was a third of the run time).
+    const int n_cblocks = (f + 8 * 16 * TILES - 1) / (8 * 16 * TILES);
+    for (int cb = blockIdx.x; cb < n_cblocks; cb += gridDim.x) {
+    const int ch0 = (cb * 8 + wave) * (16 * TILES);
     // uniform base pointers plus 32-bit per-lane byte offsets (f <= 2^20 rows of <= 2 KiB)
     const char* cbase = reinterpret_cast<const char*>(e.codes);
     const char* sbase = reinterpret_cast<const char*>(e.scale);
@@ -392,6 +396,7 @@ __global__ __launch_bounds__(kMfmaThreads) void up_gemv_mfma_kernel(const DevExp
                 mask16[(size_t)task * nwords * 2 + (tile_base >> 4)] = (uint16_t)(m >> (16 * g));
         }
     }
+    }  // channel blocks
 }
 
 // ---------------------------------------------------------------------------------------------------
@@ -399,14 +404,17 @@ __global__ __launch_bounds__(kMfmaThreads) void up_gemv_mfma_kernel(const DevExp
 // `chunk` tasks.  One workgroup of 16 waves; a wave owns experts wave, wave + 16, ... and walks the task list
 // 64 tasks at a time: the lanes compare, a ballot gives the matches and a lane's place among them.
 // Deterministic (ascending expert, ascending task).  The task ids pass through LDS in tiles.
+// order (optional): all tasks in that same order, i.e. sorted by expert (see gate_down.hip: workgroups of tasks that
+// share an expert are launched next to each other so that they share the rows they both selected in the L2).
 // ---------------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(1024) void group_tokens_kernel(const int32_t* __restrict__ task_expert, int n_tasks,
                                                             int n_all, int chunk, TokenGroup* __restrict__ groups,
-                                                            int32_t* __restrict__ n_groups) {
+                                                            int32_t* __restrict__ n_groups, int32_t* __restrict__ order) {
     constexpr int kTile = 4096;
     constexpr int kWaves = 16;
     __shared__ int first_group[1024 + 64 + 1];  // n_all <= 1088 (1024 routed + 64 shared)
     __shared__ int count[1024 + 64];
+    __shared__ int first_task[1024 + 64 + 1];   // tasks of the experts before this one (for `order`)
     __shared__ int tile[kTile];
     const int tid = threadIdx.x;
     const int wave = tid >> 6, lane = tid & 63;
@@ -429,7 +437,11 @@ __global__ __launch_bounds__(1024) void group_tokens_kernel(const int32_t* __res
     __syncthreads();
     if (tid == 0) {
         first_group[0] = 0;
-        for (int e = 0; e < n_all; ++e) first_group[e + 1] += first_group[e];
+        first_task[0] = 0;
+        for (int e = 0; e < n_all; ++e) {
+            first_group[e + 1] += first_group[e];
+            first_task[e + 1] = first_task[e] + count[e];
+        }
         n_groups[0] = first_group[n_all];
     }
     __syncthreads();
@@ -457,6 +469,7 @@ __global__ __launch_bounds__(1024) void group_tokens_kernel(const int32_t* __res
                 if (match) {
                     const int pos = k + __popcll(m & below);
                     groups[first_group[e] + pos / chunk].task[pos % chunk] = base + i0 + lane;
+                    if (order) order[first_task[e] + pos] = base + i0 + lane;
                 }
                 k += __popcll(m);
             }
@@ -472,8 +485,8 @@ extern "C" int floe_debug_set_timeline_mfma(unsigned long long* p) {
 #endif
 
 hipError_t launch_group_tokens(const int32_t* task_expert, int n_tasks, int n_all, int chunk, TokenGroup* groups,
-                               int32_t* n_groups, hipStream_t stream) {
-    group_tokens_kernel<<<dim3(1), dim3(1024), 0, stream>>>(task_expert, n_tasks, n_all, chunk, groups, n_groups);
+                               int32_t* n_groups, hipStream_t stream, int32_t* order) {
+    group_tokens_kernel<<<dim3(1), dim3(1024), 0, stream>>>(task_expert, n_tasks, n_all, chunk, groups, n_groups, order);
     return hipGetLastError();
 }
 
@@ -496,7 +509,15 @@ static hipError_t launch_mfma_inst(int max_groups, hipStream_t stream, const Dev
         attr_set[dev].store(true, std::memory_order_release);
     }
     const int ch_per_wg = 8 * 16 * TILES;
-    const dim3 grid((f + ch_per_wg - 1) / ch_per_wg, max_groups);
+    // about two workgroups per compute unit over the groups that can exist at once, each taking an equal number of
+    // channel blocks
+    const int n_cblocks = (f + ch_per_wg - 1) / ch_per_wg;
+    const int est_groups = max_groups > 2 ? (3 * max_groups + 3) / 4 : 1;
+    const int wg_per_cu = lds > 80 * 1024 ? 1 : 2;  // what the fragments in LDS leave room for
+    int want = (wg_per_cu * num_cus() + est_groups - 1) / est_groups;
+    want = want < 1 ? 1 : (want > n_cblocks ? n_cblocks : want);
+    const int per_wg = (n_cblocks + want - 1) / want;
+    const dim3 grid((n_cblocks + per_wg - 1) / per_wg, max_groups);
     up_gemv_mfma_kernel<BITS, UPC, G32, NTPAD, TILES><<<grid, dim3(kMfmaThreads), lds, stream>>>(table, groups, n_groups, x,
                                                                                                  slots, v, task_tau,
                                                                                                  mask_words, f);

@@ -174,6 +174,29 @@ def test_layer_batches_through_the_matrix_core_gemv():
     _run_layer_case(19, 3, 4096, 530, 4, 64, 2, 0, 2, True, 6, 70)
 
 
+@pytest.mark.parametrize("kernels", ["expert_order", "matrix_cores", "lds_ring"])
+def test_layer_batches_read_the_union_of_selected_rows_once(kernels):
+    """All three ways of running steps 4-5 for a batch (floe_tuning): the one-token kernels in expert order (rows shared
+    through the L2), the matrix-core pair and the LDS-ring kernel (both read the union of a group's rows once).
+    More than 16 (token, slot) tasks: per expert group the rows of the union of the tokens' masks are read once and
+    applied to exactly the tokens that selected them (matrix-core gate and down kernels).  More than 16 tokens on one
+    expert (two groups), groups of one token, shared experts that see every token, every row selected (0 %), hardly
+    any (99 %), ragged f, d from 512 to 4096, every up-GEMV kernel in front (matrix-core, packed, generic)."""
+    import paper_2505_05950_amd as F
+    F.floe_tuning(F.TUNE_UNION_KERNELS, {"expert_order": 0, "matrix_cores": 1, "lds_ring": 2}[kernels])
+    try:
+        _run_layer_case(40, 3, 4096, 530, 4, 64, 2, 0, 2, True, 24, 80)
+        _run_layer_case(41, 5, 2048, 1408, 3, 32, 16, 2, 6, False, 12, 85)
+        _run_layer_case(42, 3, 1024, 3000, 2, 64, 3, 0, 1, False, 40, 0)
+        _run_layer_case(43, 3, 1024, 3000, 2, 64, 3, 0, 1, False, 40, 99)
+        _run_layer_case(44, 3, 512, 700, 2, 64, 5, 1, 2, True, 20, 70)
+        _run_layer_case(45, 3, 1536, 333, 8, 64, 4, 0, 2, True, 18, 60)
+        _run_layer_case(46, 3, 4096, 2100, 2, 64, 8, 0, 2, True, 33, 90, gap=True)
+        _run_layer_case(47, 5, 2048, 97, 3, 32, 30, 2, 4, False, 9, 50, gap=True)
+    finally:
+        F.floe_tuning(F.TUNE_UNION_KERNELS, 0)
+
+
 def test_layer_with_more_than_65536_channels():
     _run_layer_case(20, 3, 512, 66000, 2, 64, 3, 0, 2, True, 2, 97)
 
