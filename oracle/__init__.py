@@ -45,6 +45,8 @@ _lib.floe_oracle_threshold_for_sparsity.restype = C.c_float
 _lib.floe_oracle_threshold_for_sparsity.argtypes = [_f32p, C.c_int, C.c_int]
 _lib.floe_oracle_select.argtypes = [_f32p, C.c_int, C.c_float, _i32p]
 _lib.floe_oracle_masked_dense_ffn.argtypes = [_f32p, _u16p, C.c_int, C.c_int, _u16p, C.c_float, _f64p]
+_lib.floe_oracle_sparsified_ffn.argtypes = [C.c_int, _u16p, C.c_int, C.c_int, _u16p, _f32p, C.c_float, _f64p, _i32p,
+                                            C.POINTER(C.c_int32), _f64p]
 
 
 def set_threads(n: int) -> None:
@@ -153,6 +155,25 @@ def masked_dense_ffn(w_up_f32, gd, x, tau: float) -> np.ndarray:
     if rc:
         raise ValueError("floe_oracle_masked_dense_ffn: invalid argument")
     return y
+
+
+SPARSIFY_UP, SPARSIFY_GATE, SPARSIFY_DOWN = 0, 1, 2
+
+
+def sparsified_ffn(which: int, gd, x, a_up, tau: float):
+    """Eq. 1 with S_t (Eq. 5) on a_up / a_gate / a_down (Eq. 3-4); returns (y[d], idx[K], act[f])."""
+    gd = _h(gd)
+    x = _h(x)
+    a_up = np.ascontiguousarray(a_up, dtype=np.float32)
+    f, _, d = gd.shape
+    y = np.empty((d,), np.float64)
+    idx = np.empty((f,), np.int32)
+    K = C.c_int32(0)
+    act = np.empty((f,), np.float64)
+    rc = _lib.floe_oracle_sparsified_ffn(int(which), _p(gd, _u16p), d, f, _p(x, _u16p), _p(a_up, _f32p), C.c_float(tau),
+                                         _p(y, _f64p), _p(idx, _i32p), C.byref(K), _p(act, _f64p))
+    assert rc == 0, rc
+    return y, idx[: K.value].copy(), act
 
 
 def router(router_cm, x, top_k: int, renormalize: bool):

@@ -290,6 +290,41 @@ int floe_oracle_masked_dense_ffn(const float* w_up, const uint16_t* gd, int d, i
     return 0;
 }
 
+int floe_oracle_sparsified_ffn(int which, const uint16_t* gd, int d, int f, const uint16_t* x, const float* a_up,
+                               float tau, double* y, int32_t* idx, int32_t* K_out, double* act) {
+    if (d <= 0 || f < 0 || which < 0 || which > 2) return -1;
+    // Eq. 3-4: the three activations, every channel, dense loops
+    std::vector<double> a_gate(f), a_down(f);
+    parallel_for(f, [&](int j) {
+        double g = 0.0;
+        const uint16_t* gate = gd + (size_t)j * 2 * d;
+        for (int i = 0; i < d; ++i) g += (double)half_to_float(x[i]) * (double)half_to_float(gate[i]);
+        a_gate[j] = silu(g);
+        a_down[j] = a_gate[j] * (double)a_up[j];
+    });
+    // Eq. 5 on the chosen activation, compared as binary32 and strictly (as Alg. 1 does for a_up)
+    std::vector<char> keep(f);
+    int K = 0;
+    for (int j = 0; j < f; ++j) {
+        const double a = which == 0 ? (double)a_up[j] : (which == 1 ? a_gate[j] : a_down[j]);
+        if (act) act[j] = a;
+        keep[j] = std::fabs((float)a) > tau;
+        if (keep[j]) {
+            if (idx) idx[K] = j;
+            ++K;
+        }
+    }
+    if (K_out) *K_out = K;
+    // Eq. 1 with the sparsified activation in place: a channel that was dropped contributes exactly nothing
+    parallel_for(d, [&](int i) {
+        double acc = 0.0;
+        for (int j = 0; j < f; ++j)
+            if (keep[j]) acc += a_down[j] * (double)half_to_float(gd[(size_t)j * 2 * d + d + i]);
+        y[i] = acc;
+    });
+    return 0;
+}
+
 int floe_oracle_router(const uint16_t* router_cm, int n_experts, int d, const uint16_t* x,
                        int top_k, int renormalize, int32_t* ids, double* weights, double* probs) {
     if (n_experts <= 0 || top_k < 0 || top_k > n_experts || d <= 0) return -1;

@@ -86,6 +86,18 @@ int floe_oracle_dense_ffn(const float* w_up, const uint16_t* gd, int d, int f, c
 int floe_oracle_masked_dense_ffn(const float* w_up, const uint16_t* gd, int d, int f, const uint16_t* x,
                                  float tau, double* y);
 
+/*
+ * The three candidates for sparsification of Sec. 3.2.1 (Eq. 3-5): S_t applied to
+ *   which = 0: a_up = x.W_up          (what FloE uses; equals floe_oracle_masked_dense_ffn on the same a_up),
+ *   which = 1: a_gate = SiLU(x.W_gate),
+ *   which = 2: a_down = a_gate * a_up,
+ * inside the expert forward of Eq. 1: y = sum over the kept channels of a_gate_j * a_up_j * W_down[j, :].
+ * a_up is given (the caller computes it, e.g. with floe_oracle_up_gemv); the comparison |a| > tau is strict and taken
+ * on the binary32 value of a.  Optional outputs: idx / K_out (kept channels, ascending), act (the f values compared).
+ */
+int floe_oracle_sparsified_ffn(int which, const uint16_t* gd, int d, int f, const uint16_t* x, const float* a_up,
+                               float tau, double* y, int32_t* idx, int32_t* K_out, double* act);
+
 /* Router: logits_e = x . W_r[e], softmax (max-subtracted), top_k by probability (ties -> lower id),
  * weights p_e / sum_selected(p) if renormalize else p_e.  ids are listed by descending probability. */
 int floe_oracle_router(const uint16_t* router_cm, int n_experts, int d, const uint16_t* x,

@@ -218,3 +218,80 @@ def test_layer_with_all_experts_and_equal_logits_is_the_mean():
         ys.append(O.dense_ffn(w_hat, experts[e][3], x[0]))                         # 0 % sparsity == Eq. 1
     np.testing.assert_allclose(res["y"][0], np.mean(ys, axis=0), rtol=1e-5, atol=1e-9)   # v carried as binary32
     assert np.all(res["counts"] == f)
+
+
+# ---------------------------------------------------------------- the three sparsification candidates (Sec. 3.2.1)
+def _paper_orientation_expert(seed, d, f):
+    rng_key = S.stream_key(seed, 97, S.KIND_MISC)
+    w_gate = S.normal(rng_key, d * f, 0.05).reshape(d, f).astype(np.float16)          # R^{d x f}
+    w_up = S.normal(S.stream_key(seed, 96, S.KIND_MISC), d * f, 0.05).reshape(d, f).astype(np.float16)
+    w_down = S.normal(S.stream_key(seed, 95, S.KIND_MISC), f * d, 0.05).reshape(f, d).astype(np.float16)
+    x = S.normal(S.stream_key(seed, 94, S.KIND_MISC), d, 1.0).astype(np.float16)
+    return w_gate, w_up, w_down, x
+
+
+def test_sparsified_ffn_is_eq1_with_the_sparsity_function_on_the_chosen_activation():
+    """Eq. 1 with S_t (Eq. 5) on a_up, a_gate or a_down (Eq. 3-4), written with library mat-vecs in the paper's
+    orientation: catches a wrong activation, a swapped operand, a non-strict comparison."""
+    d, f = 96, 160
+    w_gate, w_up, w_down, x = _paper_orientation_expert(5, d, f)
+    gd = compact_from_paper_orientation(w_gate, w_down)
+    x64 = x.astype(np.float64)
+    a_up = (x64 @ w_up.astype(np.float64)).astype(np.float32)                          # the caller's a_up, binary32
+    g = x64 @ w_gate.astype(np.float64)
+    a_gate = g / (1.0 + np.exp(-g))
+    a_down = a_gate * a_up.astype(np.float64)
+    for which, act in [(O.SPARSIFY_UP, a_up.astype(np.float64)), (O.SPARSIFY_GATE, a_gate), (O.SPARSIFY_DOWN, a_down)]:
+        mags = np.sort(np.abs(act.astype(np.float32)))
+        for tau in [-1.0, float(mags[f // 2]), float(mags[(9 * f) // 10]), float(mags[-1])]:
+            keep = np.abs(act.astype(np.float32)) > np.float32(tau)                    # strict, in binary32
+            ref = (np.where(keep, a_down, 0.0)) @ w_down.astype(np.float64)
+            y, idx, got_act = O.sparsified_ffn(which, gd, x, a_up, tau)
+            assert np.array_equal(idx, np.nonzero(keep)[0])
+            np.testing.assert_allclose(got_act, act, rtol=1e-12, atol=1e-15)
+            np.testing.assert_allclose(y, ref, rtol=1e-10, atol=1e-12)
+    # a threshold that sits exactly on one value keeps that channel out (strict comparison of Alg. 1)
+    tau = float(np.abs(a_up)[7])
+    _, idx, _ = O.sparsified_ffn(O.SPARSIFY_UP, gd, x, a_up, tau)
+    assert 7 not in idx
+
+
+def test_sparsified_ffn_on_a_up_is_the_sparse_expert_forward_and_all_three_are_dense_below_zero():
+    d, f = 128, 192
+    w_gate, w_up, w_down, x = _paper_orientation_expert(6, d, f)
+    gd = compact_from_paper_orientation(w_gate, w_down)
+    w_up_cm = np.ascontiguousarray(w_up.T.astype(np.float32))
+    a_up = (x.astype(np.float64) @ w_up.astype(np.float64)).astype(np.float32)
+    tau = float(np.sort(np.abs(a_up))[f // 2])
+    y_up, idx, _ = O.sparsified_ffn(O.SPARSIFY_UP, gd, x, a_up, tau)
+    np.testing.assert_allclose(y_up, O.masked_dense_ffn(w_up_cm, gd, x, tau), rtol=1e-9, atol=1e-12)
+    np.testing.assert_allclose(y_up, O.sparse_ffn(gd, x, a_up, idx)[1], rtol=1e-9, atol=1e-12)
+    dense = O.dense_ffn(w_up_cm, gd, x)                   # (keeps x.W_up in double; a_up above is its binary32 rounding)
+    for which in (O.SPARSIFY_UP, O.SPARSIFY_GATE, O.SPARSIFY_DOWN):
+        np.testing.assert_allclose(O.sparsified_ffn(which, gd, x, a_up, -1.0)[0], dense, rtol=0, atol=2e-7 * np.abs(dense).max())
+
+
+def test_loss_ordering_of_the_three_candidates_on_gaussian_inputs():
+    """Theorem of Sec. 3.2.1 (L_down <= L_up < L_gate), the part that holds whatever the distributions: at equal
+    sparsity, thresholding a_down loses least, because it drops the smallest terms of the very sum it approximates.
+    (L_up < L_gate rests on the paper's assumption about the gate activations of real models, App. A; with zero-mean
+    Gaussian synthetic weights half of the SiLU outputs are near zero and the order of those two is the other way
+    round, which the test only records.)  Averaged over tokens; the margins are far above the sampling noise."""
+    d, f, n_tok = 256, 1024, 24
+    w_gate, w_up, w_down, _ = _paper_orientation_expert(7, d, f)
+    gd = compact_from_paper_orientation(w_gate, w_down)
+    w_up_cm = np.ascontiguousarray(w_up.T.astype(np.float32))
+    for pct in (50, 80):
+        loss = {0: 0.0, 1: 0.0, 2: 0.0}
+        for t in range(n_tok):
+            x = S.normal(S.stream_key(8, 93, S.KIND_MISC, t), d, 1.0).astype(np.float16)
+            a_up = (x.astype(np.float64) @ w_up.astype(np.float64)).astype(np.float32)
+            dense = O.dense_ffn(w_up_cm, gd, x)
+            for which in (0, 1, 2):
+                _, _, act = O.sparsified_ffn(which, gd, x, a_up, -1.0)
+                tau = O.threshold_for_sparsity(act.astype(np.float32), pct)
+                y, idx, _ = O.sparsified_ffn(which, gd, x, a_up, tau)
+                assert idx.size == f - (-(-f * pct // 100))
+                loss[which] += float(((dense - y) ** 2).sum())
+        assert loss[2] < 0.8 * loss[0] and loss[2] < 0.8 * loss[1], (pct, loss)
+        print(f"sparsity {pct} %: L_down {loss[2]:.1f}  L_up {loss[0]:.1f}  L_gate {loss[1]:.1f}")
