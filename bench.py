@@ -80,11 +80,12 @@ def main():
     ap.add_argument("--copies", type=int, default=8, help="layer copies rotated over (HBM, not cache, reads)")
     ap.add_argument("--launch", choices=["graph", "stream"], default="graph",
                     help="graph: the K steps are replayed from one HIP graph; stream: plain launches")
-    ap.add_argument("--workload", choices=["layer", "expert", "stage", "stack", "batch"], default="layer",
+    ap.add_argument("--workload", choices=["layer", "expert", "stage", "stack", "batch", "variants"], default="layer",
                     help="layer: the headline metric (default); expert: single-expert sweep over bit widths and "
                          "sparsity levels (Table 1 protocol); stage: host->HBM transfer of selected channels; "
                          "stack: 32 offloaded layers per token, gate/down matrices in pinned host memory; "
-                         "batch: decode batches of configs[2] (T=1,4,16) and configs[4] (T=1,8,32)")
+                         "batch: decode batches of configs[2] (T=1,4,16) and configs[4] (T=1,8,32); "
+                         "variants: the three sparsification candidates of Sec. 3.2.1 on one expert")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run a plain 256 MiB device copy five times (reference for hardware-counter runs)")
     ap.add_argument("--batch-cases", default="", help="batch workload only: cases to run as config:T,... "
@@ -117,6 +118,8 @@ def main():
         return bench_stack(args, np, torch, S, FL, dev)
     if args.workload == "batch":
         return bench_batch(args, np, torch, S, FL, dev)
+    if args.workload == "variants":
+        return bench_variants(args, np, torch, S, FL, dev)
 
     # ---------------------------------------------------------------- inputs (seeded, synthetic)
     t0 = time.time()
@@ -436,6 +439,59 @@ def bench_expert(args, np, torch, S, FL, dev):
                       "config": {"workload": "BASELINE configs[1]: d=4096 f=14336 group 64, bits 2/3/4 x sparsity 0/50/80/90 %, "
                                              "4 weight copies rotated, HIP-graph replay"},
                       "sweep": rows}), flush=True)
+
+
+def bench_variants(args, np, torch, S, FL, dev):
+    """The three candidates for sparsification of Sec. 3.2.1 on one Mixtral-shaped expert, 1 token: S_t on a_up (FloE),
+    on a_gate or on a_down, thresholds for 80 % and 90 % of the compared activation (Eq. 6 on this token).  Reports
+    time and the bytes each candidate HAS to read: with a_gate / a_down the whole gate projection comes first."""
+    K, W = args.steps, args.warmup
+    w_up, gd = S.expert_weights(SEED, 2, D, F_INT)
+    x = torch.from_numpy(S.tokens(SEED, 2, 1, D)).to(dev)
+    copies = 4
+    gd0 = torch.from_numpy(gd).to(dev)
+    q0 = FL.floe_quantize_expert(torch.from_numpy(w_up).to(dev), BITS, GROUP)
+    experts = [FL.Expert(D, F_INT, BITS, GROUP, *(q0 if c == 0 else tuple(t.clone() for t in q0)), gd0 if c == 0 else gd0.clone())
+               for c in range(copies)]
+    stream = torch.cuda.Stream()
+    codes_meta = D * F_INT * BITS // 8 + 4 * F_INT * (D // GROUP)
+    rows = []
+    names = {FL.SPARSIFY_UP: "a_up", FL.SPARSIFY_GATE: "a_gate", FL.SPARSIFY_DOWN: "a_down"}
+    for pct in (80, 90):
+        z = -(-F_INT * pct // 100)
+        for which in (FL.SPARSIFY_UP, FL.SPARSIFY_GATE, FL.SPARSIFY_DOWN):
+            y = torch.zeros((1, D), dtype=torch.float32, device=dev)
+            # the activation that is compared: run once with a threshold below zero and read it back from the lists
+            tau0 = torch.full((1,), -1.0, device=dev)
+            v = FL.floe_up_gemv(*q0, x, D, BITS, GROUP)
+            if which == FL.SPARSIFY_UP:
+                act = v
+            else:
+                g = (x.float() @ gd0[:, 0, :].float().t())
+                a_gate = g / (1 + torch.exp(-g))
+                act = a_gate if which == FL.SPARSIFY_GATE else a_gate * v      # harness-side calibration only
+            tau = torch.kthvalue(act.abs(), z, dim=1).values.contiguous()
+            _, _, cnt = FL.floe_expert_ffn_sparsified(experts[0], which, x, tau, None, y)
+            torch.cuda.synchronize()
+            Ksel = int(cnt.item())
+            ws = torch.empty((1 << 26,), dtype=torch.uint8, device=dev)
+
+            def call(i):
+                FL.floe_expert_ffn_sparsified(experts[i % copies], which, x, tau, None, y, workspace=ws)
+            ms = _graph_time(torch, stream, call, K, W)
+            if which == FL.SPARSIFY_UP:
+                need = codes_meta + 2 * Ksel * 2 * D                         # codes, then gate and down of the kept channels
+            elif which == FL.SPARSIFY_GATE:
+                need = F_INT * 2 * D + codes_meta * Ksel // F_INT + Ksel * 2 * D   # all of gate, codes and down of the kept
+            else:
+                need = F_INT * 2 * D + codes_meta + Ksel * 2 * D             # all of gate, all codes, down of the kept
+            rows.append({"thresholded": names[which], "sparsity_pct": pct, "K": Ksel, "us_per_expert_ffn": round(ms * 1e3, 2),
+                         "bytes_the_candidate_must_read": int(need), "MB": round(need / 1e6, 1)})
+            log(f"[bench] S_t on {names[which]:6s} at {pct} %: K={Ksel}, {ms * 1e3:.1f} us, must read {need / 1e6:.1f} MB")
+    print(json.dumps({"metric": "us per expert-FFN for the three sparsification candidates (Sec. 3.2.1)", "value": rows[3]["us_per_expert_ffn"],
+                      "unit": "us", "n_gpus": 1, "higher_is_better": False, "data": "synthetic",
+                      "config": {"workload": "one Mixtral-shaped expert (d=4096 f=14336, INT2 g64 up projection), 1 token, 4 weight "
+                                             "copies rotated, HIP-graph replay"}, "results": rows}), flush=True)
 
 
 def bench_stage(args, np, torch, S, FL, dev):

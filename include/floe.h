@@ -166,6 +166,23 @@ int floe_expert_ffn_sparse(const floe_expert* e, const floe_half* x, int T, cons
                            const float* out_scale, float* y_acc, int32_t* idx, int32_t* count, void* workspace,
                            size_t workspace_bytes, void* stream);
 
+/*
+ * The three candidates for sparsification that Sec. 3.2.1 compares (Eq. 3-5): the sparsity function S_t applied to
+ *   FLOE_SPARSIFY_UP    a_up = x . W_up^Q            (what FloE uses: identical to floe_expert_ffn_sparse),
+ *   FLOE_SPARSIFY_GATE  a_gate = SiLU(x . W_gate),
+ *   FLOE_SPARSIFY_DOWN  a_down = a_gate * a_up,
+ * inside the expert forward of Eq. 1: y_acc[t] += out_scale[t] * sum over kept channels of a_gate_j a_up_j W_down[j,:],
+ * kept = { j : |a_j| > tau[t] } (strict, binary32), written to idx / count as in floe_expert_ffn_sparse (both required
+ * for the last two).  With a_gate or a_down the whole gate projection is read before any channel can be dropped and
+ * only down rows are saved: these two exist for the comparison of Sec. 3.2.1, not for speed.
+ * workspace: floe_expert_sparsified_workspace_bytes().
+ */
+typedef enum { FLOE_SPARSIFY_UP = 0, FLOE_SPARSIFY_GATE = 1, FLOE_SPARSIFY_DOWN = 2 } floe_sparsify;
+size_t floe_expert_sparsified_workspace_bytes(const floe_shape* s, int T);
+int floe_expert_ffn_sparsified(const floe_expert* e, int which, const floe_half* x, int T, const float* tau,
+                               const float* out_scale, float* y_acc, int32_t* idx, int32_t* count, void* workspace,
+                               size_t workspace_bytes, void* stream);
+
 /* ------------------------------------------------------------------------------------------------
  * One MoE layer (S1..S6).  Routed experts come first in `experts`, the n_shared always-on experts
  * (weight 1) follow.  All experts of a layer share one floe_shape.

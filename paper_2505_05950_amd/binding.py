@@ -83,6 +83,9 @@ def load():
     lib.floe_expert_workspace_bytes.argtypes = [C.POINTER(_Shape), i32]
     lib.floe_gate_down_sparse.argtypes = [C.POINTER(_Expert), vp, i32, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.floe_expert_ffn_sparse.argtypes = [C.POINTER(_Expert), vp, i32, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.floe_expert_sparsified_workspace_bytes.restype = sz
+    lib.floe_expert_sparsified_workspace_bytes.argtypes = [C.POINTER(_Shape), i32]
+    lib.floe_expert_ffn_sparsified.argtypes = [C.POINTER(_Expert), i32, vp, i32, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.floe_layer_table_bytes.restype = sz
     lib.floe_layer_table_bytes.argtypes = [C.POINTER(_Layer)]
     lib.floe_layer_build_table.argtypes = [C.POINTER(_Layer), vp, sz, vp]
@@ -241,6 +244,24 @@ def floe_expert_ffn_sparse(e: Expert, x, tau, out_scale, y_acc, idx=None, count=
     es = e.c_struct()
     _check(load().floe_expert_ffn_sparse(C.byref(es), _ptr(x), T, _ptr(tau), _ptr(out_scale), _ptr(y_acc), _ptr(idx),
                                          _ptr(count), wp, wn, _stream(stream)), "floe_expert_ffn_sparse")
+    return y_acc, idx, count
+
+
+SPARSIFY_UP, SPARSIFY_GATE, SPARSIFY_DOWN = 0, 1, 2
+
+
+def floe_expert_ffn_sparsified(e: Expert, which: int, x, tau, out_scale, y_acc, workspace=None, stream=None):
+    """Eq. 1 with the sparsity function on a_up / a_gate / a_down (Sec. 3.2.1); returns (y_acc, idx, count)."""
+    T = x.shape[0]
+    idx = torch.full((T, e.f), -1, dtype=torch.int32, device=x.device)
+    count = torch.empty((T,), dtype=torch.int32, device=x.device)
+    if workspace is None:
+        s = _shape(e.d, e.f, e.bits, e.group)
+        workspace = _workspace(int(load().floe_expert_sparsified_workspace_bytes(C.byref(s), T)), x.device)
+    wp, wn = _aligned_ptr(workspace)
+    es = e.c_struct()
+    _check(load().floe_expert_ffn_sparsified(C.byref(es), int(which), _ptr(x), T, _ptr(tau), _ptr(out_scale), _ptr(y_acc),
+                                             _ptr(idx), _ptr(count), wp, wn, _stream(stream)), "floe_expert_ffn_sparsified")
     return y_acc, idx, count
 
 

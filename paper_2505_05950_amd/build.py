@@ -9,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libfloe_hip.so")
-SOURCES = ["api.hip", "quantize.hip", "up_gemv.hip", "up_gemv_mfma.hip", "fused_layer.hip", "fused_int2.hip", "fused_int3.hip", "fused_int4.hip", "select.hip", "gate_down.hip", "gate_down_union.hip", "router.hip", "stage.hip", "prefetch.hip", "static_scratch.hip"]
+SOURCES = ["api.hip", "quantize.hip", "up_gemv.hip", "up_gemv_mfma.hip", "fused_layer.hip", "fused_int2.hip", "fused_int3.hip", "fused_int4.hip", "select.hip", "gate_down.hip", "gate_down_union.hip", "variants.hip", "router.hip", "stage.hip", "prefetch.hip", "static_scratch.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc",

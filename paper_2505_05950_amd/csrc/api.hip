@@ -387,6 +387,70 @@ int floe_expert_ffn_sparse(const floe_expert* e, const floe_half* x, int T, cons
     return FLOE_OK;
 }
 
+// workspace of the sparsification variants: [v][act][h: T*f floats each][partial: T*nblk*d floats]
+namespace {
+struct VariantWs {
+    size_t v_off, act_off, h_off, partial_off, total;
+    int nblk;
+};
+VariantWs variant_ws(const floe_shape* s, int T) {
+    VariantWs w;
+    w.nblk = gd_blocks(T, s->f);
+    size_t o = 0;
+    w.v_off = o;       o += align_up((size_t)T * s->f * 4);
+    w.act_off = o;     o += align_up((size_t)T * s->f * 4);
+    w.h_off = o;       o += align_up((size_t)T * s->f * 4);
+    w.partial_off = o; o += align_up((size_t)T * w.nblk * s->d * 4);
+    w.total = o;
+    return w;
+}
+}  // namespace
+
+size_t floe_expert_sparsified_workspace_bytes(const floe_shape* s, int T) {
+    if (check_shape(s) != FLOE_OK || T < 0) return 0;
+    const size_t a = expert_ws(s, T).total, b = variant_ws(s, T).total;
+    return a > b ? a : b;
+}
+
+int floe_expert_ffn_sparsified(const floe_expert* e, int which, const floe_half* x, int T, const float* tau,
+                               const float* out_scale, float* y_acc, int32_t* idx, int32_t* count, void* workspace,
+                               size_t workspace_bytes, void* stream) {
+    if (which == FLOE_SPARSIFY_UP)
+        return floe_expert_ffn_sparse(e, x, T, tau, out_scale, y_acc, idx, count, workspace, workspace_bytes, stream);
+    if (which != FLOE_SPARSIFY_GATE && which != FLOE_SPARSIFY_DOWN) return FLOE_EINVAL;
+    if (!e) return FLOE_EINVAL;
+    int rc = check_shape(&e->s);
+    if (rc) return rc;
+    if ((rc = check_T(T))) return rc;
+    if (T == 0) return FLOE_OK;
+    if (!e->up_codes || !e->up_scale || !e->up_zero || !e->gd || !x || !tau || !y_acc || !idx || !count || !workspace)
+        return FLOE_EINVAL;
+    if (!aligned(e->up_codes, 16) || !aligned(e->gd, 16) || !aligned(x, 16) || !aligned(y_acc, 16) ||
+        !aligned(workspace, kAlign))
+        return FLOE_EINVAL;
+    if (e->gd_is_staged || e->gd_rows != e->s.f) return FLOE_EINVAL;
+    const VariantWs w = variant_ws(&e->s, T);
+    if (workspace_bytes < w.total) return FLOE_EWORKSPACE;
+    char* base = static_cast<char*>(workspace);
+    float* v = reinterpret_cast<float*>(base + w.v_off);
+    float* act = reinterpret_cast<float*>(base + w.act_off);
+    float* hval = reinterpret_cast<float*>(base + w.h_off);
+    float* partial = reinterpret_cast<float*>(base + w.partial_off);
+    hipStream_t st = (hipStream_t)stream;
+    const h16* xh = reinterpret_cast<const h16*>(x);
+    const h16* gd = reinterpret_cast<const h16*>(e->gd);
+    // a_up for every channel (the quantized up projection), a_gate for every channel, the chosen activation against t,
+    // then only the down rows of the channels that are kept
+    FLOE_LAUNCH(FLOE_KERNEL_UP_GEMV, st,
+                launch_up_gemv(single_map(e), xh, nullptr, v, nullptr, nullptr, e->s.d, e->s.f, e->s.bits, e->s.group, T, st));
+    FLOE_HIP(launch_gate_dense(gd, xh, v, which, e->s.d, e->s.f, T, act, hval, st));
+    FLOE_LAUNCH(FLOE_KERNEL_SELECT, st, launch_select(act, e->s.f, T, tau, idx, count, st));
+    FLOE_LAUNCH(FLOE_KERNEL_GATE_DOWN, st,
+                launch_down_rows(gd, hval, idx, count, out_scale, e->s.d, e->s.f, T, w.nblk, partial, st));
+    FLOE_LAUNCH(FLOE_KERNEL_COMBINE, st, launch_combine(partial, e->s.d, T, 1, w.nblk, y_acc, nullptr, st));
+    return FLOE_OK;
+}
+
 size_t floe_layer_table_bytes(const floe_layer* L) {
     if (!L || L->n_experts < 0 || L->n_shared < 0) return 0;
     return align_up((size_t)(L->n_experts + L->n_shared) * sizeof(DevExpert));

@@ -128,6 +128,13 @@ UnionPlan union_plan(int d, int f, int n_tasks, int n_all, int chunk);
 bool union_shape_ok(int d, int f, const UnionPlan& p);
 hipError_t launch_gate_down_union(const UnionArgs& a, const UnionPlan& p, int d, hipStream_t stream);
 
+// The other sparsification candidates of Sec. 3.2.1 (variants.hip): act = a_gate (which = 1) or a_down (which = 2) and
+// h = a_gate * a_up for every channel; then the down rows of the kept channels only.
+hipError_t launch_gate_dense(const h16* gd, const h16* x, const float* v, int which, int d, int f, int T, float* act,
+                             float* hval, hipStream_t stream);
+hipError_t launch_down_rows(const h16* gd, const float* hval, const int32_t* idx, const int32_t* count,
+                            const float* out_scale, int d, int f, int T, int nblk, float* partial, hipStream_t stream);
+
 // S6 (and the "+=" of the one-expert entry points): reduce partial over blocks and slots.
 //   y_acc != nullptr: y_acc[t][i] += sum;   y_half != nullptr: y_half[t][i] = fp16(sum)
 hipError_t launch_combine(const float* partial, int d, int T, int slots, int nblk, float* y_acc, h16* y_half,
