@@ -719,6 +719,53 @@ def bench_stack(args, np, torch, S, FL, dev):
         sweep.append({"vram_budget_GB": budget, "resident_layers": n_res, "ms_per_token": round(b_ms, 3),
                       "tokens_per_s": round(1e3 / b_ms, 1), "staged_MB_per_token": round(b_bytes / 1e6, 1)})
         log(f"[bench] budget {budget} GB: {n_res} layers resident, {b_ms:.2f} ms/token, {b_bytes / 1e6:.0f} MB staged")
+    # ---- the same budgets spent on resident CHANNELS instead of whole layers: per expert the channels that the
+    # calibration tokens selected most often stay in HBM (a policy of this harness; the paper names none), every layer
+    # keeps the same share, and a token copies only the selected channels that are not resident
+    cal_counts = []
+    for e in range(N_EXPERTS):
+        vcal = FL.floe_up_gemv(*base[e][0], cal, D, BITS, GROUP)
+        cal_counts.append((vcal.abs() > tau_e[e]).sum(dim=0))
+    M_cache = FL.MissPath(torch.cuda.Stream(), TOP_K, dev)
+    cstats = torch.zeros((n_layers, TOP_K, 4), dtype=torch.int32, device=dev)
+    cache_sweep = []
+    for budget in (12, 16, 20, 24, 32, 48):
+        share = max(0.0, min(1.0, (budget - fixed_gb) / (n_layers * layer_gb)))
+        r_per = int(share * F_INT)
+        caches = []
+        for p_ in range(pool):                     # one cache per distinct pinned layer (the 32 slots alias them)
+            c = FL.ChannelCache(layers[p_], 1, N_EXPERTS * r_per, cap)
+            for e in range(N_EXPERTS):
+                if r_per == 0:
+                    break
+                hot = torch.argsort(cal_counts[e], descending=True, stable=True)[:r_per].sort().values.to(torch.int32).contiguous()
+                cnt = torch.tensor([r_per], dtype=torch.int32, device=dev)
+                FL.floe_channel_cache_load(layers[p_], c, e, hot, cnt, e * r_per, r_per)
+            caches.append(c)
+        torch.cuda.synchronize()
+        lat, staged_b, hits, total = [], [], 0, 0
+        for i in range(n_tok + n_warm):
+            x = toks[i:i + 1].contiguous()
+            torch.cuda.synchronize()
+            t1 = time.perf_counter()
+            for l in range(n_layers):
+                FL.floe_moe_layer_decode_cached(layers[l], caches[l % pool], M_cache, x, y=y, stats=stats[l],
+                                                cache_stats=cstats[l], workspace=ws)
+                yf = y.float()
+                x = (yf / yf.std()).half()
+            torch.cuda.synchronize()
+            dt = time.perf_counter() - t1
+            if i >= n_warm:
+                lat.append(dt)
+                rec = stats.cpu().numpy().reshape(n_layers, TOP_K, 4)
+                staged_b.append(int(rec[:, :, 3].sum()) * 4 * D)
+                hits += int(cstats.cpu().numpy().reshape(n_layers, TOP_K, 4)[:, :, 2].sum())
+                total += int(rec[:, :, 1].sum())
+        row = {"vram_budget_GB": budget, "resident_share_of_channels": round(share, 3), "ms_per_token": round(float(np.median(lat)) * 1e3, 3),
+               "staged_MB_per_token": round(float(np.mean(staged_b)) / 1e6, 1), "hit_rate": round(hits / max(total, 1), 3)}
+        cache_sweep.append(row)
+        log(f"[bench] channel cache, budget {budget} GB: {row}")
+        del caches
     # ---- prefetch of the next layer from the current hidden state (intra-expert reuse, Sec. 3.3).  Hidden states of
     # neighbouring layers are made alike on purpose: x_{l+1} = (x_l + beta * y_l / std(y_l)) / std(...), which gives a
     # cosine similarity of about 1 / sqrt(1 + beta^2) (0.95 at beta = 0.33; the paper reports > 0.95 on Mixtral).
@@ -784,7 +831,8 @@ def bench_stack(args, np, torch, S, FL, dev):
                       "staged_bytes_per_token": int(nbytes), "staged_GBps": round(nbytes / (ms * 1e-3) / 1e9, 2),
                       "pinned_memcpy_GBps": round(peak, 2), "tokens_per_s": round(1e3 / ms, 2),
                       "resident_hbm_GB": round(fixed_gb, 2),
-                      "vram_budget_sweep": sweep, "prefetch_next_layer": prefetch_rows}), flush=True)
+                      "vram_budget_sweep": sweep, "resident_channel_cache_sweep": cache_sweep,
+                      "prefetch_next_layer": prefetch_rows}), flush=True)
 
 
 def bench_batch(args, np, torch, S, FL, dev):

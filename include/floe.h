@@ -207,7 +207,8 @@ typedef struct {
     int32_t expert; /* expert id */
     int32_t count;  /* K: number of selected channels */
     float weight;   /* combine weight */
-    int32_t pad;
+    int32_t staged; /* rows copied host -> HBM for this (token, slot) by this call (0 for a resident layer).  With chunks
+                       of 4*d bytes: bytes touched = count * 4 * d, bytes staged = staged * 4 * d */
 } floe_slot_stat;
 
 size_t floe_layer_table_bytes(const floe_layer* L);
@@ -318,6 +319,35 @@ int floe_moe_layer_decode_prefetched(const floe_layer* L, const floe_prefetch* p
                                      const floe_half* x, int T, floe_half* y, floe_slot_stat* stats,
                                      floe_prefetch_stat* prefetch_stats, void* workspace, size_t workspace_bytes,
                                      void* stream);
+
+/* ------------------------------------------------------------------------------------------------
+ * Resident channels under a memory budget ("with additional VRAM, we cache more ...", Sec. 4.1): some [gate | down]
+ * chunks of an offloaded layer are kept in HBM, and a decode call copies only the selected channels that are not.
+ * Which channels are kept is the caller's policy; the paper gives none.
+ *   pool          dev [resident_rows + T * slots * capacity_rows][2][d]: the resident chunks first, then one slab of
+ *                 capacity_rows rows per (token, slot) for the chunks that have to be copied
+ *   row_of        dev [n_experts + n_shared][f]: pool row of channel j of expert e, or -1 (the caller fills it with -1
+ *                 once; floe_channel_cache_load enters the rows it writes)
+ * floe_channel_cache_load: channels idx[0 .. min(count[0], max_rows)) (dev) of `expert` are copied from its pinned host
+ *   matrix to pool rows first_row, first_row + 1, ... (byte copies) and entered in row_of; first_row + max_rows must not
+ *   exceed resident_rows.  A channel loaded twice keeps its latest row.
+ * floe_moe_layer_decode_cached: as floe_moe_layer_decode_offloaded, but a selected channel with a resident row is read
+ *   there and only the others cross the bus (m->miss_stream) into the task's slab; more misses than capacity_rows:
+ *   m->overflow[q] = 1 and the channels without a row are left out.  cache_stats (dev [T * slots] or NULL): hits, misses.
+ *   Results are identical to floe_moe_layer_decode_offloaded (same kernels, same order of summation).
+ */
+typedef struct {
+    floe_half* pool;
+    int32_t* row_of;
+    int32_t resident_rows;
+    int32_t capacity_rows;
+} floe_channel_cache;
+
+int floe_channel_cache_load(const floe_layer* L, const floe_channel_cache* c, int expert, const int32_t* idx,
+                            const int32_t* count, int first_row, int max_rows, void* stream);
+int floe_moe_layer_decode_cached(const floe_layer* L, const floe_channel_cache* c, const floe_miss_path* m,
+                                 const floe_half* x, int T, floe_half* y, floe_slot_stat* stats,
+                                 floe_prefetch_stat* cache_stats, void* workspace, size_t workspace_bytes, void* stream);
 
 /* ------------------------------------------------------------------------------------------------
  * S7 -- Sec. 3.4.2 (compact asynchronous transfer), done the MI355X way: a copy kernel on a side

@@ -12,5 +12,6 @@ from .binding import (  # noqa: F401
     floe_moe_layer_decode_offloaded, floe_moe_layer_prefetch,
     floe_moe_layer_decode_prefetched, Prefetch, MissPath, PREFETCH_STAT_DTYPE, floe_stage_channels, floe_status_string,
     words_per_channel, SLOT_STAT_DTYPE, floe_profile_kernel, KERNEL_IDS, floe_tuning, TUNE_UNION_KERNELS,
+    ChannelCache, floe_channel_cache_load, floe_moe_layer_decode_cached,
     floe_expert_ffn_sparsified, SPARSIFY_UP, SPARSIFY_GATE, SPARSIFY_DOWN,
 )

@@ -12,7 +12,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_NAME = "libfloe_hip.so"
 _lib = None
 
-SLOT_STAT_DTYPE = np.dtype([("expert", np.int32), ("count", np.int32), ("weight", np.float32), ("pad", np.int32)])
+SLOT_STAT_DTYPE = np.dtype([("expert", np.int32), ("count", np.int32), ("weight", np.float32), ("staged", np.int32)])
 
 
 class FloeError(RuntimeError):
@@ -53,6 +53,10 @@ class _Prefetch(C.Structure):
 class _MissPath(C.Structure):
     _fields_ = [("miss_stream", C.c_void_p), ("ev_lists_ready", C.c_void_p), ("ev_staged", C.c_void_p),
                 ("overflow", C.c_void_p)]
+
+
+class _ChannelCache(C.Structure):
+    _fields_ = [("pool", C.c_void_p), ("row_of", C.c_void_p), ("resident_rows", C.c_int32), ("capacity_rows", C.c_int32)]
 
 
 def lib_path() -> str:
@@ -97,6 +101,9 @@ def load():
     lib.floe_moe_layer_prefetch.argtypes = [C.POINTER(_Layer), C.POINTER(_Prefetch), vp, i32, vp, sz, vp]
     lib.floe_moe_layer_decode_prefetched.argtypes = [C.POINTER(_Layer), C.POINTER(_Prefetch), C.POINTER(_MissPath), vp, i32,
                                                      vp, vp, vp, vp, sz, vp]
+    lib.floe_channel_cache_load.argtypes = [C.POINTER(_Layer), C.POINTER(_ChannelCache), i32, vp, vp, i32, i32, vp]
+    lib.floe_moe_layer_decode_cached.argtypes = [C.POINTER(_Layer), C.POINTER(_ChannelCache), C.POINTER(_MissPath), vp, i32,
+                                                 vp, vp, vp, vp, sz, vp]
     lib.floe_stage_channels.argtypes = [vp, i32, i32, vp, vp, i32, vp, vp, vp, vp]
     _lib = lib
     return lib
@@ -421,6 +428,37 @@ def floe_moe_layer_decode_prefetched(L: Layer, P: Prefetch, M: MissPath, x, y=No
     _check(load().floe_moe_layer_decode_prefetched(C.byref(L._c), C.byref(P._c), C.byref(M._c), _ptr(x), T, _ptr(y),
                                                    _ptr(stats), _ptr(prefetch_stats), wp, wn, _stream(stream)),
            "floe_moe_layer_decode_prefetched")
+    return y
+
+
+class ChannelCache:
+    """Buffers of a floe_channel_cache: the pool (resident rows, then one slab per (token, slot)) and the row map."""
+
+    def __init__(self, L: "Layer", T: int, resident_rows: int, capacity_rows: int, device=None):
+        dev = device if device is not None else L.tau.device
+        n = T * (L.top_k + L.n_shared)
+        self.resident_rows, self.capacity_rows = int(resident_rows), int(capacity_rows)
+        self.pool = torch.empty((self.resident_rows + n * self.capacity_rows, 2, L.d), dtype=torch.float16, device=dev)
+        self.row_of = torch.full((len(L.experts), L.f), -1, dtype=torch.int32, device=dev)
+        self._c = _ChannelCache(self.pool.data_ptr(), self.row_of.data_ptr(), self.resident_rows, self.capacity_rows)
+
+
+def floe_channel_cache_load(L: Layer, cache: ChannelCache, expert: int, idx, count, first_row: int, max_rows: int, stream=None):
+    _check(load().floe_channel_cache_load(C.byref(L._c), C.byref(cache._c), int(expert), _ptr(idx), _ptr(count), int(first_row),
+                                          int(max_rows), _stream(stream)), "floe_channel_cache_load")
+
+
+def floe_moe_layer_decode_cached(L: Layer, cache: ChannelCache, M: MissPath, x, y=None, stats=None, cache_stats=None,
+                                 workspace=None, stream=None):
+    T = x.shape[0]
+    if y is None:
+        y = torch.empty((T, L.d), dtype=torch.float16, device=x.device)
+    if workspace is None:
+        workspace = L.workspace(T)
+    wp, wn = _aligned_ptr(workspace)
+    _check(load().floe_moe_layer_decode_cached(C.byref(L._c), C.byref(cache._c), C.byref(M._c), _ptr(x), T, _ptr(y),
+                                               _ptr(stats), _ptr(cache_stats), wp, wn, _stream(stream)),
+           "floe_moe_layer_decode_cached")
     return y
 
 

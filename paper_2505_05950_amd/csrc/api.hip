@@ -242,7 +242,7 @@ const char* floe_status_string(int status) {
 }
 
 int floe_last_hip_error(void) { return g_last_hip_error; }
-int floe_abi_version(void) { return 3; }
+int floe_abi_version(void) { return 4; }
 
 int floe_profile_kernel(int kernel_id, void* start_event, void* stop_event) {
     if (kernel_id < 0 || kernel_id > FLOE_KERNEL_FUSED_FFN) return FLOE_EINVAL;
@@ -705,7 +705,9 @@ int floe_moe_layer_decode_offloaded(const floe_layer* L, const floe_offload* o, 
                                  count, task_weight, partial, L->s.d, L->s.f, w.n_tasks, w.nblk, st));
     FLOE_LAUNCH(FLOE_KERNEL_COMBINE, st,
                 launch_combine(partial, L->s.d, T, slots, w.nblk, nullptr, reinterpret_cast<h16*>(y), st));
-    if (stats) FLOE_HIP(launch_stats(task_expert, count, 0, task_weight, reinterpret_cast<SlotStat*>(stats), w.n_tasks, st));
+    if (stats)
+        FLOE_HIP(launch_stats(task_expert, count, 0, task_weight, reinterpret_cast<SlotStat*>(stats), w.n_tasks, st, count,
+                              o->capacity_rows));
     return FLOE_OK;
 }
 
@@ -793,7 +795,78 @@ int floe_moe_layer_decode_prefetched(const floe_layer* L, const floe_prefetch* p
                                  task_weight, partial, L->s.d, L->s.f, w.n_tasks, w.nblk, st, rows));
     FLOE_LAUNCH(FLOE_KERNEL_COMBINE, st,
                 launch_combine(partial, L->s.d, T, slots, w.nblk, nullptr, reinterpret_cast<h16*>(y), st));
-    if (stats) FLOE_HIP(launch_stats(task_expert, count, 0, task_weight, reinterpret_cast<SlotStat*>(stats), w.n_tasks, st));
+    if (stats)
+        FLOE_HIP(launch_stats(task_expert, count, 0, task_weight, reinterpret_cast<SlotStat*>(stats), w.n_tasks, st, miss_count));
+    return FLOE_OK;
+}
+
+int floe_channel_cache_load(const floe_layer* L, const floe_channel_cache* c, int expert, const int32_t* idx,
+                            const int32_t* count, int first_row, int max_rows, void* stream) {
+    int rc = check_layer(L);
+    if (rc) return rc;
+    if (!c || !c->pool || !c->row_of || !idx || !count || !L->dev_table || !L->gd_on_host) return FLOE_EINVAL;
+    if (expert < 0 || expert >= L->n_experts + L->n_shared || first_row < 0 || max_rows < 0) return FLOE_EINVAL;
+    if ((long long)first_row + max_rows > c->resident_rows) return FLOE_EINVAL;  // the resident part of the pool ends there
+    if (!aligned(c->pool, 16)) return FLOE_EINVAL;
+    FLOE_LAUNCH(FLOE_KERNEL_STAGE, (hipStream_t)stream,
+                launch_cache_load(static_cast<const DevExpert*>(L->dev_table), expert, L->s.d, L->s.f, idx, count, first_row,
+                                  max_rows, reinterpret_cast<h16*>(c->pool), c->row_of, (hipStream_t)stream));
+    return FLOE_OK;
+}
+
+int floe_moe_layer_decode_cached(const floe_layer* L, const floe_channel_cache* c, const floe_miss_path* m,
+                                 const floe_half* x, int T, floe_half* y, floe_slot_stat* stats,
+                                 floe_prefetch_stat* cache_stats, void* workspace, size_t workspace_bytes, void* stream) {
+    int rc = check_layer(L);
+    if (rc) return rc;
+    if ((rc = check_T(T))) return rc;
+    if (T == 0) return FLOE_OK;
+    if (!c || !c->pool || !c->row_of || c->capacity_rows <= 0 || c->resident_rows < 0) return FLOE_EINVAL;
+    if (!m || !m->ev_lists_ready || !m->ev_staged) return FLOE_EINVAL;
+    if (!L->dev_table || !L->gd_on_host || !x || !y || !workspace) return FLOE_EINVAL;
+    if (!aligned(x, 16) || !aligned(y, 8) || !aligned(workspace, kAlign) || !aligned(c->pool, 16)) return FLOE_EINVAL;
+    const LayerWs w = layer_ws(L, T);
+    if (workspace_bytes < w.total) return FLOE_EWORKSPACE;
+    char* base = static_cast<char*>(workspace);
+    DevExpert* task_table = reinterpret_cast<DevExpert*>(base + w.table_off);
+    int32_t* task_expert = reinterpret_cast<int32_t*>(base + w.expert_off);
+    float* task_weight = reinterpret_cast<float*>(base + w.weight_off);
+    int32_t* count = reinterpret_cast<int32_t*>(base + w.count_off);
+    float* v = reinterpret_cast<float*>(base + w.v_off);
+    int32_t* idx = reinterpret_cast<int32_t*>(base + w.idx_off);
+    int32_t* rows = reinterpret_cast<int32_t*>(base + w.rows_off);
+    int32_t* miss_idx = reinterpret_cast<int32_t*>(base + w.missidx_off);
+    int32_t* miss_rows = reinterpret_cast<int32_t*>(base + w.missrows_off);
+    int32_t* miss_count = reinterpret_cast<int32_t*>(base + w.misscount_off);
+    float* partial = reinterpret_cast<float*>(base + w.partial_off);
+    hipStream_t st = (hipStream_t)stream, side = (hipStream_t)m->miss_stream;
+    const h16* xh = reinterpret_cast<const h16*>(x);
+    const int slots = L->top_k + L->n_shared;
+    TaskMap map{};
+    map.task_table = task_table;
+    map.slots = slots;
+
+    // lists on `stream`; where each selected channel sits (resident row, or a fresh row of the task's slab) and which
+    // ones are missing; the misses cross the bus on the miss stream; gate/down on the pool's rows
+    if ((rc = layer_lists(L, w, base, xh, T, st))) return rc;
+    FLOE_HIP(launch_match_rows(idx, count, task_expert, L->s.f, slots, c->capacity_rows, nullptr, nullptr, nullptr, rows,
+                               miss_idx, miss_rows, miss_count, m->overflow, reinterpret_cast<PrefetchStat*>(cache_stats),
+                               w.n_tasks, st, c->row_of, c->resident_rows));
+    FLOE_HIP(hipEventRecord((hipEvent_t)m->ev_lists_ready, st));
+    FLOE_HIP(hipStreamWaitEvent(side, (hipEvent_t)m->ev_lists_ready, 0));
+    FLOE_LAUNCH(FLOE_KERNEL_STAGE, side,
+                launch_stage_tasks(task_table, L->s.d, L->s.f, miss_idx, miss_count, c->capacity_rows,
+                                   reinterpret_cast<h16*>(c->pool), nullptr, w.n_tasks, side, miss_rows));
+    FLOE_HIP(hipEventRecord((hipEvent_t)m->ev_staged, side));
+    FLOE_HIP(hipStreamWaitEvent(st, (hipEvent_t)m->ev_staged, 0));
+    FLOE_LAUNCH(FLOE_KERNEL_GATE_DOWN, st,
+                launch_gate_down(map, reinterpret_cast<const h16*>(c->pool), c->capacity_rows, xh, v, nullptr, idx, count,
+                                 task_weight, partial, L->s.d, L->s.f, w.n_tasks, w.nblk, st, rows));
+    FLOE_LAUNCH(FLOE_KERNEL_COMBINE, st,
+                launch_combine(partial, L->s.d, T, slots, w.nblk, nullptr, reinterpret_cast<h16*>(y), st));
+    if (stats)
+        FLOE_HIP(launch_stats(task_expert, count, 0, task_weight, reinterpret_cast<SlotStat*>(stats), w.n_tasks, st, miss_count,
+                              c->capacity_rows));
     return FLOE_OK;
 }
 

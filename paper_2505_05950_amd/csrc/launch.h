@@ -160,11 +160,13 @@ struct SlotStat {
     int32_t expert;
     int32_t count;
     float weight;
-    int32_t pad;
+    int32_t staged;
 };
 // count_parts != 0: the count of task q is the sum of count[q * count_parts .. + count_parts)
+// staged (optional): rows of task q that were copied host -> HBM for this call; capacity > 0 clamps it (a list
+// longer than the staging slab is truncated)
 hipError_t launch_stats(const int32_t* task_expert, const int32_t* count, int count_parts, const float* task_weight,
-                        SlotStat* stats, int n_tasks, hipStream_t stream);
+                        SlotStat* stats, int n_tasks, hipStream_t stream, const int32_t* staged = nullptr, int capacity = 0);
 
 // S7
 hipError_t launch_stage(const h16* host_gd_dev, int d, int f, const int32_t* idx, const int32_t* count,
@@ -192,6 +194,11 @@ hipError_t launch_match_rows(const int32_t* idx, const int32_t* count, const int
                              int capacity_rows, const int32_t* row_of, const int32_t* pred_expert,
                              const int32_t* pred_count, int32_t* rows, int32_t* miss_idx, int32_t* miss_rows,
                              int32_t* miss_count, int32_t* overflow, PrefetchStat* stat, int n_tasks,
-                             hipStream_t stream);
+                             hipStream_t stream, const int32_t* expert_row_of = nullptr, int miss_first_row = 0);
+// Resident-channel cache: with expert_row_of ([n_experts][f], pool row of a resident channel or -1) match_rows looks the
+// channels up there instead (rows are rows of the whole pool; the misses of task q go to rows miss_first_row +
+// q * capacity_rows + m).  launch_cache_load makes channels resident.
+hipError_t launch_cache_load(const DevExpert* table, int expert, int d, int f, const int32_t* idx, const int32_t* count,
+                             int first_row, int max_rows, h16* pool, int32_t* row_of, hipStream_t stream);
 
 }  // namespace floe

@@ -42,21 +42,27 @@ __global__ __launch_bounds__(256) void match_rows_kernel(const int32_t* __restri
                                                          int32_t* __restrict__ rows, int32_t* __restrict__ miss_idx,
                                                          int32_t* __restrict__ miss_rows,
                                                          int32_t* __restrict__ miss_count,
-                                                         int32_t* __restrict__ overflow, PrefetchStat* __restrict__ stat) {
+                                                         int32_t* __restrict__ overflow, PrefetchStat* __restrict__ stat,
+                                                         const int32_t* __restrict__ expert_row_of, int miss_first_row) {
     __shared__ int wave_tot[4];
     __shared__ int hit_tot[4];
     const int q = blockIdx.x;
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int t = q / slots;
     const int ex = task_expert[q];
-    // the predicted task of the same token that loaded this expert, if any (slots <= 64: every thread scans)
+    // Resident-channel cache (expert_row_of given): the map is the expert's own, its entries are rows of the whole pool,
+    // and the task's fresh rows are its slab behind the resident part of the pool.
+    const bool cache = expert_row_of != nullptr;
+    // Prefetch: the predicted task of the same token that loaded this expert, if any (slots <= 64: every thread scans)
     int qp = -1;
-    for (int s = 0; s < slots; ++s)
-        if (qp < 0 && pred_expert[t * slots + s] == ex) qp = t * slots + s;
-    const bool matched = qp >= 0;
-    const int slab = matched ? qp : n_tasks + q;             // spare slabs follow the predicted ones
-    const int base = matched ? pred_count[qp] : 0;           // fresh rows go behind the predicted ones
-    const int32_t* map = matched ? row_of + (size_t)qp * f : nullptr;
+    if (!cache)
+        for (int s = 0; s < slots; ++s)
+            if (qp < 0 && pred_expert[t * slots + s] == ex) qp = t * slots + s;
+    const bool matched = cache || qp >= 0;
+    const int slab = cache ? q : (matched ? qp : n_tasks + q);   // spare slabs follow the predicted ones
+    const int base = (!cache && matched) ? pred_count[qp] : 0;   // fresh rows go behind the predicted ones
+    const int32_t* map = cache ? expert_row_of + (size_t)ex * f : (matched ? row_of + (size_t)qp * f : nullptr);
+    const int slab_row0 = cache ? miss_first_row + slab * capacity_rows : slab * capacity_rows;
     const int32_t* list = idx + (size_t)q * f;
     int32_t* out_rows = rows + (size_t)q * f;
     int32_t* out_mi = miss_idx + (size_t)q * f;
@@ -91,11 +97,11 @@ __global__ __launch_bounds__(256) void match_rows_kernel(const int32_t* __restri
         if (k < K) {
             int row = -1;
             if (hit) {
-                row = slab * capacity_rows + r;
+                row = cache ? r : slab_row0 + r;
             } else if (miss) {
                 const int m = n_miss + off + before;
                 const int fresh = base + m;
-                if (fresh < capacity_rows) row = slab * capacity_rows + fresh;
+                if (fresh < capacity_rows) row = slab_row0 + fresh;
                 out_mi[m] = j;          // listed even when it does not fit: its row is -1 and nothing is copied
                 out_mr[m] = row;
             }
@@ -112,7 +118,7 @@ __global__ __launch_bounds__(256) void match_rows_kernel(const int32_t* __restri
         if (stat) {
             PrefetchStat s;
             s.expert_predicted = matched ? 1 : 0;
-            s.predicted = matched ? pred_count[qp] : 0;
+            s.predicted = (!cache && matched) ? pred_count[qp] : 0;
             s.hits = n_hit;
             s.misses = n_miss;
             stat[q] = s;
@@ -132,11 +138,38 @@ hipError_t launch_match_rows(const int32_t* idx, const int32_t* count, const int
                              int capacity_rows, const int32_t* row_of, const int32_t* pred_expert,
                              const int32_t* pred_count, int32_t* rows, int32_t* miss_idx, int32_t* miss_rows,
                              int32_t* miss_count, int32_t* overflow, PrefetchStat* stat, int n_tasks,
-                             hipStream_t stream) {
+                             hipStream_t stream, const int32_t* expert_row_of, int miss_first_row) {
     if (n_tasks == 0) return hipSuccess;
     match_rows_kernel<<<dim3(n_tasks), dim3(256), 0, stream>>>(idx, count, task_expert, f, slots, capacity_rows, n_tasks,
                                                               row_of, pred_expert, pred_count, rows, miss_idx, miss_rows,
-                                                              miss_count, overflow, stat);
+                                                              miss_count, overflow, stat, expert_row_of, miss_first_row);
+    return hipGetLastError();
+}
+
+// Resident-channel cache (more memory = more of the experts kept in HBM, Sec. 4.1): the listed channels of one expert
+// are copied from its host matrix into rows first_row, first_row + 1, ... of the pool and entered in the expert's map.
+__global__ __launch_bounds__(256) void cache_load_kernel(const DevExpert* __restrict__ table, int expert, int vec_per_chunk,
+                                                         int f, const int32_t* __restrict__ idx,
+                                                         const int32_t* __restrict__ count, int first_row, int max_rows,
+                                                         uint4* __restrict__ pool, int32_t* __restrict__ row_of) {
+    const uint4* src = reinterpret_cast<const uint4*>(table[expert].gd);
+    const int K = min(min(count[0], max_rows), f);
+    const int lane = threadIdx.x & 63;
+    const int gw = blockIdx.x * 4 + (threadIdx.x >> 6), nw = gridDim.x * 4;
+    for (int k = gw; k < K; k += nw) {
+        const int j = idx[k];
+        if ((unsigned)j >= (unsigned)f) continue;
+        const uint4* s = src + (size_t)j * vec_per_chunk;
+        uint4* o = pool + (size_t)(first_row + k) * vec_per_chunk;
+        for (int i = lane; i < vec_per_chunk; i += kWave) o[i] = s[i];
+        if (lane == 0) row_of[(size_t)expert * f + j] = first_row + k;
+    }
+}
+
+hipError_t launch_cache_load(const DevExpert* table, int expert, int d, int f, const int32_t* idx, const int32_t* count,
+                             int first_row, int max_rows, h16* pool, int32_t* row_of, hipStream_t stream) {
+    cache_load_kernel<<<dim3(num_cus()), dim3(256), 0, stream>>>(table, expert, d / 4, f, idx, count, first_row, max_rows,
+                                                                reinterpret_cast<uint4*>(pool), row_of);
     return hipGetLastError();
 }
 

@@ -154,7 +154,8 @@ hipError_t launch_router(const RouterArgs& a, int T, hipStream_t stream) {
 
 // one wave per task: the lanes share the per-workgroup counts of a fused launch
 __global__ __launch_bounds__(256) void stats_kernel(const int32_t* task_expert, const int32_t* count, int count_parts,
-                                                    const float* task_weight, SlotStat* stats, int n_tasks) {
+                                                    const float* task_weight, SlotStat* stats, int n_tasks,
+                                                    const int32_t* staged, int capacity) {
     const int q = blockIdx.x * 4 + (threadIdx.x >> 6);
     const int lane = threadIdx.x & 63;
     if (q >= n_tasks) return;  // wave-uniform
@@ -171,16 +172,16 @@ __global__ __launch_bounds__(256) void stats_kernel(const int32_t* task_expert, 
         s.expert = task_expert[q];
         s.count = c;
         s.weight = task_weight[q];
-        s.pad = 0;
+        s.staged = staged ? (capacity > 0 ? min(staged[q], capacity) : staged[q]) : 0;
         stats[q] = s;
     }
 }
 
 hipError_t launch_stats(const int32_t* task_expert, const int32_t* count, int count_parts, const float* task_weight,
-                        SlotStat* stats, int n_tasks, hipStream_t stream) {
+                        SlotStat* stats, int n_tasks, hipStream_t stream, const int32_t* staged, int capacity) {
     if (n_tasks == 0) return hipSuccess;
     stats_kernel<<<dim3((n_tasks + 3) / 4), dim3(256), 0, stream>>>(task_expert, count, count_parts, task_weight,
-                                                                        stats, n_tasks);
+                                                                        stats, n_tasks, staged, capacity);
     return hipGetLastError();
 }
 

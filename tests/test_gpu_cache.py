@@ -1,0 +1,110 @@
+"""Resident-channel cache of an offloaded layer (floe_channel_cache_load / floe_moe_layer_decode_cached): resident
+rows are byte copies of the host rows, only the selected channels without a resident row cross the bus, and the result is
+that of the plain offloaded decode (bit for bit) and of the oracle."""
+import numpy as np
+import pytest
+import torch
+
+import floe_synth as S
+import oracle as O
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _threads():
+    O.set_threads(16)
+    yield
+    O.set_threads(1)
+
+
+@pytest.mark.parametrize("d,f", [(1024, 2048), (4096, 640)])
+def test_cached_decode_matches_offloaded_decode_and_oracle(d, f):
+    import gpu_common as G
+    import paper_2505_05950_amd as F
+    bits, group, n, top_k, T, pct = 2, 64, 4, 2, 3, 80
+    experts = [G.make_expert(*S.expert_weights(70, 4, d, f, 0, e), bits, group) for e in range(n)]
+    experts_np = [e[0] for e in experts]
+    wr = S.router_weights(70, 4, n, d)
+    x = S.tokens(70, 4, T, d)
+    tau = np.zeros((T, n), np.float32)
+    for t in range(T):
+        for e in range(n):
+            tau[t, e] = O.threshold_for_sparsity(O.up_gemv(*experts_np[e][:3], d, bits, group, x[t]), pct)
+    tau *= np.float32(1.0 + 2e-3)          # off the order statistic: no channel sits exactly on its threshold
+    ref = O.moe_layer(experts_np, 0, top_k, True, wr, x, tau, bits, group)
+    pinned = [torch.from_numpy(e[3]).pin_memory() for e in experts_np]
+    ex_host = [F.Expert(d, f, bits, group, e[1].up_codes, e[1].up_scale, e[1].up_zero, pinned[i]) for i, e in enumerate(experts)]
+    L = F.Layer(ex_host, 0, top_k, True, G.dev(wr), G.dev(tau), True, gd_on_host=True)
+    slots = top_k
+    side = torch.cuda.Stream()
+    ev_a, ev_b = torch.cuda.Event(), torch.cuda.Event()
+    staging = torch.zeros((T * slots, f, 2, d), dtype=torch.float16, device=G.DEV)
+    st_off = torch.zeros((T, slots, 4), dtype=torch.int32, device=G.DEV)
+    y_off = F.floe_moe_layer_decode_offloaded(L, G.dev(x), staging, f, side, ev_a, ev_b, stats=st_off).clone()
+    torch.cuda.synchronize()
+    so = st_off.cpu().numpy().reshape(T, slots, 4).copy().view(F.SLOT_STAT_DTYPE).reshape(T, slots)
+    assert np.array_equal(so["staged"], so["count"])          # nothing resident: every selected chunk crossed the bus
+
+    # resident sets: a different pattern per expert (every third channel from e, plus a solid block); expert 3: nothing
+    resident = []
+    for e in range(n):
+        r = np.zeros(0, np.int32) if e == 3 else np.union1d(np.arange(e, f, 3), np.arange(100 * e, 100 * e + 57)).astype(np.int32)
+        resident.append(r)
+    total = sum(r.size for r in resident)
+    cap = f
+    cache = F.ChannelCache(L, T, total + 5, cap)
+    cache.pool.zero_()
+    first = 0
+    for e in range(n):
+        if resident[e].size == 0:
+            continue
+        idx = G.dev(resident[e])
+        cnt = torch.tensor([resident[e].size], dtype=torch.int32, device=G.DEV)
+        F.floe_channel_cache_load(L, cache, e, idx, cnt, first, resident[e].size)
+        first += resident[e].size
+    torch.cuda.synchronize()
+    pool = cache.pool.cpu().numpy()
+    row_of = cache.row_of.cpu().numpy()
+    first = 0
+    for e in range(n):
+        r = resident[e]
+        assert np.array_equal(np.nonzero(row_of[e] >= 0)[0], r)
+        assert np.array_equal(row_of[e][r], first + np.arange(r.size))
+        assert pool[first:first + r.size].tobytes() == experts_np[e][3][r].tobytes()     # byte copies of the host rows
+        first += r.size
+    with pytest.raises(F.FloeError):        # loading past the resident part of the pool is refused
+        F.floe_channel_cache_load(L, cache, 0, G.dev(resident[0]), torch.tensor([4], dtype=torch.int32, device=G.DEV), total, 10)
+
+    M = F.MissPath(torch.cuda.Stream(), T * slots, G.DEV)
+    stats = torch.zeros((T, slots, 4), dtype=torch.int32, device=G.DEV)
+    cstats = torch.zeros((T * slots, 4), dtype=torch.int32, device=G.DEV)
+    y = F.floe_moe_layer_decode_cached(L, cache, M, G.dev(x), stats=stats, cache_stats=cstats)
+    torch.cuda.synchronize()
+    assert torch.equal(y, y_off), "cached decode differs from the offloaded decode"
+    for t in range(T):
+        assert G.rel_err(y[t].cpu().numpy().astype(np.float64), ref["y"][t]) <= G.Y_TIGHT
+    st = stats.cpu().numpy().reshape(T, slots, 4).copy().view(F.SLOT_STAT_DTYPE).reshape(T, slots)
+    cs = cstats.cpu().numpy().view(F.PREFETCH_STAT_DTYPE).reshape(T, slots)
+    pool_after = cache.pool.cpu().numpy()
+    for t in range(T):
+        for s_ in range(slots):
+            e = int(ref["ids"][t, s_])
+            v = O.up_gemv(*experts_np[e][:3], d, bits, group, x[t])
+            sel = O.select(v, float(tau[t, e]))
+            miss = np.setdiff1d(sel, resident[e])
+            assert st[t, s_]["expert"] == e and st[t, s_]["count"] == sel.size
+            assert st[t, s_]["staged"] == miss.size == cs[t, s_]["misses"]
+            assert cs[t, s_]["hits"] == sel.size - miss.size
+            # the misses sit, in ascending channel order, at the start of the task's slab, as byte copies
+            q = t * slots + s_
+            slab0 = cache.resident_rows + q * cap
+            assert pool_after[slab0:slab0 + miss.size].tobytes() == experts_np[e][3][miss].tobytes()
+    assert M.overflow.cpu().numpy().tolist() == [0] * (T * slots)
+
+    # a slab that is too small: the channels without a row are left out and the task is flagged
+    small = F.ChannelCache(L, T, 8, 4)
+    M2 = F.MissPath(torch.cuda.Stream(), T * slots, G.DEV)
+    F.floe_moe_layer_decode_cached(L, small, M2, G.dev(x))
+    torch.cuda.synchronize()
+    assert M2.overflow.cpu().numpy().tolist() == [1] * (T * slots)

@@ -311,11 +311,12 @@ def test_layer_decode_replayed_from_a_hip_graph_matches_eager(T):
             _ = (y_static.float() * 2).sum().item()          # eager work between replays
 
 
-def test_offloaded_layer_matches_resident_layer_and_oracle():
+@pytest.mark.parametrize("d,f", [(1024, 2048), (4096, 1600)])    # the second: the chunk size of the Mixtral-shaped stack
+def test_offloaded_layer_matches_resident_layer_and_oracle(d, f):
     """Gate/down matrices in pinned host memory, selected chunks staged on a side stream (Sec. 3.4.2)."""
     import gpu_common as G
     import paper_2505_05950_amd as F
-    d, f, bits, group, n, top_k, T, pct = 1024, 2048, 2, 64, 4, 2, 2, 80
+    bits, group, n, top_k, T, pct = 2, 64, 4, 2, 2, 80
     experts = [G.make_expert(*S.expert_weights(16, 4, d, f, 0, e), bits, group) for e in range(n)]
     experts_np = [e[0] for e in experts]
     wr = S.router_weights(16, 4, n, d)
