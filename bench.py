@@ -91,6 +91,9 @@ def main():
     ap.add_argument("--batch-cases", default="", help="batch workload only: cases to run as config:T,... "
                                                       "(e.g. 2:16,4:32; empty = all)")
     ap.add_argument("--union-kernels", type=int, default=0, help="floe_tuning(FLOE_TUNE_UNION_KERNELS): 0 = library default")
+    ap.add_argument("--stack-parts", default="plain,budget,cache,prefetch",
+                    help="stack workload only: which measurements to run (a short list makes a short profile)")
+    ap.add_argument("--copy-workgroups", type=int, default=0, help="floe_tuning(FLOE_TUNE_STAGE_WORKGROUPS): 0 = library default")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0)
     args = ap.parse_args()
@@ -109,6 +112,8 @@ def main():
     FL.load()
     if args.union_kernels:
         FL.floe_tuning(FL.TUNE_UNION_KERNELS, args.union_kernels)
+    if args.copy_workgroups:
+        FL.floe_tuning(FL.TUNE_STAGE_WORKGROUPS, args.copy_workgroups)
     K, W, R = args.steps, args.warmup, max(1, args.copies)
     if args.workload == "expert":
         return bench_expert(args, np, torch, S, FL, dev)
@@ -711,9 +716,10 @@ def bench_stack(args, np, torch, S, FL, dev):
                 staged.append(int(np.minimum(ks, cap).sum()) * 4 * D)
         return float(np.median(lat)) * 1e3, float(np.mean(staged)), ovf   # median: a token that touches host pages for the first time pays for it once
 
-    ms, nbytes, ovf = run(0)
+    parts = set(args.stack_parts.split(","))
+    ms, nbytes, ovf = run(0) if "plain" in parts else (float("nan"), 0.0, 0)
     sweep = []
-    for budget in (12, 16, 20, 24, 32, 48, 66):
+    for budget in (12, 16, 20, 24, 32, 48, 66) if "budget" in parts else ():
         n_res = int(max(0, min(n_layers, (budget - fixed_gb) // layer_gb)))
         b_ms, b_bytes, _ = run(n_res)
         sweep.append({"vram_budget_GB": budget, "resident_layers": n_res, "ms_per_token": round(b_ms, 3),
@@ -729,7 +735,7 @@ def bench_stack(args, np, torch, S, FL, dev):
     M_cache = FL.MissPath(torch.cuda.Stream(), TOP_K, dev)
     cstats = torch.zeros((n_layers, TOP_K, 4), dtype=torch.int32, device=dev)
     cache_sweep = []
-    for budget in (12, 16, 20, 24, 32, 48):
+    for budget in (12, 16, 20, 24, 32, 48) if "cache" in parts else ():
         share = max(0.0, min(1.0, (budget - fixed_gb) / (n_layers * layer_gb)))
         r_per = int(share * F_INT)
         caches = []
@@ -774,12 +780,9 @@ def bench_stack(args, np, torch, S, FL, dev):
     M = FL.MissPath(miss_stream, TOP_K, dev)
     ws_pre = layers[0].new_workspace(1)
     pstats = torch.zeros((n_layers, TOP_K, 4), dtype=torch.int32, device=dev)
-    prefetch_rows = []
-    first = True
-    for beta in (0.33, 0.2):
+    def run_prefetch(beta, extra):
         lat, cosines, agg = [], [], np.zeros(5)
-        extra = 4 if first else 0          # the first pass also warms the spare slabs and both streams
-        first = False
+        all_rows = torch.zeros((), dtype=torch.int64, device=dev)      # every row the prefetches copied, used or not
         for i in range(-extra, n_tok + n_warm):
             i = max(i, 0)
             x = toks[i:i + 1].contiguous()
@@ -791,6 +794,8 @@ def bench_stack(args, np, torch, S, FL, dev):
                     FL.floe_moe_layer_prefetch(layers[l + 1], P2[(l + 1) % 2], x, ws_pre)
                 FL.floe_moe_layer_decode_prefetched(layers[l], P2[l % 2], M, x, y=y, stats=stats[l],
                                                     prefetch_stats=pstats[l], workspace=ws)
+                if i >= n_warm:
+                    all_rows += P2[l % 2].pred_count.clamp(max=cap).sum()
                 xf, yf = x.float(), y.float()
                 xn = xf + beta * yf / yf.std()
                 xn = xn / xn.std()
@@ -803,15 +808,37 @@ def bench_stack(args, np, torch, S, FL, dev):
                 ps = pstats.cpu().numpy().reshape(n_layers, TOP_K, 4)[1:]        # layer 0 is predicted from its own input
                 agg += np.array([ps[..., 0].sum(), ps[..., 1].sum(), ps[..., 2].sum(), ps[..., 3].sum(), ps[..., 0].size])
         hits, misses, predicted = agg[2], agg[3], agg[1]
+        copied = (float(all_rows.item()) + misses) / n_tok * 4 * D
         row = {"beta": beta, "cosine_similarity": round(float(torch.stack(cosines).mean().item()), 4),
                "expert_prediction_rate": round(float(agg[0] / agg[4]), 4),
                "channel_recall": round(float(hits / max(hits + misses, 1)), 4),
                "channel_precision": round(float(hits / max(predicted, 1)), 4),
                "ms_per_token": round(float(np.median(lat)) * 1e3, 3),
-               "prefetched_MB_per_token": round(float(predicted) / n_tok * 4 * D / 1e6, 1),
-               "missed_MB_per_token": round(float(misses) / n_tok * 4 * D / 1e6, 1)}
+               "prefetched_MB_per_token": round(float(all_rows.item()) / n_tok * 4 * D / 1e6, 1),
+               "prefetched_for_the_right_expert_MB_per_token": round(float(predicted) / n_tok * 4 * D / 1e6, 1),
+               "missed_MB_per_token": round(float(misses) / n_tok * 4 * D / 1e6, 1),
+               "copied_MB_per_token": round(float(copied) / 1e6, 1),
+               "link_GBps": round(float(copied) / float(np.median(lat)) / 1e9, 2)}
+        return row, lat
+
+    prefetch_rows = []
+    first = True
+    for beta in (0.33, 0.2) if "prefetch" in parts else ():
+        row, lat = run_prefetch(beta, 4 if first else 0)    # the first pass also warms the spare slabs and both streams
+        first = False
         prefetch_rows.append(row)
         log(f"[bench] prefetch: {row} per-token ms {[round(v * 1e3, 1) for v in lat]}")
+    # ---- how many copy workgroups: host reads in flight beyond what the link needs delay the HBM reads of the kernels
+    # that run beside the copy (the up GEMV of the layer being decoded while the next layer is prefetched)
+    wg_sweep = []
+    for wgs in (256, 128, 64, 32, 16, 8) if "copywgs" in parts else ():
+        FL.floe_tuning(FL.TUNE_STAGE_WORKGROUPS, wgs)
+        p_ms, _, _ = run(0)
+        row, _ = run_prefetch(0.33, 4 if first else 0)
+        first = False
+        wg_sweep.append({"copy_workgroups": wgs, "plain_ms_per_token": round(p_ms, 3), "prefetch_ms_per_token": row["ms_per_token"]})
+        log(f"[bench] copy workgroups {wgs}: plain {p_ms:.2f} ms/token, prefetched (beta 0.33) {row['ms_per_token']:.2f} ms/token")
+    FL.floe_tuning(FL.TUNE_STAGE_WORKGROUPS, 0)
 
     # plain pinned copy of the same volume for reference
     flat = pinned[0][0].view(-1)
@@ -832,7 +859,7 @@ def bench_stack(args, np, torch, S, FL, dev):
                       "pinned_memcpy_GBps": round(peak, 2), "tokens_per_s": round(1e3 / ms, 2),
                       "resident_hbm_GB": round(fixed_gb, 2),
                       "vram_budget_sweep": sweep, "resident_channel_cache_sweep": cache_sweep,
-                      "prefetch_next_layer": prefetch_rows}), flush=True)
+                      "prefetch_next_layer": prefetch_rows, "copy_workgroups_sweep": wg_sweep}), flush=True)
 
 
 def bench_batch(args, np, torch, S, FL, dev):

@@ -94,10 +94,14 @@ int floe_profile_kernel(int kernel_id, void* start_event, void* stop_event);
  *                                projections on the matrix cores (dense token x row tiles);
  *                            2 = per expert group, the union of the selected rows read once into a ring in LDS, one
  *                                wave per token.
- * Process-wide.  Workspace sizes depend on it: do not change it between a *_workspace_bytes query and the decode
+ *   FLOE_TUNE_STAGE_WORKGROUPS  workgroups (of four waves, four 16-byte reads in flight per lane) of the kernels that
+ *                            copy selected chunks out of pinned host memory; 0 = the library's default, at most 4096.
+ *                            More workgroups than the link needs keep more host reads in flight, and these delay the
+ *                            HBM reads of kernels that run beside the copy.
+ * Process-wide.  Workspace sizes depend on FLOE_TUNE_UNION_KERNELS: do not change it between a *_workspace_bytes query and the decode
  * call that uses the workspace.  Unknown key or value: FLOE_EINVAL.
  */
-typedef enum { FLOE_TUNE_UNION_KERNELS = 1 } floe_tuning_key;
+typedef enum { FLOE_TUNE_UNION_KERNELS = 1, FLOE_TUNE_STAGE_WORKGROUPS = 2 } floe_tuning_key;
 int floe_tuning(int key, int value);
 
 /* ------------------------------------------------------------------------------------------------

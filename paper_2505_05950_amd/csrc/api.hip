@@ -114,7 +114,7 @@ bool mask_path_ok(int f) { return mask_words_per_task(f) <= 2048; }
 
 // workspace of the layer: per-task table, counts, mask words, v, idx, partial
 struct LayerWs {
-    size_t table_off, expert_off, weight_off, tau_off, count_off, mask_off, groups_off, ngroups_off, order_off, v_off, idx_off,
+    size_t table_off, expert_off, weight_off, tau_off, logit_off, count_off, mask_off, groups_off, ngroups_off, order_off, v_off, idx_off,
         rows_off, missidx_off, missrows_off, misscount_off, urow_off, ucount_off, hbuf_off, partial_off, total;
     int n_tasks, nblk, nblk_fused, fused_passes;
     bool batch_mfma;  // tokens of an expert share one pass over its codes (matrix-core up GEMV)
@@ -144,6 +144,7 @@ LayerWs layer_ws(const floe_layer* L, int T) {
     w.expert_off = o; o += align_up((size_t)w.n_tasks * 4);
     w.weight_off = o; o += align_up((size_t)w.n_tasks * 4);
     w.tau_off = o;    o += align_up((size_t)w.n_tasks * 4);
+    w.logit_off = o;  o += router_split_pays(L->n_experts, L->s.d, T) ? align_up((size_t)T * L->n_experts * 4) : 0;
     w.count_off = o;  o += align_up((size_t)w.n_tasks * count_parts * 4);
     w.mask_off = o;   o += align_up((size_t)w.n_tasks * mask_words_per_task(L->s.f) * 4);
     w.groups_off = o; o += align_up((size_t)mfma_max_groups(L->n_experts + L->n_shared, w.n_tasks) * sizeof(TokenGroup));
@@ -180,6 +181,24 @@ int check_layer(const floe_layer* L) {
     return FLOE_OK;
 }
 
+// arguments of the stand-alone router: it fills the per-task arrays at the head of the workspace
+RouterArgs router_args(const floe_layer* L, const LayerWs& w, char* base, const h16* xh) {
+    RouterArgs ra;
+    ra.router_cm = reinterpret_cast<const h16*>(L->router_cm);
+    ra.x = xh;
+    ra.tau = L->tau;
+    ra.tau_stride_t = L->tau_stride_t;
+    ra.n_experts = L->n_experts; ra.top_k = L->top_k; ra.n_shared = L->n_shared; ra.renormalize = L->renormalize;
+    ra.d = L->s.d;
+    ra.table = static_cast<const DevExpert*>(L->dev_table);
+    ra.task_table = reinterpret_cast<DevExpert*>(base + w.table_off);
+    ra.task_expert = reinterpret_cast<int32_t*>(base + w.expert_off);
+    ra.task_weight = reinterpret_cast<float*>(base + w.weight_off);
+    ra.task_tau = reinterpret_cast<float*>(base + w.tau_off);
+    ra.logits = w.logit_off != w.count_off ? reinterpret_cast<float*>(base + w.logit_off) : nullptr;
+    return ra;
+}
+
 // S1-S3 of a layer as separate results in the workspace (offloaded paths need the index lists in memory):
 // task table / expert / weight / tau, v, idx, count.
 int layer_lists(const floe_layer* L, const LayerWs& w, char* base, const h16* xh, int T, hipStream_t st) {
@@ -206,16 +225,7 @@ int layer_lists(const floe_layer* L, const LayerWs& w, char* base, const h16* xh
                     launch_up_gemv(map, xh, &ro, v, nullptr, nullptr, L->s.d, L->s.f, L->s.bits, L->s.group,
                                    w.n_tasks, st));
     } else {
-        RouterArgs ra;
-        ra.router_cm = reinterpret_cast<const h16*>(L->router_cm);
-        ra.x = xh;
-        ra.tau = L->tau;
-        ra.tau_stride_t = L->tau_stride_t;
-        ra.n_experts = L->n_experts; ra.top_k = L->top_k; ra.n_shared = L->n_shared; ra.renormalize = L->renormalize;
-        ra.d = L->s.d;
-        ra.table = static_cast<const DevExpert*>(L->dev_table);
-        ra.task_table = task_table;
-        ra.task_expert = task_expert; ra.task_weight = task_weight; ra.task_tau = task_tau;
+        const RouterArgs ra = router_args(L, w, base, xh);
         FLOE_LAUNCH(FLOE_KERNEL_ROUTER, st, launch_router(ra, T, st));
         FLOE_LAUNCH(FLOE_KERNEL_UP_GEMV, st,
                     launch_up_gemv(map, xh, nullptr, v, nullptr, nullptr, L->s.d, L->s.f, L->s.bits, L->s.group,
@@ -258,6 +268,10 @@ int floe_tuning(int key, int value) {
         case FLOE_TUNE_UNION_KERNELS:
             if (value < 0 || value > 2) return FLOE_EINVAL;
             set_union_mode(value);
+            return FLOE_OK;
+        case FLOE_TUNE_STAGE_WORKGROUPS:
+            if (value < 0 || value > 4096) return FLOE_EINVAL;
+            set_stage_workgroups(value);
             return FLOE_OK;
         default: return FLOE_EINVAL;
     }
@@ -537,16 +551,7 @@ int floe_moe_layer_decode(const floe_layer* L, const floe_half* x, int T, floe_h
         ro.task_table = task_table;
         ro.task_expert = task_expert; ro.task_weight = task_weight; ro.task_tau = task_tau;
         if (!in_place) {
-            RouterArgs ra;
-            ra.router_cm = ro.router_cm;
-            ra.x = xh;
-            ra.tau = L->tau;
-            ra.tau_stride_t = L->tau_stride_t;
-            ra.n_experts = L->n_experts; ra.top_k = L->top_k; ra.n_shared = L->n_shared; ra.renormalize = L->renormalize;
-            ra.d = L->s.d;
-            ra.table = ro.table;
-            ra.task_table = task_table;
-            ra.task_expert = task_expert; ra.task_weight = task_weight; ra.task_tau = task_tau;
+            const RouterArgs ra = router_args(L, w, base, xh);
             FLOE_LAUNCH(FLOE_KERNEL_ROUTER, st, launch_router(ra, T, st));
         }
         FusedArgs a{};
@@ -559,16 +564,7 @@ int floe_moe_layer_decode(const floe_layer* L, const floe_half* x, int T, floe_h
     } else if (w.use_union) {
         // decode batch: [router] -> [token groups per expert] -> [up GEMV + mask bits] -> [gate on the union of the
         // group's rows] -> [down]; every selected row is read once per expert group
-        RouterArgs ra;
-        ra.router_cm = reinterpret_cast<const h16*>(L->router_cm);
-        ra.x = xh;
-        ra.tau = L->tau;
-        ra.tau_stride_t = L->tau_stride_t;
-        ra.n_experts = L->n_experts; ra.top_k = L->top_k; ra.n_shared = L->n_shared; ra.renormalize = L->renormalize;
-        ra.d = L->s.d;
-        ra.table = static_cast<const DevExpert*>(L->dev_table);
-        ra.task_table = task_table;
-        ra.task_expert = task_expert; ra.task_weight = task_weight; ra.task_tau = task_tau;
+        const RouterArgs ra = router_args(L, w, base, xh);
         FLOE_LAUNCH(FLOE_KERNEL_ROUTER, st, launch_router(ra, T, st));
         TokenGroup* groups = reinterpret_cast<TokenGroup*>(base + w.groups_off);
         int32_t* n_groups = reinterpret_cast<int32_t*>(base + w.ngroups_off);
@@ -613,16 +609,7 @@ int floe_moe_layer_decode(const floe_layer* L, const floe_half* x, int T, floe_h
                     launch_gate_down(map, nullptr, L->s.f, xh, v, mask, nullptr, count, task_weight, partial, L->s.d, L->s.f,
                                      w.n_tasks, w.nblk, st));
     } else {
-        RouterArgs ra;
-        ra.router_cm = reinterpret_cast<const h16*>(L->router_cm);
-        ra.x = xh;
-        ra.tau = L->tau;
-        ra.tau_stride_t = L->tau_stride_t;
-        ra.n_experts = L->n_experts; ra.top_k = L->top_k; ra.n_shared = L->n_shared; ra.renormalize = L->renormalize;
-        ra.d = L->s.d;
-        ra.table = static_cast<const DevExpert*>(L->dev_table);
-        ra.task_table = task_table;
-        ra.task_expert = task_expert; ra.task_weight = task_weight; ra.task_tau = task_tau;
+        const RouterArgs ra = router_args(L, w, base, xh);
         FLOE_LAUNCH(FLOE_KERNEL_ROUTER, st, launch_router(ra, T, st));
         // batches: the gate/down workgroups are launched in expert order (tasks that share an expert run side by side
         // and share its rows in the L2)

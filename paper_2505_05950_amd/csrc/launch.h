@@ -107,6 +107,9 @@ struct UnionPlan {
     int max_groups;
     bool matrix_cores, fused;  // which kernels run (union_mode)
 };
+constexpr int kStageWorkgroupsDefault = 32;  // 128 waves x 4 KiB in flight: the link is full, a GEMV beside it keeps most of its speed
+int stage_workgroups();
+void set_stage_workgroups(int n);  // 0 = default
 int union_mode();
 void set_union_mode(int m);
 struct UnionArgs {
@@ -152,7 +155,12 @@ struct RouterArgs {
     int32_t* task_expert;     // [n_tasks] out
     float* task_weight;       // [n_tasks] out
     float* task_tau;          // [n_tasks] out
+    float* logits;            // [T][n_experts] scratch of the two-launch form; nullptr = one launch always
 };
+// the router matrix of a token is worth spreading over several workgroups from this size on (two launches then)
+inline bool router_split_pays(int n_experts, int d, int T) {
+    return (size_t)n_experts * d * 2 >= (size_t)128 * 1024 && n_experts >= 32 && T <= 4096;
+}
 hipError_t launch_router(const RouterArgs& a, int T, hipStream_t stream);
 
 // stats: (expert, count, weight) per task

@@ -1,7 +1,8 @@
 // S1: router (the paper only says that a router picks the activated experts of each MoE layer, Sec. 3.3;
 // the arithmetic is the usual softmax-top-k of the models it evaluates): logits = x . W_r, softmax with the
 // maximum subtracted, top_k by probability with ties to the lower expert id, optional renormalisation.
-// One workgroup per token writes the task table the later kernels index: task q = token * slots + slot,
+// One workgroup per token (or, for many experts, two launches: see router_logits_kernel) writes the task table the
+// later kernels index: task q = token * slots + slot,
 // slots 0..top_k-1 routed (descending probability), then the n_shared always-on experts with weight 1.
 #include "floe_dev.h"
 #include "launch.h"
@@ -60,59 +61,39 @@ __device__ __forceinline__ void route_select_wave64(float logit, int lane, int n
     }
 }
 
-// One workgroup of 16 waves per token.  A wave takes experts wave, wave + 16, ... and keeps kInFlight rows in flight
-// at a time (all 16-byte pieces of a row and of x requested before the packed dot products run), so a layer with
-// 64 experts of d <= 2048 costs one round trip to memory, not sixteen.  NV = d / 512 pieces per lane.
-template <int NV>
-__global__ __launch_bounds__(1024) void router_kernel(RouterArgs a) {
-    constexpr int kInFlight = NV <= 4 ? 4 : (NV <= 8 ? 2 : 1);
-    __shared__ float prob[kMaxExperts];
-    __shared__ int sel_id[64];
-    __shared__ float sel_w[64];
-    __shared__ DevExpert tab[kMaxExperts + 64];
-    __shared__ float taus[kMaxExperts + 64];
-    const int t = blockIdx.x;
-    const int tid = threadIdx.x;
-    const int wave = tid >> 6, lane = tid & 63;
+// logit of expert e for the token whose x pieces the lanes hold, for up to Q experts at a time: all 16-byte pieces of
+// the Q rows are requested before the packed dot products run.  Every lane returns the full sums.
+template <int NV, int Q>
+__device__ __forceinline__ void router_logits(const h16* __restrict__ router_cm, const uint4 (&xv)[NV], int lane,
+                                              const int (&e)[Q], float (&out)[Q]) {
     constexpr int d = NV * 512;
-    const int slots = a.top_k + a.n_shared;
-    const h16* xt = a.x + (size_t)t * d;
-    // every expert's table entry and threshold travel beside the router rows, so that resolving the picks costs
-    // no further round trip to memory
-    for (int e = tid; e < a.n_experts + a.n_shared; e += 1024) {
-        tab[e] = a.table[e];
-        taus[e] = a.tau[(size_t)t * a.tau_stride_t + e];
+    uint4 w[Q][NV];
+#pragma unroll
+    for (int q = 0; q < Q; ++q) {
+        const uint4* wp = reinterpret_cast<const uint4*>(router_cm + (size_t)e[q] * d);
+#pragma unroll
+        for (int r = 0; r < NV; ++r) w[q][r] = wp[r * kWave + lane];
     }
-    if (a.top_k > 0) {
-        uint4 xv[NV];
-        const uint4* xp = reinterpret_cast<const uint4*>(xt);
 #pragma unroll
-        for (int r = 0; r < NV; ++r) xv[r] = xp[r * kWave + lane];
-        for (int e0 = wave; e0 < a.n_experts; e0 += 16 * kInFlight) {
-            uint4 w[kInFlight][NV];
+    for (int q = 0; q < Q; ++q) {
+        float acc = 0.0f;
 #pragma unroll
-            for (int q = 0; q < kInFlight; ++q) {
-                const int e = e0 + 16 * q < a.n_experts ? e0 + 16 * q : e0;
-                const uint4* wp = reinterpret_cast<const uint4*>(a.router_cm + (size_t)e * d);
-#pragma unroll
-                for (int r = 0; r < NV; ++r) w[q][r] = wp[r * kWave + lane];
-            }
-#pragma unroll
-            for (int q = 0; q < kInFlight; ++q) {
-                float acc = 0.0f;
-#pragma unroll
-                for (int r = 0; r < NV; ++r) {
-                    acc = dot2(xv[r].x, w[q][r].x, acc);
-                    acc = dot2(xv[r].y, w[q][r].y, acc);
-                    acc = dot2(xv[r].z, w[q][r].z, acc);
-                    acc = dot2(xv[r].w, w[q][r].w, acc);
-                }
-                acc = wave_allreduce_sum(acc);
-                if (lane == 0 && e0 + 16 * q < a.n_experts) prob[e0 + 16 * q] = acc;
-            }
+        for (int r = 0; r < NV; ++r) {
+            acc = dot2(xv[r].x, w[q][r].x, acc);
+            acc = dot2(xv[r].y, w[q][r].y, acc);
+            acc = dot2(xv[r].z, w[q][r].z, acc);
+            acc = dot2(xv[r].w, w[q][r].w, acc);
         }
+        out[q] = wave_allreduce_sum(acc);
     }
-    __syncthreads();
+}
+
+// softmax + top-k over prob[0, n_experts) and the task table of token t; called by all threads of a workgroup
+// (at least 64) after the logits are in LDS.  tab / taus: LDS copies of every expert's table entry and threshold.
+__device__ __forceinline__ void router_pick_and_write(const RouterArgs& a, int t, const float* prob, int* sel_id,
+                                                      float* sel_w, const DevExpert* tab, const float* taus) {
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int slots = a.top_k + a.n_shared;
     if (a.n_experts <= 64) {
         if (wave == 0) {
             if (a.top_k > 0)
@@ -124,7 +105,7 @@ __global__ __launch_bounds__(1024) void router_kernel(RouterArgs a) {
             }
         }
     } else if (tid == 0) {
-        route_select(prob, a.n_experts, a.top_k, a.n_shared, a.renormalize, sel_id, sel_w);
+        route_select(const_cast<float*>(prob), a.n_experts, a.top_k, a.n_shared, a.renormalize, sel_id, sel_w);
     }
     __syncthreads();
     // one thread per slot resolves the expert: its pointers, weight and threshold go to the task table
@@ -138,10 +119,110 @@ __global__ __launch_bounds__(1024) void router_kernel(RouterArgs a) {
     }
 }
 
+// One workgroup of 16 waves per token.  A wave takes experts wave, wave + 16, ... and keeps kInFlight rows in flight
+// at a time, so a layer with 64 experts of d <= 2048 costs one round trip to memory, not sixteen.  NV = d / 512
+// pieces per lane.
+template <int NV>
+__global__ __launch_bounds__(1024) void router_kernel(RouterArgs a) {
+    constexpr int kInFlight = NV <= 4 ? 4 : (NV <= 8 ? 2 : 1);
+    __shared__ float prob[kMaxExperts];
+    __shared__ int sel_id[64];
+    __shared__ float sel_w[64];
+    __shared__ DevExpert tab[kMaxExperts + 64];
+    __shared__ float taus[kMaxExperts + 64];
+    const int t = blockIdx.x;
+    const int tid = threadIdx.x;
+    const int wave = tid >> 6, lane = tid & 63;
+    constexpr int d = NV * 512;
+    const h16* xt = a.x + (size_t)t * d;
+    // every expert's table entry and threshold travel beside the router rows, so that resolving the picks costs
+    // no further round trip to memory
+    for (int e = tid; e < a.n_experts + a.n_shared; e += 1024) {
+        tab[e] = a.table[e];
+        taus[e] = a.tau[(size_t)t * a.tau_stride_t + e];
+    }
+    if (a.top_k > 0) {
+        uint4 xv[NV];
+        const uint4* xp = reinterpret_cast<const uint4*>(xt);
+#pragma unroll
+        for (int r = 0; r < NV; ++r) xv[r] = xp[r * kWave + lane];
+        for (int e0 = wave; e0 < a.n_experts; e0 += 16 * kInFlight) {
+            int e[kInFlight];
+            float acc[kInFlight];
+#pragma unroll
+            for (int q = 0; q < kInFlight; ++q) e[q] = e0 + 16 * q < a.n_experts ? e0 + 16 * q : e0;
+            router_logits<NV, kInFlight>(a.router_cm, xv, lane, e, acc);
+#pragma unroll
+            for (int q = 0; q < kInFlight; ++q)
+                if (lane == 0 && e0 + 16 * q < a.n_experts) prob[e0 + 16 * q] = acc[q];
+        }
+    }
+    __syncthreads();
+    router_pick_and_write(a, t, prob, sel_id, sel_w, tab, taus);
+}
+
+// The same routing in two launches, for layers with many experts: one compute unit cannot pull a router matrix of a
+// few hundred KB as fast as sixteen can.  The first kernel spreads the logits of a token over gridDim.x workgroups of
+// four waves (a wave per expert at a time) and leaves them in a.logits[t][e]; the second picks.  The sums are formed
+// exactly as in router_kernel, so both ways give the same bits.
+template <int NV>
+__global__ __launch_bounds__(256) void router_logits_kernel(RouterArgs a) {
+    constexpr int d = NV * 512;
+    constexpr int Q = NV <= 4 ? 2 : 1;
+    const int t = blockIdx.y;
+    const int lane = threadIdx.x & 63;
+    const int gw = blockIdx.x * 4 + (threadIdx.x >> 6), nw = gridDim.x * 4;
+    uint4 xv[NV];
+    const uint4* xp = reinterpret_cast<const uint4*>(a.x + (size_t)t * d);
+#pragma unroll
+    for (int r = 0; r < NV; ++r) xv[r] = xp[r * kWave + lane];
+    for (int e0 = gw; e0 < a.n_experts; e0 += nw * Q) {
+        int e[Q];
+        float acc[Q];
+#pragma unroll
+        for (int q = 0; q < Q; ++q) e[q] = e0 + nw * q < a.n_experts ? e0 + nw * q : e0;
+        router_logits<NV, Q>(a.router_cm, xv, lane, e, acc);
+#pragma unroll
+        for (int q = 0; q < Q; ++q)
+            if (lane == 0 && e0 + nw * q < a.n_experts) a.logits[(size_t)t * a.n_experts + e0 + nw * q] = acc[q];
+    }
+}
+
+__global__ __launch_bounds__(256) void router_pick_kernel(RouterArgs a) {
+    __shared__ float prob[kMaxExperts];
+    __shared__ int sel_id[64];
+    __shared__ float sel_w[64];
+    __shared__ DevExpert tab[kMaxExperts + 64];
+    __shared__ float taus[kMaxExperts + 64];
+    const int t = blockIdx.x;
+    const int tid = threadIdx.x;
+    for (int e = tid; e < a.n_experts + a.n_shared; e += 256) {
+        tab[e] = a.table[e];
+        taus[e] = a.tau[(size_t)t * a.tau_stride_t + e];
+        if (e < a.n_experts) prob[e] = a.logits[(size_t)t * a.n_experts + e];
+    }
+    __syncthreads();
+    router_pick_and_write(a, t, prob, sel_id, sel_w, tab, taus);
+}
+
 hipError_t launch_router(const RouterArgs& a, int T, hipStream_t stream) {
     if (T == 0) return hipSuccess;
-#define FLOE_ROUTER_NV(N) \
-    case N: router_kernel<N><<<dim3(T), dim3(1024), 0, stream>>>(a); break;
+    const bool split = a.logits != nullptr && a.top_k > 0 && router_split_pays(a.n_experts, a.d, T);
+    // workgroups per token of the split: every wave gets at least one expert, the launch about two waves of workgroups
+    int per_token = (a.n_experts + 3) / 4;
+    if (split) {
+        const int room = 2 * num_cus() / T;
+        per_token = per_token < room ? per_token : (room < 1 ? 1 : room);
+    }
+#define FLOE_ROUTER_NV(N)                                                                      \
+    case N:                                                                                    \
+        if (split) {                                                                           \
+            router_logits_kernel<N><<<dim3(per_token, T), dim3(256), 0, stream>>>(a);          \
+            router_pick_kernel<<<dim3(T), dim3(256), 0, stream>>>(a);                          \
+        } else {                                                                               \
+            router_kernel<N><<<dim3(T), dim3(1024), 0, stream>>>(a);                           \
+        }                                                                                      \
+        break;
     switch (a.d / 512) {
         FLOE_ROUTER_NV(1) FLOE_ROUTER_NV(2) FLOE_ROUTER_NV(3) FLOE_ROUTER_NV(4) FLOE_ROUTER_NV(5) FLOE_ROUTER_NV(6)
         FLOE_ROUTER_NV(7) FLOE_ROUTER_NV(8) FLOE_ROUTER_NV(9) FLOE_ROUTER_NV(10) FLOE_ROUTER_NV(11) FLOE_ROUTER_NV(12)

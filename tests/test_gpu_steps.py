@@ -336,3 +336,31 @@ def test_staged_rows_feed_gate_down():
     assert K <= cap
     y_ref = O.sparse_ffn(ex_np[3], x[0], v.cpu().numpy()[0], got_idx)[1]
     assert G.rel_err(y.cpu().numpy()[0].astype(np.float64), y_ref) <= 2e-4
+
+
+# ------------------------------------------------------------------------------------------- staged code ring
+@pytest.mark.parametrize("f,group,T", [(1, 64, 1), (27, 64, 1), (112, 64, 2), (113, 128, 1), (250, 256, 3), (341, 64, 1),
+                                       (28 * 4 * 3 + 5, 64, 2), (2000, 64, 1), (14336, 64, 1)])
+def test_fused_kernel_codes_through_the_lds_ring_match_the_register_path(f, group, T):
+    """The INT2 producers of the fused kernel fetch their codes through a ring in LDS that is read back behind
+    hand-counted waits (three memory requests per pass, in source order).  Should a compiler ever change that count,
+    a pass would read the previous occupant of its slot: v would differ.  This compares the fused kernel's v (it stores
+    v when the caller asks for the index list) with the GEMV kernel that keeps the codes in registers, bit for bit: both
+    form every channel's sum in the same order.  Shapes: one channel, less than one pass per producer, exactly one block,
+    one more, ragged last blocks, every block length (28 / 14 / 7 passes) and the full Mixtral width."""
+    G = _gc()
+    import paper_2505_05950_amd as F
+    d, bits = 4096, 2
+    w_up, gd = S.expert_weights(80, 2, d, f)
+    ex_np, ex_dev = G.make_expert(w_up, gd, bits, group)
+    x = G.dev(S.tokens(80, 2, T, d))
+    v_ref = F.floe_up_gemv(ex_dev.up_codes, ex_dev.up_scale, ex_dev.up_zero, x, d, bits, group)
+    tau = torch.full((T,), 0.5, dtype=torch.float32, device=G.DEV)
+    y = torch.zeros((T, d), dtype=torch.float32, device=G.DEV)
+    nbytes = F.floe_expert_workspace_bytes(d, f, bits, group, T)
+    ws = torch.zeros((nbytes + 512,), dtype=torch.uint8, device=G.DEV)
+    F.floe_expert_ffn_sparse(ex_dev, x, tau, None, y, workspace=ws)          # with the list: the fused kernel stores v
+    torch.cuda.synchronize()
+    off = (-ws.data_ptr()) % 256
+    v_fused = ws[off: off + T * f * 4].view(torch.float32).reshape(T, f)     # v is the first array of the workspace
+    assert torch.equal(v_fused, v_ref), (v_fused - v_ref).abs().max().item()
