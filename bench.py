@@ -93,6 +93,7 @@ def main():
     ap.add_argument("--union-kernels", type=int, default=0, help="floe_tuning(FLOE_TUNE_UNION_KERNELS): 0 = library default")
     ap.add_argument("--stack-parts", default="plain,budget,cache,prefetch",
                     help="stack workload only: which measurements to run (a short list makes a short profile)")
+    ap.add_argument("--grouped-gemv", type=int, default=0, help="floe_tuning(FLOE_TUNE_GROUPED_GEMV): 0 = library default")
     ap.add_argument("--copy-workgroups", type=int, default=0, help="floe_tuning(FLOE_TUNE_STAGE_WORKGROUPS): 0 = library default")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0)
@@ -112,6 +113,8 @@ def main():
     FL.load()
     if args.union_kernels:
         FL.floe_tuning(FL.TUNE_UNION_KERNELS, args.union_kernels)
+    if args.grouped_gemv:
+        FL.floe_tuning(FL.TUNE_GROUPED_GEMV, args.grouped_gemv)
     if args.copy_workgroups:
         FL.floe_tuning(FL.TUNE_STAGE_WORKGROUPS, args.copy_workgroups)
     K, W, R = args.steps, args.warmup, max(1, args.copies)
@@ -888,7 +891,7 @@ def bench_batch(args, np, torch, S, FL, dev):
     stream = torch.cuda.Stream()
     for name, cfg, d, f, bits, group, n, n_shared, top_k, renorm, pct, Ts in (
             ("configs[2]", 3, 4096, 14336, 2, 64, 8, 0, 2, True, 90, (1, 4, 16, 64)),
-            ("configs[4]", 5, 2048, 1408, 3, 32, 64, 2, 6, False, 85, (1, 8, 32))):
+            ("configs[4]", 5, 2048, 1408, 3, 32, 64, 2, 6, False, 85, (1, 8, 32, 128))):
         want = [c.split(":") for c in args.batch_cases.split(",") if c]
         Ts = [T for T in Ts if not want or [name[8], str(T)] in want]
         if not Ts:

@@ -98,10 +98,14 @@ int floe_profile_kernel(int kernel_id, void* start_event, void* stop_event);
  *                            copy selected chunks out of pinned host memory; 0 = the library's default, at most 4096.
  *                            More workgroups than the link needs keep more host reads in flight, and these delay the
  *                            HBM reads of kernels that run beside the copy.
- * Process-wide.  Workspace sizes depend on FLOE_TUNE_UNION_KERNELS: do not change it between a *_workspace_bytes query and the decode
+ *   FLOE_TUNE_GROUPED_GEMV   decode batches (T >= 2; INT2 g64, INT3 / INT4 g32 or g64; d 1024, 2048 or 4096): whether the
+ *                            tokens routed to one expert share one pass over its codes on the matrix cores:
+ *                            0 = where measurement says it pays (about two tokens per expert; six for INT3),
+ *                            1 = whenever the shape allows, 2 = never (one pass per (token, slot)).
+ * Process-wide.  Workspace sizes depend on FLOE_TUNE_UNION_KERNELS and FLOE_TUNE_GROUPED_GEMV: do not change it between a *_workspace_bytes query and the decode
  * call that uses the workspace.  Unknown key or value: FLOE_EINVAL.
  */
-typedef enum { FLOE_TUNE_UNION_KERNELS = 1, FLOE_TUNE_STAGE_WORKGROUPS = 2 } floe_tuning_key;
+typedef enum { FLOE_TUNE_UNION_KERNELS = 1, FLOE_TUNE_STAGE_WORKGROUPS = 2, FLOE_TUNE_GROUPED_GEMV = 3 } floe_tuning_key;
 int floe_tuning(int key, int value);
 
 /* ------------------------------------------------------------------------------------------------

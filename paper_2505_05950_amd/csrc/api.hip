@@ -132,7 +132,7 @@ LayerWs layer_ws(const floe_layer* L, int T) {
     const int n_all = L->n_experts + L->n_shared;
     w.chunk = mfma_chunk(n_all, w.n_tasks);
     w.up = union_plan(L->s.d, L->s.f, w.n_tasks, n_all, w.chunk);
-    w.batch_mfma = T >= 2 && mfma_grouped_shape(L->s.d, L->s.bits, L->s.group) && mfma_batch_pays(n_all, w.n_tasks);
+    w.batch_mfma = T >= 2 && mfma_grouped_shape(L->s.d, L->s.bits, L->s.group) && mfma_batch_pays(n_all, w.n_tasks, L->s.bits);
     w.use_union = union_mode() != 0 && !L->gd_on_host && T >= 2 && (!w.fused_passes || w.batch_mfma) &&
                   mask_path_ok(L->s.f) && union_shape_ok(L->s.d, L->s.f, w.up);
     int nblk_alloc = w.nblk > w.nblk_fused ? w.nblk : w.nblk_fused;
@@ -268,6 +268,10 @@ int floe_tuning(int key, int value) {
         case FLOE_TUNE_UNION_KERNELS:
             if (value < 0 || value > 2) return FLOE_EINVAL;
             set_union_mode(value);
+            return FLOE_OK;
+        case FLOE_TUNE_GROUPED_GEMV:
+            if (value < 0 || value > 2) return FLOE_EINVAL;
+            set_grouped_gemv_mode(value);
             return FLOE_OK;
         case FLOE_TUNE_STAGE_WORKGROUPS:
             if (value < 0 || value > 4096) return FLOE_EINVAL;

@@ -68,7 +68,7 @@ struct TokenGroup {
     int32_t task[16];  // ascending task ids (token * slots + slot)
 };
 inline bool mfma_grouped_shape(int d, int bits, int group) {
-    return ((bits == 2 && group == 64) || (bits == 4 && (group == 32 || group == 64))) &&
+    return ((bits == 2 && group == 64) || ((bits == 3 || bits == 4) && (group == 32 || group == 64))) &&
            (d == 1024 || d == 2048 || d == 4096);
 }
 // tasks per group (token rows of the MFMA tile that are used): 8 while experts see few tokens each, else 16
@@ -76,8 +76,18 @@ inline int mfma_chunk(int n_all, int n_tasks) { return n_tasks <= 8 * n_all ? 8 
 inline int mfma_max_groups(int n_all, int n_tasks) {
     return (n_all < n_tasks ? n_all : n_tasks) + n_tasks / mfma_chunk(n_all, n_tasks) + 1;
 }
-// grouping pays once experts see about two tokens each; below that the per-token kernels read the same bytes
-inline bool mfma_batch_pays(int n_all, int n_tasks) { return n_tasks >= 2 * n_all; }
+// Grouping pays once experts see about two tokens each; below that the per-token kernels read the same bytes.  The
+// INT3 form is bound by its unpacking and by one round trip per eight units on short channels, not by the bytes: it
+// needs about six tokens per expert before it beats the per-token kernel.  grouped_gemv_mode: 0 = this rule,
+// 1 = whenever the shape allows, 2 = never (floe_tuning).
+int grouped_gemv_mode();
+void set_grouped_gemv_mode(int m);
+inline bool mfma_batch_pays(int n_all, int n_tasks, int bits) {
+    const int mode = grouped_gemv_mode();
+    if (mode == 1) return true;
+    if (mode == 2) return false;
+    return n_tasks >= (bits == 3 ? 6 : 2) * n_all;
+}
 hipError_t launch_group_tokens(const int32_t* task_expert, int n_tasks, int n_all, int chunk, TokenGroup* groups,
                                int32_t* n_groups, hipStream_t stream, int32_t* order = nullptr);
 hipError_t launch_up_gemv_grouped(const DevExpert* table, const TokenGroup* groups, const int32_t* n_groups,

@@ -29,6 +29,10 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kMfmaThreads = 512;              // 8 waves
 
+static std::atomic<int> g_grouped_gemv_mode{0};
+int grouped_gemv_mode() { return g_grouped_gemv_mode.load(std::memory_order_relaxed); }
+void set_grouped_gemv_mode(int m) { g_grouped_gemv_mode.store(m >= 0 && m <= 2 ? m : 0, std::memory_order_relaxed); }
+
 // How the 64 codes of a unit are dealt to the four lane quarters g and the two MFMAs j.
 //  kLaneWords           code words a lane loads per unit
 //  word(k, g)           index (inside the unit) of the lane's k-th word
@@ -66,10 +70,37 @@ template <bool G32> struct MfmaTraits<4, G32> {  // MFMA j reads word 4j + g: it
     }
 };
 
+// INT3: the 32 codes of a half unit are 96 contiguous bits; quarter g owns the 24 bits [24g, 24g + 24) of them, which
+// lie in words a, a + 1 of the half unit with a = g / 2.  A lane loads those two words itself (kOwnWords) and shifts
+// its field down; codes 0..3 of the field stay in the low 16-bit half, codes 4..7 move to the high half.
+template <bool G32> struct MfmaTraits<3, G32> {
+    static constexpr int kLaneWords = 4;  // two words for each of the two MFMAs
+    static constexpr int kPmax = 6;
+    __device__ static constexpr int word(int k, int g) { return 3 * (k >> 1) + (g >> 1) + (k & 1); }
+    __device__ static constexpr int code(int j, int g, int s) {
+        constexpr int t[8] = {0, 4, 1, 5, 2, 6, 3, 7};
+        return 32 * j + 8 * g + t[s];
+    }
+    __device__ static constexpr int pos(int j, int s) {
+        constexpr int t[8] = {0, 0, 3, 3, 6, 6, 6, 6};
+        (void)j;
+        return t[s];
+    }
+};
+
 // the 4 registers (8 fp16 subnormals) of MFMA j from the lane's code words
 template <int BITS, bool G32>
 __device__ __forceinline__ void weight_frag(const uint32_t* w, int j, int g, uint32_t (&r)[4]) {
-    if (BITS == 2 && !G32) {
+    if (BITS == 3) {
+        // w[2j], w[2j+1]: the two words that hold the quarter's 24 bits, at bit 24g - 32(g/2) of the pair
+        const uint64_t pair = ((uint64_t)w[2 * j + 1] << 32) | w[2 * j];
+        const uint32_t c24 = (uint32_t)(pair >> (24 * g - 32 * (g >> 1)));
+        const uint32_t t = (c24 & 0x00000FFFu) | ((c24 << 4) & 0x0FFF0000u);
+        r[0] = t & 0x00070007u;         // codes (0, 4) at bits [0,3)
+        r[1] = t & 0x00380038u;         // codes (1, 5) at bits [3,6)
+        r[2] = t & 0x01C001C0u;         // codes (2, 6) at bits [6,9)
+        r[3] = (t >> 3) & 0x01C001C0u;  // codes (3, 7) from bits [9,12) to [6,9)
+    } else if (BITS == 2 && !G32) {
         const uint32_t W = w[0], a = W << 4, b = W >> 6;
         if (j == 0) {
             r[0] = a & 0x00300030u;  // codes (0, 8)  at bits [4,6)
@@ -109,6 +140,7 @@ __global__ __launch_bounds__(kMfmaThreads) void up_gemv_mfma_kernel(const DevExp
     constexpr int LW = Tr::kLaneWords;
     constexpr int kCw = BITS * 2;               // code words per unit (64 codes)
     constexpr int LWQ = kCw / 4;                // 128-bit vectors per unit
+    constexpr bool kOwnWords = BITS == 3;       // every lane loads the words of its own quarter (no exchange)
     constexpr int GPU_ = G32 ? 2 : 1;           // quantization groups per unit
     constexpr int kGroupsPerRow = UPC * GPU_;   // scale / zero entries per channel
     constexpr float kScaleBack = (float)(1 << (24 - Tr::kPmax));
@@ -239,7 +271,8 @@ __global__ __launch_bounds__(kMfmaThreads) void up_gemv_mfma_kernel(const DevExp
     constexpr int kBlk = 8;                    // units per block
     constexpr int NB = UPC / kBlk;             // blocks per channel (2, 4 or 8)
     constexpr int NSB = (NB + 3) / 4;          // super-blocks of 4 blocks (meta registers)
-    constexpr int kRaw = 2 * LWQ;              // uint4 a lane loads per tile per block (its two units)
+    constexpr int kRaw = kOwnWords ? 1 : 2 * LWQ;  // uint4 a lane loads per tile per block (its two units)
+    constexpr int kOwn = kOwnWords ? 2 * kBlk : 1;  // own-words form: a word pair per unit and MFMA
     constexpr int kMetaRegs = 4 * GPU_;        // 32-bit registers holding a block's 8 * GPU_ fp16 scales
     uint32_t coff[TILES], moff[TILES];
     int chan[TILES];
@@ -247,7 +280,7 @@ __global__ __launch_bounds__(kMfmaThreads) void up_gemv_mfma_kernel(const DevExp
     for (int tt = 0; tt < TILES; ++tt) {
         chan[tt] = ch0 + 16 * tt + c;
         const uint32_t chl = chan[tt] < f ? chan[tt] : f - 1;  // clamped lanes load valid memory, never store
-        coff[tt] = chl * (UPC * kCw) * 4u + (uint32_t)(2 * g) * (kCw * 4u);
+        coff[tt] = chl * (UPC * kCw) * 4u + (kOwnWords ? (uint32_t)(g >> 1) * 4u : (uint32_t)(2 * g) * (kCw * 4u));
         moff[tt] = chl * kGroupsPerRow * 2u;
     }
     float acc[TILES][4];
@@ -266,8 +299,10 @@ __global__ __launch_bounds__(kMfmaThreads) void up_gemv_mfma_kernel(const DevExp
             const uint32_t off = moff[tt] + (uint32_t)(blk * kBlk * GPU_) * 2u;
 #pragma unroll
             for (int r4 = 0; r4 < GPU_; ++r4) {
-                const uint4 a = *reinterpret_cast<const uint4*>(sbase + off + 16 * r4);
-                const uint4 bq = *reinterpret_cast<const uint4*>(zbase + off + 16 * r4);
+                // (the expert's pointers come out of a table in memory: say that they are global, or every load is a flat
+                // one, which the LDS wait counter tracks as well)
+                const uint4 a = gload16(sbase + off + 16 * r4);
+                const uint4 bq = gload16(zbase + off + 16 * r4);
                 ms[tt][Q][4 * r4 + 0] = a.x; ms[tt][Q][4 * r4 + 1] = a.y; ms[tt][Q][4 * r4 + 2] = a.z; ms[tt][Q][4 * r4 + 3] = a.w;
                 mz[tt][Q][4 * r4 + 0] = bq.x; mz[tt][Q][4 * r4 + 1] = bq.y; mz[tt][Q][4 * r4 + 2] = bq.z; mz[tt][Q][4 * r4 + 3] = bq.w;
             }
@@ -275,13 +310,22 @@ __global__ __launch_bounds__(kMfmaThreads) void up_gemv_mfma_kernel(const DevExp
 
     struct Block {
         uint4 raw[TILES][kRaw];
+        uint32_t own[TILES][kOwn][2];
     };
     auto load_block = [&](Block& b, int blk) {
 #pragma unroll
         for (int tt = 0; tt < TILES; ++tt) {
-            const uint4* p = reinterpret_cast<const uint4*>(cbase + (coff[tt] + (uint32_t)blk * (kBlk * kCw * 4u)));
+            const char* pb = cbase + (coff[tt] + (uint32_t)blk * (kBlk * kCw * 4u));
+            if constexpr (kOwnWords) {
 #pragma unroll
-            for (int r = 0; r < kRaw; ++r) b.raw[tt][r] = p[r];
+                for (int r = 0; r < kOwn; ++r) {  // r = 2 * unit + MFMA: half units are 12 bytes apart
+                    b.own[tt][r][0] = gload4(pb + 12 * r);
+                    b.own[tt][r][1] = gload4(pb + 12 * r + 4);
+                }
+            } else {
+#pragma unroll
+                for (int r = 0; r < kRaw; ++r) b.raw[tt][r] = gload16(pb + 16 * r);
+            }
         }
     };
     auto transpose4 = [](uint4& q) {  // across the four lane quarters: register k <- word g of quarter k's vector
@@ -305,10 +349,12 @@ __global__ __launch_bounds__(kMfmaThreads) void up_gemv_mfma_kernel(const DevExp
                 bs[tt][r] = (uint32_t)__builtin_amdgcn_ds_bpermute(src_lane4, (int)sv);
                 bz[tt][r] = (uint32_t)__builtin_amdgcn_ds_bpermute(src_lane4, (int)zv);
             }
+        if constexpr (!kOwnWords) {
 #pragma unroll
-        for (int tt = 0; tt < TILES; ++tt)
+            for (int tt = 0; tt < TILES; ++tt)
 #pragma unroll
-            for (int r = 0; r < kRaw; ++r) transpose4(b.raw[tt][r]);
+                for (int r = 0; r < kRaw; ++r) transpose4(b.raw[tt][r]);
+        }
         // after the transposes: raw[tt][h * LWQ + w4] component k = word (4 * w4 + g) of unit 2k + h
 #pragma unroll
         for (int uu = 0; uu < kBlk; ++uu) {
@@ -329,10 +375,15 @@ __global__ __launch_bounds__(kMfmaThreads) void up_gemv_mfma_kernel(const DevExp
 #pragma unroll
             for (int tt = 0; tt < TILES; ++tt) {
                 uint32_t w[LW];
+                if constexpr (kOwnWords) {
+                    w[0] = b.own[tt][2 * uu][0]; w[1] = b.own[tt][2 * uu][1];
+                    w[2] = b.own[tt][2 * uu + 1][0]; w[3] = b.own[tt][2 * uu + 1][1];
+                } else {
 #pragma unroll
-                for (int k = 0; k < LW; ++k) {
-                    const uint4 q = b.raw[tt][h * LWQ + (LWQ == 1 ? 0 : k)];
-                    w[k] = kq == 0 ? q.x : (kq == 1 ? q.y : (kq == 2 ? q.z : q.w));
+                    for (int k = 0; k < LW; ++k) {
+                        const uint4 q = b.raw[tt][h * LWQ + (LWQ == 1 ? 0 : k)];
+                        w[k] = kq == 0 ? q.x : (kq == 1 ? q.y : (kq == 2 ? q.z : q.w));
+                    }
                 }
                 uint32_t r0[4], r1[4];
                 weight_frag<BITS, G32>(w, 0, g, r0);
@@ -435,14 +486,29 @@ __global__ __launch_bounds__(1024) void group_tokens_kernel(const int32_t* __res
     __syncthreads();
     for (int e = tid; e < n_all; e += 1024) first_group[e + 1] = (count[e] + chunk - 1) / chunk;
     __syncthreads();
-    if (tid == 0) {
-        first_group[0] = 0;
-        first_task[0] = 0;
-        for (int e = 0; e < n_all; ++e) {
-            first_group[e + 1] += first_group[e];
-            first_task[e + 1] = first_task[e] + count[e];
+    if (wave == 0) {  // prefix sums over the experts, 64 at a time
+        int run_g = 0, run_t = 0;
+        for (int e0 = 0; e0 < n_all; e0 += kWave) {
+            const int e = e0 + lane;
+            int sg = e < n_all ? first_group[e + 1] : 0;
+            int st = e < n_all ? count[e] : 0;
+#pragma unroll
+            for (int o = 1; o < kWave; o <<= 1) {
+                const int ug = __shfl_up(sg, o, kWave), ut = __shfl_up(st, o, kWave);
+                if (lane >= o) { sg += ug; st += ut; }
+            }
+            if (e < n_all) {
+                first_group[e + 1] = run_g + sg;
+                first_task[e + 1] = run_t + st;
+            }
+            run_g += __shfl(sg, kWave - 1, kWave);
+            run_t += __shfl(st, kWave - 1, kWave);
         }
-        n_groups[0] = first_group[n_all];
+        if (lane == 0) {
+            first_group[0] = 0;
+            first_task[0] = 0;
+            n_groups[0] = run_g;
+        }
     }
     __syncthreads();
     // group headers
@@ -495,7 +561,7 @@ static hipError_t launch_mfma_inst(int max_groups, hipStream_t stream, const Dev
                                    const int32_t* n_groups, const h16* x, int slots, float* v, const float* task_tau,
                                    uint32_t* mask_words, int f) {
     // channels per wave = 16 * TILES: code blocks are double-buffered and all scales / zeros sit in registers
-    constexpr int TILES = (BITS == 4 && G32) ? 1 : 2;
+    constexpr int TILES = ((BITS == 4 && G32) || BITS == 3) ? 1 : 2;
     constexpr size_t lds = (size_t)UPC * 8 * NTPAD * 16 + (size_t)UPC * (G32 ? 2 : 1) * NTPAD * 4;
     // the attribute belongs to the function on one device: set once per device, from whichever thread comes first
     constexpr int kMaxDevices = 64;
@@ -548,6 +614,9 @@ hipError_t launch_up_gemv_grouped(const DevExpert* table, const TokenGroup* grou
     const int upc = d / 64;
     const bool g32 = group == 32;
     if (bits == 2) return launch_mfma_upc<2, false>(upc, chunk, max_groups, stream, table, groups, n_groups, x, slots, v, task_tau, mask_words, f);
+    if (bits == 3)
+        return g32 ? launch_mfma_upc<3, true>(upc, chunk, max_groups, stream, table, groups, n_groups, x, slots, v, task_tau, mask_words, f)
+                   : launch_mfma_upc<3, false>(upc, chunk, max_groups, stream, table, groups, n_groups, x, slots, v, task_tau, mask_words, f);
     return g32 ? launch_mfma_upc<4, true>(upc, chunk, max_groups, stream, table, groups, n_groups, x, slots, v, task_tau, mask_words, f)
                : launch_mfma_upc<4, false>(upc, chunk, max_groups, stream, table, groups, n_groups, x, slots, v, task_tau, mask_words, f);
 }

@@ -168,10 +168,20 @@ def test_layer_with_more_than_64_experts_takes_the_serial_top_k():
 
 def test_layer_batches_through_the_matrix_core_gemv():
     """Decode batches group the tokens of an expert (chunks of 16) and run S2 on the matrix cores:
-    INT4 / INT2, groups of 32 and 64, more than 16 tokens per expert, ragged f."""
-    _run_layer_case(17, 3, 2048, 650, 4, 32, 4, 1, 2, True, 20, 80)
-    _run_layer_case(18, 3, 1024, 1000, 2, 32, 3, 0, 1, False, 37, 60)
-    _run_layer_case(19, 3, 4096, 530, 4, 64, 2, 0, 2, True, 6, 70)
+    INT4 / INT3 / INT2, groups of 32 and 64, more than 16 tokens per expert, ragged f."""
+    import paper_2505_05950_amd as F
+    F.load()
+    F.floe_tuning(F.TUNE_GROUPED_GEMV, 1)       # wherever the shape allows, whatever the batch size
+    try:
+        _run_layer_case(17, 3, 2048, 650, 4, 32, 4, 1, 2, True, 20, 80)
+        _run_layer_case(18, 3, 1024, 1000, 2, 32, 3, 0, 1, False, 37, 60)
+        _run_layer_case(19, 3, 4096, 530, 4, 64, 2, 0, 2, True, 6, 70)
+        # INT3: a quarter's 24 bits straddle the words of a half unit
+        _run_layer_case(41, 5, 2048, 333, 3, 32, 6, 1, 2, False, 24, 85)
+        _run_layer_case(42, 5, 1024, 600, 3, 64, 3, 0, 1, True, 20, 70)
+        _run_layer_case(43, 5, 4096, 130, 3, 32, 2, 0, 2, True, 5, 60)
+    finally:
+        F.floe_tuning(F.TUNE_GROUPED_GEMV, 0)
 
 
 @pytest.mark.parametrize("kernels", ["expert_order", "matrix_cores", "lds_ring"])
