@@ -103,7 +103,16 @@ __global__ __launch_bounds__(kFusedThreads, fused_wgs_per_cu) void fused_ffn_ker
     __shared__ uint4 xlds[d / 8];               // the token, for the consumers' gate dot products
     const int tid = threadIdx.x;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;  // the wave index as a scalar
-    const int task = blockIdx.y;
+    // Which (task, channel block) this workgroup takes.  Workgroups go to the eight XCDs round-robin in launch order.
+    // With several tasks and a block count that is a multiple of eight, the tasks' workgroups for one channel block are
+    // launched next to each other on one XCD: tasks that were routed to the same expert then read that block's codes
+    // (and the rows both select) from HBM once, the later ones from the L2.
+    int task = blockIdx.y, blk = blockIdx.x;
+    if (gridDim.y > 1 && (gridDim.x & 7) == 0) {
+        const int L = blockIdx.y * gridDim.x + blockIdx.x, s_ = L >> 3;
+        task = s_ % (int)gridDim.y;
+        blk = 8 * (s_ / (int)gridDim.y) + (L & 7);
+    }
     const int t = task / map.slots;
     const int slot = task - t * map.slots;
     const h16* xt = x + (size_t)t * d;
@@ -146,7 +155,7 @@ __global__ __launch_bounds__(kFusedThreads, fused_wgs_per_cu) void fused_ffn_ker
     if (producer) {
         // ================================================================ producer: codes -> v -> queue
         const int G = d >> gshift;
-        const int jw = (blockIdx.x * kFusedProducers + wave) * kQ;
+        const int jw = (blk * kFusedProducers + wave) * kQ;
         auto channel_of = [&](int p) {
             const int j = jw + p * CPW + sub;
             return j < f ? j : f - 1;  // keep the address in bounds; a clamped lane's result is not used
@@ -199,7 +208,7 @@ __global__ __launch_bounds__(kFusedThreads, fused_wgs_per_cu) void fused_ffn_ker
                 const float wl = route_weight_wave16(pick, ro.top_k, ro.renormalize);
                 if (slot < ro.top_k) wgt = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, wl), slot));
             }
-            if (blockIdx.x == 0 && tid == 0) {  // the task's routing record (statistics)
+            if (blk == 0 && tid == 0) {  // the task's routing record (statistics)
                 ro.task_table[task] = e;
                 ro.task_expert[task] = ex;
                 ro.task_weight[task] = wgt;
@@ -359,7 +368,7 @@ __global__ __launch_bounds__(kFusedThreads, fused_wgs_per_cu) void fused_ffn_ker
     __syncthreads();
     FLOE_TL(7);
     // ---- the workgroup's partial y: consumers summed in a fixed order
-    float4* out = reinterpret_cast<float4*>(partial + ((size_t)task * gridDim.x + blockIdx.x) * d);
+    float4* out = reinterpret_cast<float4*>(partial + ((size_t)task * gridDim.x + blk) * d);
     for (int c4 = tid; c4 < d / 4; c4 += kFusedThreads) {
         float4 s = reinterpret_cast<const float4*>(&yred[0][0])[c4];
 #pragma unroll
@@ -369,7 +378,7 @@ __global__ __launch_bounds__(kFusedThreads, fused_wgs_per_cu) void fused_ffn_ker
         }
         out[c4] = s;
     }
-    if (tid == 0) wg_count[(size_t)task * gridDim.x + blockIdx.x] = n_sel;
+    if (tid == 0) wg_count[(size_t)task * gridDim.x + blk] = n_sel;
     FLOE_TL(8);
 }
 
