@@ -255,6 +255,29 @@ def test_expert_ffn_without_a_list_gives_the_same_result(d, f, bits, group, T):
         assert G.rel_err(y1[t], w * O.sparse_ffn(ex_np[3], x[t], v_ref[t], got)[1]) <= G.Y_TIGHT
 
 
+@pytest.mark.parametrize("f,T,want_list", [(448, 1, False), (448, 2, True), (450, 1, False), (2240, 1, False)])
+def test_expert_ffn_with_every_channel_selected_meets_the_tight_bar(f, T, want_list):
+    """tau < 0 selects every channel: every queue of the fused kernel runs full, so a consumer leaves its loop because
+    the queue is exhausted, not because it saw its producer's flag.  The INT2 producer's staging ring lies in the slabs
+    that the consumers store their results in, so a consumer has to wait for the flag before that store.  d = 4096,
+    INT2, whole blocks of 112 channels (and one ragged), dense result compared with the oracle at the tight bar."""
+    G = _gc()
+    import paper_2505_05950_amd as F
+    d, bits, group = 4096, 2, 64
+    ex_np, ex_dev, x = _expert_case(31, 58, d, f, bits, group, T)
+    tau = np.full((T,), -1.0, np.float32)
+    y = torch.zeros((T, d), dtype=torch.float32, device=G.DEV)
+    y, idx, count = F.floe_expert_ffn_sparse(ex_dev, G.dev(x), G.dev(tau), None, y, want_list=want_list)
+    torch.cuda.synchronize()
+    y = y.cpu().numpy().astype(np.float64)
+    every = np.arange(f, dtype=np.int32)
+    for t in range(T):
+        v_ref = O.up_gemv(*ex_np[:3], d, bits, group, x[t])
+        if want_list:
+            assert count[t].item() == f and np.array_equal(idx[t].cpu().numpy(), every)
+        assert G.rel_err(y[t], O.sparse_ffn(ex_np[3], x[t], v_ref, every)[1]) <= G.Y_TIGHT
+
+
 def test_expert_ffn_with_more_than_65536_channels_uses_the_select_kernel():
     """Lists longer than 2048 mask words are compacted by the stand-alone select kernel; same results."""
     G = _gc()
