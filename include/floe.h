@@ -86,14 +86,14 @@ int floe_profile_kernel(int kernel_id, void* start_event, void* stop_event);
  * Tuning switch (no part of the method; every setting gives results within the same parity bars).
  *   FLOE_TUNE_UNION_KERNELS  how Alg. 1 steps 4-5 run for decode batches (more than 16 (token, slot) pairs), where
  *                            the tokens of an expert select overlapping rows:
- *                            0 = one workgroup set per (token, slot), launched in expert order on XCD-aligned channel
- *                                blocks, so that a row several tokens selected is fetched from HBM once and served to
- *                                the others by the L2 (default; the fastest measured at the sparsity levels of
- *                                Sec. 3.2.1);
+ *                            0 = chosen per call (default): 1 once the experts see about a dozen tokens each, else 3;
  *                            1 = per expert group, the union of the selected rows read once, gate and down
  *                                projections on the matrix cores (dense token x row tiles);
  *                            2 = per expert group, the union of the selected rows read once into a ring in LDS, one
- *                                wave per token.
+ *                                wave per token;
+ *                            3 = one workgroup set per (token, slot), launched in expert order on XCD-aligned channel
+ *                                blocks, so that a row several tokens selected is fetched from HBM once and served to
+ *                                the others by the L2.
  *   FLOE_TUNE_STAGE_WORKGROUPS  workgroups (of four waves, four 16-byte reads in flight per lane) of the kernels that
  *                            copy selected chunks out of pinned host memory; 0 = the library's default, at most 4096.
  *                            More workgroups than the link needs keep more host reads in flight, and these delay the
@@ -102,8 +102,8 @@ int floe_profile_kernel(int kernel_id, void* start_event, void* stop_event);
  *                            tokens routed to one expert share one pass over its codes on the matrix cores:
  *                            0 = where measurement says it pays (about two tokens per expert; six for INT3),
  *                            1 = whenever the shape allows, 2 = never (one pass per (token, slot)).
- * Process-wide.  Workspace sizes depend on FLOE_TUNE_UNION_KERNELS and FLOE_TUNE_GROUPED_GEMV: do not change it between a *_workspace_bytes query and the decode
- * call that uses the workspace.  Unknown key or value: FLOE_EINVAL.
+ * Process-wide.  Workspace sizes depend on FLOE_TUNE_UNION_KERNELS and FLOE_TUNE_GROUPED_GEMV: do not change them
+ * between a *_workspace_bytes query and the decode call that uses the workspace.  Unknown key or value: FLOE_EINVAL.
  */
 typedef enum { FLOE_TUNE_UNION_KERNELS = 1, FLOE_TUNE_STAGE_WORKGROUPS = 2, FLOE_TUNE_GROUPED_GEMV = 3 } floe_tuning_key;
 int floe_tuning(int key, int value);

@@ -133,7 +133,7 @@ LayerWs layer_ws(const floe_layer* L, int T) {
     w.chunk = mfma_chunk(n_all, w.n_tasks);
     w.up = union_plan(L->s.d, L->s.f, w.n_tasks, n_all, w.chunk);
     w.batch_mfma = T >= 2 && mfma_grouped_shape(L->s.d, L->s.bits, L->s.group) && mfma_batch_pays(n_all, w.n_tasks, L->s.bits);
-    w.use_union = union_mode() != 0 && !L->gd_on_host && T >= 2 && (!w.fused_passes || w.batch_mfma) &&
+    w.use_union = union_kernels_for(n_all, w.n_tasks) != 3 && !L->gd_on_host && T >= 2 && (!w.fused_passes || w.batch_mfma) &&
                   mask_path_ok(L->s.f) && union_shape_ok(L->s.d, L->s.f, w.up);
     int nblk_alloc = w.nblk > w.nblk_fused ? w.nblk : w.nblk_fused;
     if (w.use_union && w.up.nblk_down > nblk_alloc) nblk_alloc = w.up.nblk_down;
@@ -266,7 +266,7 @@ int floe_profile_kernel(int kernel_id, void* start_event, void* stop_event) {
 int floe_tuning(int key, int value) {
     switch (key) {
         case FLOE_TUNE_UNION_KERNELS:
-            if (value < 0 || value > 2) return FLOE_EINVAL;
+            if (value < 0 || value > 3) return FLOE_EINVAL;
             set_union_mode(value);
             return FLOE_OK;
         case FLOE_TUNE_GROUPED_GEMV:

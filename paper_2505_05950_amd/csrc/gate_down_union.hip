@@ -19,6 +19,7 @@
 //                       registers (v_perm_b32) turns them into B fragments, the accumulators never leave the registers,
 //                       and the workgroup stores one fp32 partial per live token; S6 (combine_kernel) adds the partials.
 #include <atomic>
+#include <cmath>
 
 #include "floe_dev.h"
 #include "launch.h"
@@ -538,29 +539,46 @@ __global__ __launch_bounds__(kFusedUnionWaves * 64) void union_fused_kernel(Unio
 // ---------------------------------------------------------------------------------------------------------------
 // host side
 // ---------------------------------------------------------------------------------------------------------------
-// Which kernels run steps 4-5 of a decode batch (floe_tuning): 0 = the one-token kernels launched in expert order (rows
-// that several tokens selected are shared through the L2; the default, and the fastest measured), 1 = matrix cores
-// (gate_union_kernel + down_union_kernel), 2 = rows staged through an LDS ring (union_fused_kernel).  Process-wide:
+// Which kernels run steps 4-5 of a decode batch (floe_tuning): 0 = chosen per call (below), 1 = matrix cores
+// (gate_union_kernel + down_union_kernel), 2 = rows staged through an LDS ring (union_fused_kernel), 3 = the one-token
+// kernels launched in expert order (rows that several tokens selected are shared through the L2).  Process-wide:
 // workspace sizes depend on it, so it must not change between a size query and the call that uses the workspace.
 static std::atomic<int> g_union_mode{0};
 int union_mode() { return g_union_mode.load(std::memory_order_relaxed); }
-void set_union_mode(int m) { g_union_mode.store(m >= 0 && m <= 2 ? m : 0, std::memory_order_relaxed); }
+void set_union_mode(int m) { g_union_mode.store(m >= 0 && m <= 3 ? m : 0, std::memory_order_relaxed); }
+// Measured (8 experts, d = 4096, f = 14336, 90 %): the matrix-core pair overtakes the one-token kernels once an expert
+// sees about a dozen tokens (its union is then most of the matrix and every row serves several tokens).
+int union_kernels_for(int n_all, int n_tasks) {
+    const int m = union_mode();
+    if (m != 0) return m;
+    return (long long)n_tasks >= 12ll * n_all ? 1 : 3;
+}
+
+// Expected number of token groups when n_tasks (token, slot) pairs fall on n_all experts uniformly: per expert
+// E[ceil(X / chunk)] = sum over k >= 0 of P(X > k * chunk), X binomial, by its normal approximation.
+static double expected_groups(int n_all, int n_tasks, int chunk) {
+    const double pr = 1.0 / n_all, mu = n_tasks * pr, sd = sqrt(n_tasks * pr * (1.0 - pr)) + 1e-9;
+    double per = 0.0;
+    for (int k = 0; k * chunk < n_tasks; ++k) per += 0.5 * erfc(((double)k * chunk + 0.5 - mu) / (sd * 1.4142135623730951));
+    return per * n_all;
+}
 
 UnionPlan union_plan(int d, int f, int n_tasks, int n_all, int chunk) {
     UnionPlan p{};
     const int nwords = mask_words_per_task(f);
     p.max_groups = mfma_max_groups(n_all, n_tasks);
-    // about one gate workgroup per compute unit for the groups that can exist at once (every task is in one group)
-    int est = n_tasks / chunk + 1;
-    est = est < (n_all < n_tasks ? n_all : n_tasks) ? (n_all < n_tasks ? n_all : n_tasks) : est;
-    int nb = (num_cus() + est - 1) / est;
+    const int kernels = union_kernels_for(n_all, n_tasks);
+    p.matrix_cores = kernels == 1;
+    p.fused = kernels == 2;
+    // Gate workgroups hold the group's activations in LDS, one per compute unit: a launch of a little less than one
+    // workgroup per compute unit for the groups to be expected runs in one round (a few more and it takes two).
+    const double est = expected_groups(n_all, n_tasks, chunk);
+    int nb = (int)(0.95 * num_cus() / (est > 1.0 ? est : 1.0));
     nb = nb < 1 ? 1 : (nb > nwords ? nwords : nb);
     // at least two tiles of work per wave where the block is long enough: 16 rows x 8 waves x 2 = 256 channels = 8 words
     const int by_len = (nwords + 7) / 8;
     nb = nb > by_len ? by_len : nb;
     nb = nb < 1 ? 1 : nb;
-    p.matrix_cores = union_mode() == 1;
-    p.fused = union_mode() == 2;
     if (p.matrix_cores) {
         // down blocks: a divisor of the gate blocks, about half as many (fewer partial results to add up afterwards)
         p.nblk_down = nb >= 2 ? nb / 2 : 1;

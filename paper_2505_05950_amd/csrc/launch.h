@@ -121,6 +121,7 @@ constexpr int kStageWorkgroupsDefault = 32;  // 128 waves x 4 KiB in flight: the
 int stage_workgroups();
 void set_stage_workgroups(int n);  // 0 = default
 int union_mode();
+int union_kernels_for(int n_all, int n_tasks);  // 1 matrix cores, 2 LDS ring, 3 one-token kernels in expert order
 void set_union_mode(int m);
 struct UnionArgs {
     const DevExpert* table;

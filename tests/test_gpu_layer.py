@@ -193,7 +193,7 @@ def test_layer_batches_read_the_union_of_selected_rows_once(kernels):
     expert (two groups), groups of one token, shared experts that see every token, every row selected (0 %), hardly
     any (99 %), ragged f, d from 512 to 4096, every up-GEMV kernel in front (matrix-core, packed, generic)."""
     import paper_2505_05950_amd as F
-    F.floe_tuning(F.TUNE_UNION_KERNELS, {"expert_order": 0, "matrix_cores": 1, "lds_ring": 2}[kernels])
+    F.floe_tuning(F.TUNE_UNION_KERNELS, {"expert_order": 3, "matrix_cores": 1, "lds_ring": 2}[kernels])
     try:
         _run_layer_case(40, 3, 4096, 530, 4, 64, 2, 0, 2, True, 24, 80)
         _run_layer_case(41, 5, 2048, 1408, 3, 32, 16, 2, 6, False, 12, 85)
