@@ -12,8 +12,9 @@ namespace floe {
 
 constexpr int kMaxExperts = 1024;
 
-// Softmax + top-k for n <= 64 experts on one wave (lane e holds expert e).  Same expf, the same ascending sum and the
-// same tie rule (lower id) as route_select, so both give the same bits.
+// Softmax + top-k for n <= 64 experts on one wave (lane e holds expert e).  Same expf and the same tie rule (lower id)
+// as route_select; the sum of the exponentials is a DPP tree instead of that routine's ascending chain (64 dependent
+// scalar reads cost more than the rest of the routing together), so weights may differ from it in the last bit.
 __device__ __forceinline__ float lane_f(float v, int l) {
     return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), l));
 }
@@ -24,8 +25,7 @@ __device__ __forceinline__ void route_select_wave64(float logit, int lane, int n
     float mx = row16_allreduce_max(live ? logit : -INFINITY);
     mx = fmaxf(fmaxf(lane_f(mx, 0), lane_f(mx, 16)), fmaxf(lane_f(mx, 32), lane_f(mx, 48)));
     const float p = live ? expf(logit - mx) : 0.0f;
-    float sum = 0.0f;
-    for (int e = 0; e < n; ++e) sum += lane_f(p, e);
+    const float sum = wave_allreduce_sum(p);
     float cur = live ? p : -3.0f;
     float sel = 0.0f, my_w = 0.0f;
     int my_id = 0;
