@@ -160,7 +160,7 @@ __global__ __launch_bounds__(kGateWaves * 64) void gate_union_kernel(UnionArgs a
     constexpr int d = 512 * NV;
     constexpr int kSteps = d / 32;
     constexpr int kXStride = d * 2 + 16;  // bytes
-    constexpr int kDepth = 16;            // k-steps of a tile's rows in flight per lane (16 bytes each)
+    constexpr int kDepth = 16;            // k-steps of a tile's rows in flight per lane (16 bytes each; 32 measured slower)
     static_assert(kSteps % kDepth == 0, "d is a multiple of 512");
     extern __shared__ __align__(16) unsigned char lds[];
     unsigned char* xl = lds;                                                  // [NT][kXStride]
