@@ -19,27 +19,36 @@ FLAGS = [
 ]
 
 
-def _compile(src: str) -> str:
-    obj = os.path.join(OBJ, src.replace(".hip", ".o"))
-    cmd = [HIPCC] + FLAGS + ["-c", os.path.join(CSRC, src), "-o", obj]
+# Instrumented build for tuning: every kernel that carries FLOE_TL marks stores a clock value per workgroup and mark into
+# a buffer handed over through floe_debug_set_timeline_* (see FLOE_TL in csrc/floe_dev.h).  A library of its own
+# (libfloe_hip_timeline.so); the product library never contains the marks.
+LIB_TIMELINE = os.path.join(HERE, "libfloe_hip_timeline.so")
+OBJ_TIMELINE = os.path.join(HERE, "_build_timeline")
+
+
+def _compile(src: str, timeline: bool = False) -> str:
+    obj = os.path.join(OBJ_TIMELINE if timeline else OBJ, src.replace(".hip", ".o"))
+    cmd = [HIPCC] + FLAGS + (["-DFLOE_TIMELINE"] if timeline else []) + ["-c", os.path.join(CSRC, src), "-o", obj]
     res = subprocess.run(cmd, capture_output=True, text=True)
     if res.returncode != 0:
         raise RuntimeError(f"hipcc failed for {src}:\n{res.stdout}\n{res.stderr}")
     return obj
 
 
-def build(verbose: bool = False) -> str:
-    os.makedirs(OBJ, exist_ok=True)
+def build(verbose: bool = False, timeline: bool = False) -> str:
+    os.makedirs(OBJ_TIMELINE if timeline else OBJ, exist_ok=True)
+    lib = LIB_TIMELINE if timeline else LIB
     with fut.ThreadPoolExecutor(max_workers=min(8, len(SOURCES))) as ex:
-        objs = list(ex.map(_compile, SOURCES))
-    cmd = [HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB] + objs
+        objs = list(ex.map(lambda src: _compile(src, timeline), SOURCES))
+    cmd = [HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", lib] + objs
     res = subprocess.run(cmd, capture_output=True, text=True)
     if res.returncode != 0:
         raise RuntimeError(f"link failed:\n{res.stdout}\n{res.stderr}")
     if verbose:
-        print("built", LIB)
-    return LIB
+        print("built", lib)
+    return lib
 
 
 if __name__ == "__main__":
-    build(verbose=True)
+    import sys
+    build(verbose=True, timeline="--timeline" in sys.argv[1:])

@@ -867,8 +867,16 @@ int floe_stage_channels(const floe_half* host_gd, int d, int f, const int32_t* i
     if (d <= 0 || f <= 0 || capacity_rows < 0) return FLOE_EINVAL;
     if (d % 4 != 0) return FLOE_ESHAPE;
     if (!aligned(host_gd, 16) || !aligned(hbm_dst, 16)) return FLOE_EINVAL;
-    void* dev_view = nullptr;
-    FLOE_HIP(hipHostGetDevicePointer(&dev_view, const_cast<floe_half*>(host_gd), 0));
+    // the device view of the pinned matrix; callers stage from the same few matrices over and over
+    static thread_local const floe_half* last_host = nullptr;
+    static thread_local void* last_dev = nullptr;
+    if (host_gd != last_host) {
+        void* dev_view = nullptr;
+        FLOE_HIP(hipHostGetDevicePointer(&dev_view, const_cast<floe_half*>(host_gd), 0));
+        last_host = host_gd;
+        last_dev = dev_view;
+    }
+    void* dev_view = last_dev;
     hipStream_t st = (hipStream_t)side_stream;
     FLOE_LAUNCH(FLOE_KERNEL_STAGE, st, launch_stage(static_cast<const h16*>(dev_view), d, f, idx, count, capacity_rows,
                           reinterpret_cast<h16*>(hbm_dst), overflow, st));
