@@ -935,7 +935,7 @@ def bench_batch(args, np, torch, S, FL, dev):
         del L
     print(json.dumps({"metric": "us per MoE layer-token for decode batches", "value": out[0]["us_per_layer_token"], "unit": "us",
                       "n_gpus": 1, "higher_is_better": False, "data": "synthetic",
-                      "config": {"workload": "BASELINE configs[2] (T=1,4,16) and configs[4] (T=1,8,32), cache-hot weights, HIP-graph replay"},
+                      "config": {"workload": "BASELINE configs[2] (T=1,4,16,64) and configs[4] (T=1,8,32,128), one layer replayed (weights may sit in the last-level cache), HIP-graph replay"},
                       "results": out}), flush=True)
 
 
