@@ -128,7 +128,7 @@ __device__ __forceinline__ h16x8 as_h8(const uint32_t (&r)[4]) {
 }
 
 template <int BITS, int UPC, bool G32, int NTPAD, int TILES>
-__global__ __launch_bounds__(kMfmaThreads) void up_gemv_mfma_kernel(const DevExpert* __restrict__ table,
+__global__ __launch_bounds__(kMfmaThreads, BITS == 3 ? 4 : 1) void up_gemv_mfma_kernel(const DevExpert* __restrict__ table,
                                                                      const TokenGroup* __restrict__ groups,
                                                                      const int32_t* __restrict__ n_groups,
                                                                      const h16* __restrict__ x, int slots,
@@ -417,13 +417,23 @@ __global__ __launch_bounds__(kMfmaThreads) void up_gemv_mfma_kernel(const DevExp
 
     static_assert(NB % 2 == 0, "units per channel must be a multiple of 16");
     FLOE_TL(3);
-    Block b0, b1;
-    load_block(b0, 0);
-    for (int blk = 0; blk < NB; blk += 2) {
-        load_block(b1, blk + 1);
-        compute_block(b0, blk);
-        if (blk + 2 < NB) load_block(b0, blk + 2);
-        compute_block(b1, blk + 1);
+    if constexpr (kOwnWords) {
+        // one block at a time: sixteen waves per compute unit (128 registers each) cover the round trips instead
+        Block b0;
+#pragma unroll 1
+        for (int blk = 0; blk < NB; ++blk) {
+            load_block(b0, blk);
+            compute_block(b0, blk);
+        }
+    } else {
+        Block b0, b1;
+        load_block(b0, 0);
+        for (int blk = 0; blk < NB; blk += 2) {
+            load_block(b1, blk + 1);
+            compute_block(b0, blk);
+            if (blk + 2 < NB) load_block(b0, blk + 2);
+            compute_block(b1, blk + 1);
+        }
     }
 
     FLOE_TL(4);
