@@ -100,7 +100,7 @@ int floe_profile_kernel(int kernel_id, void* start_event, void* stop_event);
  *                            HBM reads of kernels that run beside the copy.
  *   FLOE_TUNE_GROUPED_GEMV   decode batches (T >= 2; INT2 g64, INT3 / INT4 g32 or g64; d 1024, 2048 or 4096): whether the
  *                            tokens routed to one expert share one pass over its codes on the matrix cores:
- *                            0 = where measurement says it pays (about two tokens per expert; six for INT3),
+ *                            0 = where measurement says it pays (about two tokens per expert; three to four for INT3),
  *                            1 = whenever the shape allows, 2 = never (one pass per (token, slot)).
  * Process-wide.  Workspace sizes depend on FLOE_TUNE_UNION_KERNELS and FLOE_TUNE_GROUPED_GEMV: do not change them
  * between a *_workspace_bytes query and the decode call that uses the workspace.  Unknown key or value: FLOE_EINVAL.

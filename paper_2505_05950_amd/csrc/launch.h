@@ -78,7 +78,7 @@ inline int mfma_max_groups(int n_all, int n_tasks) {
 }
 // Grouping pays once experts see about two tokens each; below that the per-token kernels read the same bytes.  The
 // INT3 form is bound by its unpacking and by one round trip per eight units on short channels, not by the bytes: it
-// needs about six tokens per expert before it beats the per-token kernel.  grouped_gemv_mode: 0 = this rule,
+// needs three to four tokens per expert before it beats the per-token kernel.  grouped_gemv_mode: 0 = this rule,
 // 1 = whenever the shape allows, 2 = never (floe_tuning).
 int grouped_gemv_mode();
 void set_grouped_gemv_mode(int m);
@@ -86,7 +86,7 @@ inline bool mfma_batch_pays(int n_all, int n_tasks, int bits) {
     const int mode = grouped_gemv_mode();
     if (mode == 1) return true;
     if (mode == 2) return false;
-    return n_tasks >= (bits == 3 ? 6 : 2) * n_all;
+    return bits == 3 ? 2 * n_tasks >= 7 * n_all : n_tasks >= 2 * n_all;
 }
 hipError_t launch_group_tokens(const int32_t* task_expert, int n_tasks, int n_all, int chunk, TokenGroup* groups,
                                int32_t* n_groups, hipStream_t stream, int32_t* order = nullptr);

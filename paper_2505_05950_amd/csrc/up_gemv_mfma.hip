@@ -566,6 +566,12 @@ hipError_t launch_group_tokens(const int32_t* task_expert, int n_tasks, int n_al
     return hipGetLastError();
 }
 
+// codes, scales and zeros of the channels one workgroup covers per block (8 waves x TILES tiles of 16 channels)
+template <int BITS, int UPC, bool G32, int TILES>
+constexpr size_t ch_per_wg_bytes() {
+    return (size_t)(8 * 16 * TILES) * ((size_t)UPC * BITS * 8 + (size_t)UPC * (G32 ? 2 : 1) * 4);
+}
+
 template <int BITS, int UPC, bool G32, int NTPAD>
 static hipError_t launch_mfma_inst(int max_groups, hipStream_t stream, const DevExpert* table, const TokenGroup* groups,
                                    const int32_t* n_groups, const h16* x, int slots, float* v, const float* task_tau,
@@ -592,7 +598,13 @@ static hipError_t launch_mfma_inst(int max_groups, hipStream_t stream, const Dev
     const int wg_per_cu = lds > 80 * 1024 ? 1 : 2;  // what the fragments in LDS leave room for
     int want = (wg_per_cu * num_cus() + est_groups - 1) / est_groups;
     want = want < 1 ? 1 : (want > n_cblocks ? n_cblocks : want);
-    const int per_wg = (n_cblocks + want - 1) / want;
+    int per_wg = (n_cblocks + want - 1) / want;
+    // Short blocks (small d and f): one per workgroup, so that there are more workgroups than the chip holds at once
+    // and the fragments of the later ones are prepared while the earlier ones stream (measured at d = 2048, f = 1408,
+    // INT3: 145 us per layer call against 157 us at T = 32, 293 against 318 us at T = 128; with the 328 KB blocks of
+    // d = 4096 fewer, longer workgroups stay faster).
+    constexpr size_t block_bytes = (size_t)ch_per_wg_bytes<BITS, UPC, G32, TILES>();
+    if (block_bytes < 192 * 1024) per_wg = 1;
     const dim3 grid((n_cblocks + per_wg - 1) / per_wg, max_groups);
     up_gemv_mfma_kernel<BITS, UPC, G32, NTPAD, TILES><<<grid, dim3(kMfmaThreads), lds, stream>>>(table, groups, n_groups, x,
                                                                                                  slots, v, task_tau,
