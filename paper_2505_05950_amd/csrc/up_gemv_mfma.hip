@@ -462,39 +462,43 @@ __global__ __launch_bounds__(kMfmaThreads, BITS == 3 ? 4 : 1) void up_gemv_mfma_
 
 // ---------------------------------------------------------------------------------------------------
 // Grouping: for every expert the ascending list of tasks (token, slot) routed to it, cut into chunks of
-// `chunk` tasks.  One workgroup of 16 waves; a wave owns experts wave, wave + 16, ... and walks the task list
-// 64 tasks at a time: the lanes compare, a ballot gives the matches and a lane's place among them.
-// Deterministic (ascending expert, ascending task).  The task ids pass through LDS in tiles.
+// `chunk` tasks.  One workgroup of 16 waves, a thread per task.  Deterministic (ascending expert, ascending task).
 // order (optional): all tasks in that same order, i.e. sorted by expert (see gate_down.hip: workgroups of tasks that
 // share an expert are launched next to each other so that they share the rows they both selected in the L2).
 // ---------------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(1024) void group_tokens_kernel(const int32_t* __restrict__ task_expert, int n_tasks,
                                                             int n_all, int chunk, TokenGroup* __restrict__ groups,
                                                             int32_t* __restrict__ n_groups, int32_t* __restrict__ order) {
-    constexpr int kTile = 4096;
+    // A thread per task, 1024 tasks (16 waves of 64) at a time.  A task's place in its expert's list is
+    //   (tasks of that expert in earlier tiles) + (in earlier waves of this tile) + (in lower lanes of this wave),
+    // the last found by ballots over the distinct experts of the wave.  Every wave then stores its 64 tasks with two
+    // instructions; written expert by expert instead, the stores had one or two lanes each and their number (not the
+    // arithmetic) set the kernel's time.
     constexpr int kWaves = 16;
-    __shared__ int first_group[1024 + 64 + 1];  // n_all <= 1088 (1024 routed + 64 shared)
-    __shared__ int count[1024 + 64];
-    __shared__ int first_task[1024 + 64 + 1];   // tasks of the experts before this one (for `order`)
-    __shared__ int tile[kTile];
+    constexpr int kTile = kWaves * kWave;
+    constexpr int kMaxExperts = 1024 + 64;  // 1024 routed + 64 shared
+    __shared__ int first_group[kMaxExperts + 1];
+    __shared__ int first_task[kMaxExperts + 1];  // tasks of the experts before this one (for `order`)
+    __shared__ int count[kMaxExperts];           // tasks per expert; in pass 2 the tasks placed by earlier tiles
+    __shared__ __align__(16) uint8_t in_wave[kWaves][kMaxExperts];  // tasks of an expert inside one wave's 64 tasks of the tile
     const int tid = threadIdx.x;
     const int wave = tid >> 6, lane = tid & 63;
     const unsigned long long below = (1ull << lane) - 1ull;
+    auto expert_of = [&](int task) {
+        const int e = task < n_tasks ? task_expert[task] : -1;
+        return (unsigned)e < (unsigned)n_all ? e : -1;  // an id outside the table belongs to no group
+    };
+    const bool one_tile = n_tasks <= kTile;  // the common case: the expert read in pass 1 serves pass 2 as well
     // pass 1: tasks per expert
-    for (int e = tid; e < n_all; e += 1024) count[e] = 0;
+    for (int e = tid; e < n_all; e += kTile) count[e] = 0;
+    __syncthreads();
+    int mine = -1;
     for (int base = 0; base < n_tasks; base += kTile) {
-        const int n = min(kTile, n_tasks - base);
-        __syncthreads();
-        for (int i = tid; i < n; i += 1024) tile[i] = task_expert[base + i];
-        __syncthreads();
-        for (int e = wave; e < n_all; e += kWaves) {
-            int c = 0;
-            for (int i0 = 0; i0 < n; i0 += kWave) c += __popcll(__ballot(i0 + lane < n && tile[i0 + lane] == e));
-            if (lane == 0) count[e] += c;  // only this wave touches count[e]
-        }
+        mine = expert_of(base + tid);
+        if (mine >= 0) atomicAdd(&count[mine], 1);  // integer adds in LDS: the order does not matter
     }
     __syncthreads();
-    for (int e = tid; e < n_all; e += 1024) first_group[e + 1] = (count[e] + chunk - 1) / chunk;
+    for (int e = tid; e < n_all; e += kTile) first_group[e + 1] = (count[e] + chunk - 1) / chunk;
     __syncthreads();
     if (wave == 0) {  // prefix sums over the experts, 64 at a time
         int run_g = 0, run_t = 0;
@@ -521,35 +525,52 @@ __global__ __launch_bounds__(1024) void group_tokens_kernel(const int32_t* __res
         }
     }
     __syncthreads();
-    // group headers
-    for (int e = wave; e < n_all; e += kWaves) {
+    // group headers; count[] then becomes the number of tasks that earlier tiles placed
+    for (int e = tid; e < n_all; e += kTile) {
         const int g0 = first_group[e], ng = first_group[e + 1] - g0, c = count[e];
-        for (int g = lane; g < ng; g += kWave) {
+        for (int g = 0; g < ng; ++g) {
             groups[g0 + g].expert = e;
             groups[g0 + g].n = min(chunk, c - g * chunk);
         }
+        count[e] = 0;
     }
     // pass 2: the tasks, in ascending order, into their chunks
     for (int base = 0; base < n_tasks; base += kTile) {
-        const int n = min(kTile, n_tasks - base);
-        __syncthreads();
-        for (int i = tid; i < n; i += 1024) tile[i] = task_expert[base + i];
-        __syncthreads();
-        for (int e = wave; e < n_all; e += kWaves) {
-            // position of the first task of this tile among the expert's tasks: what earlier tiles held (count[] is
-            // re-used as that running position; the totals went into the headers)
-            int k = base == 0 ? 0 : count[e];
-            for (int i0 = 0; i0 < n; i0 += kWave) {
-                const bool match = i0 + lane < n && tile[i0 + lane] == e;
+        for (int i = tid; i < kWaves * kMaxExperts / 4; i += kTile) reinterpret_cast<uint32_t*>(&in_wave[0][0])[i] = 0u;
+        __syncthreads();  // in_wave cleared (and, the first time, the headers' reads of count[] are over)
+        if (!one_tile) mine = expert_of(base + tid);
+        int rank = 0;
+        {
+            unsigned long long todo = __ballot(mine >= 0);
+            while (todo) {  // once per distinct expert among the wave's tasks
+                const int e = __shfl(mine, __ffsll((long long)todo) - 1, kWave);
+                const bool match = mine == e;
                 const unsigned long long m = __ballot(match);
                 if (match) {
-                    const int pos = k + __popcll(m & below);
-                    groups[first_group[e] + pos / chunk].task[pos % chunk] = base + i0 + lane;
-                    if (order) order[first_task[e] + pos] = base + i0 + lane;
+                    rank = __popcll(m & below);
+                    if (rank == 0) in_wave[wave][e] = (uint8_t)__popcll(m);
                 }
-                k += __popcll(m);
+                todo &= ~m;
             }
-            if (lane == 0) count[e] = k;
+        }
+        __syncthreads();
+        if (mine >= 0) {
+            int pos = count[mine] + rank;
+            for (int w = 0; w < wave; ++w) pos += in_wave[w][mine];
+            const int task = base + tid;
+            groups[first_group[mine] + pos / chunk].task[pos % chunk] = task;
+            if (order) order[first_task[mine] + pos] = task;
+        }
+        if (!one_tile) {
+            __syncthreads();  // every read of count[] for this tile is over
+            for (int e = tid; e < n_all; e += kTile) {
+                int c = count[e];
+#pragma unroll
+                for (int w = 0; w < kWaves; ++w) c += in_wave[w][e];
+                count[e] = c;
+            }
+            // the next tile's first barrier orders these writes before its reads; its clearing of in_wave needs one more
+            __syncthreads();
         }
     }
 }

@@ -180,6 +180,10 @@ def test_layer_batches_through_the_matrix_core_gemv():
         _run_layer_case(41, 5, 2048, 333, 3, 32, 6, 1, 2, False, 24, 85)
         _run_layer_case(42, 5, 1024, 600, 3, 64, 3, 0, 1, True, 20, 70)
         _run_layer_case(43, 5, 4096, 130, 3, 32, 2, 0, 2, True, 5, 60)
+        # more (token, slot) tasks than the grouping kernel takes at a time (1024): 300 tokens x (4 routed + 1 shared),
+        # and one that fills a tile and leaves a ragged second one with few experts (many groups per expert)
+        _run_layer_case(44, 5, 1024, 320, 4, 32, 20, 1, 4, False, 300, 70)
+        _run_layer_case(45, 3, 1024, 200, 2, 64, 3, 0, 2, True, 530, 60)
     finally:
         F.floe_tuning(F.TUNE_GROUPED_GEMV, 0)
 
