@@ -92,12 +92,13 @@ __global__ __launch_bounds__(kFusedThreads, fused_wgs_per_cu) void fused_ffn_ker
     constexpr int NV = d / 512;           // uint4 per lane of a gate column / down row
     constexpr int kQ = kPasses * CPW;     // queue capacity = channels per producer
     static_assert(kDepth >= 1 && kDepth <= kPasses, "depth of the load pipeline");
-    __shared__ float plog[16];
+    __shared__ float plog[32];                  // router: two partial dot products per expert
     __shared__ DevExpert tab[32];
     __shared__ float taus[32];
     __shared__ int qj[kFusedProducers][kQ];     // selected channel, -1 = not written yet
     __shared__ float qh[kFusedProducers][kQ];   // its v times the routing weight
     __shared__ int done[kFusedProducers];
+    __shared__ int expert_of_queue[kFusedProducers];  // the expert its producer picked (-1 = not yet), for the consumers
     __shared__ int n_sel;
     __shared__ float yred[kFusedConsumers][d];
     __shared__ uint4 xlds[d / 8];               // the token, for the consumers' gate dot products
@@ -117,34 +118,75 @@ __global__ __launch_bounds__(kFusedThreads, fused_wgs_per_cu) void fused_ffn_ker
     const int slot = task - t * map.slots;
     const h16* xt = x + (size_t)t * d;
     for (int i = tid; i < kFusedProducers * kQ; i += kFusedThreads) (&qj[0][0])[i] = -1;
-    if (tid < kFusedProducers) done[tid] = 0;
+    if (tid < kFusedProducers) {
+        done[tid] = 0;
+        expert_of_queue[tid] = -1;
+    }
     if (tid == 0) n_sel = 0;
     for (int i = tid; i < d / 8; i += kFusedThreads) xlds[i] = reinterpret_cast<const uint4*>(xt)[i];
     FLOE_TL(0);
 
     const bool producer = wave < kFusedProducers;
     const int u = lane % UPC, sub = CPW == 1 ? 0 : lane / UPC;
-    DevExpert e;
-    float tau;
+    DevExpert e{};
+    float tau = 0.0f;
     Pick16 pick{};
     int ex = 0;
     if (ROUTED) {
-        // ---- S1 in place (as in the routed GEMV kernel): all waves share the router's dot products
+        // ---- S1 in place.  Every workgroup of the launch repeats it, so its cost is the length of the prologue of all of
+        // them: the router rows are requested first (half a row per item, dealt over all waves), the token comes from the copy in
+        // LDS once the barrier has passed (read from memory by every wave it doubled the bytes a workgroup pulls through
+        // the L2), and only the producers work out the pick: they need it to request codes, while a consumer needs
+        // the expert's gate/down address no earlier than its first queue entry and would only take issue slots from the
+        // two producers on its SIMD.
         if (tid < ro.n_experts + ro.n_shared) {
             tab[tid] = ro.table[tid];
             taus[tid] = ro.tau[(size_t)t * ro.tau_stride_t + tid];
         }
-        route_logits_to_lds<d, kFusedThreads / 64, 1>(xt, ro, wave, lane, plog);
+        constexpr int kParts = 2, NVR = d / 512 / kParts;
+        constexpr int NW = kFusedThreads / 64;
+        constexpr int kItems = (16 * kParts + NW - 1) / NW;  // items a wave may have to take (<= 16 experts)
+        const int n_items = ro.n_experts * kParts;
+        uint4 rw[kItems][NVR];
+#pragma unroll
+        for (int q = 0; q < kItems; ++q) {
+            const int it = wave + q * NW;
+            if (it >= n_items) break;  // wave-uniform
+            const uint4* wq = reinterpret_cast<const uint4*>(ro.router_cm + (size_t)(it / kParts) * d);
+#pragma unroll
+            for (int r = 0; r < NVR; ++r) rw[q][r] = wq[((it % kParts) * NVR + r) * kWave + lane];
+        }
+        __syncthreads();  // xlds, queues and flags are set up
+#pragma unroll
+        for (int q = 0; q < kItems; ++q) {
+            const int it = wave + q * NW;
+            if (it >= n_items) break;
+            float acc = 0.0f;
+#pragma unroll
+            for (int r = 0; r < NVR; ++r) {
+                const uint4 xr = xlds[((it % kParts) * NVR + r) * kWave + lane];
+                acc = dot2(xr.x, rw[q][r].x, acc);
+                acc = dot2(xr.y, rw[q][r].y, acc);
+                acc = dot2(xr.z, rw[q][r].z, acc);
+                acc = dot2(xr.w, rw[q][r].w, acc);
+            }
+            acc = group_reduce_sum_to_last<64>(acc);
+            if (lane == kWave - 1) plog[it] = acc;
+        }
         FLOE_TL(1);
         __syncthreads();
         ex = ro.n_experts + (slot - ro.top_k);  // a shared expert
-        if (ro.top_k > 0) {
-            const float lg = (lane & 15) < ro.n_experts ? plog[lane & 15] : 0.0f;
-            pick = route_pick_wave16(lg, lane, ro.n_experts, ro.top_k);
-            if (slot < ro.top_k) ex = __builtin_amdgcn_readlane(pick.id, slot);
+        if (producer) {
+            if (ro.top_k > 0) {
+                const int l16 = lane & 15;
+                const float lg = l16 < ro.n_experts ? plog[2 * l16] + plog[2 * l16 + 1] : 0.0f;
+                pick = route_pick_wave16(lg, lane, ro.n_experts, ro.top_k);
+                if (slot < ro.top_k) ex = __builtin_amdgcn_readlane(pick.id, slot);
+            }
+            if (lane == 0) lds_poke(&expert_of_queue[wave], ex);
+            e = tab[ex];
+            tau = taus[ex];
         }
-        e = tab[ex];
-        tau = taus[ex];
     } else {
         e = task_expert_of(map, task);
         tau = task_tau[task];
@@ -299,6 +341,11 @@ __global__ __launch_bounds__(kFusedThreads, fused_wgs_per_cu) void fused_ffn_ker
         // ================================================================ consumer: queue -> chunk -> y
         const int c = wave - kFusedProducers;   // consumer id: serves queue c / kFusedCpp, entries c % kFusedCpp, + kFusedCpp, ...
         const int qc = c / kFusedCpp;
+        if (ROUTED) {  // the producer of this queue publishes its expert right after the pick
+            int exq;
+            while ((exq = __builtin_amdgcn_readfirstlane(lds_peek(&expert_of_queue[qc]))) < 0) __builtin_amdgcn_s_sleep(4);
+            e = tab[exq];
+        }
         float acc[8 * NV];
 #pragma unroll
         for (int i = 0; i < 8 * NV; ++i) acc[i] = 0.0f;
