@@ -144,7 +144,10 @@ LayerWs layer_ws(const floe_layer* L, int T) {
     w.expert_off = o; o += align_up((size_t)w.n_tasks * 4);
     w.weight_off = o; o += align_up((size_t)w.n_tasks * 4);
     w.tau_off = o;    o += align_up((size_t)w.n_tasks * 4);
-    w.logit_off = o;  o += router_split_pays(L->n_experts, L->s.d, T) ? align_up((size_t)T * L->n_experts * 4) : 0;
+    // router logits in memory: between the two launches of a split router, or in front of a fused kernel that picks in place
+    const bool logits_kept = router_split_pays(L->n_experts, L->s.d, T) ||
+                             (w.fused_passes && fused_route_mode(L->n_experts, L->top_k, L->n_shared) == 1);
+    w.logit_off = o;  o += logits_kept ? align_up((size_t)T * L->n_experts * 4) : 0;
     w.count_off = o;  o += align_up((size_t)w.n_tasks * count_parts * 4);
     w.mask_off = o;   o += align_up((size_t)w.n_tasks * mask_words_per_task(L->s.f) * 4);
     w.groups_off = o; o += align_up((size_t)mfma_max_groups(L->n_experts + L->n_shared, w.n_tasks) * sizeof(TokenGroup));
@@ -213,7 +216,7 @@ int layer_lists(const floe_layer* L, const LayerWs& w, char* base, const h16* xh
     map.task_table = task_table;
     map.slots = L->top_k + L->n_shared;
     if (route_in_place_ok(L->s.d, L->s.bits, L->s.group, L->n_experts, L->top_k, L->n_shared)) {
-        RouteArgs ro;
+        RouteArgs ro{};
         ro.router_cm = reinterpret_cast<const h16*>(L->router_cm);
         ro.tau = L->tau;
         ro.tau_stride_t = L->tau_stride_t;
@@ -544,9 +547,11 @@ int floe_moe_layer_decode(const floe_layer* L, const floe_half* x, int T, floe_h
     int nblk = w.nblk, count_parts = 0;
     if (w.fused_passes && !batch_mfma) {
         // small batch: [(router +) up GEMV + selection + gate/down on the workgroup's own channels] -> [combine];
-        // with INT2 and <= 16 experts the router runs inside the same kernel, otherwise in one of its own before it
-        const bool in_place = route_in_place_ok(L->s.d, L->s.bits, L->s.group, L->n_experts, L->top_k, L->n_shared);
-        RouteArgs ro;
+        // with <= 16 experts the router runs inside the same kernel; with <= 64 its dot products run in a kernel in front
+        // and softmax / top-k inside; otherwise the whole router runs in front
+        const int route_mode = fused_route_mode(L->n_experts, L->top_k, L->n_shared);
+        const bool in_place = route_mode != 0;
+        RouteArgs ro{};
         ro.router_cm = reinterpret_cast<const h16*>(L->router_cm);
         ro.tau = L->tau;
         ro.tau_stride_t = L->tau_stride_t;
@@ -554,9 +559,14 @@ int floe_moe_layer_decode(const floe_layer* L, const floe_half* x, int T, floe_h
         ro.table = static_cast<const DevExpert*>(L->dev_table);
         ro.task_table = task_table;
         ro.task_expert = task_expert; ro.task_weight = task_weight; ro.task_tau = task_tau;
-        if (!in_place) {
+        if (route_mode == 0) {
             const RouterArgs ra = router_args(L, w, base, xh);
             FLOE_LAUNCH(FLOE_KERNEL_ROUTER, st, launch_router(ra, T, st));
+        } else if (route_mode == 1) {
+            const RouterArgs ra = router_args(L, w, base, xh);
+            if (!ra.logits) return FLOE_EWORKSPACE;
+            FLOE_LAUNCH(FLOE_KERNEL_ROUTER, st, launch_router_logits(ra, T, st));
+            ro.logits = ra.logits;
         }
         FusedArgs a{};
         a.map = map; a.x = xh; a.route = in_place ? &ro : nullptr; a.task_tau = task_tau; a.task_scale = task_weight;
@@ -598,7 +608,7 @@ int floe_moe_layer_decode(const floe_layer* L, const floe_half* x, int T, floe_h
     } else if (mask_ok && !batch_mfma &&
                route_in_place_ok(L->s.d, L->s.bits, L->s.group, L->n_experts, L->top_k, L->n_shared)) {
         // larger batches of shapes without a matrix-core path: [router + up GEMV + mask] -> [compaction + gate/down]
-        RouteArgs ro;
+        RouteArgs ro{};
         ro.router_cm = reinterpret_cast<const h16*>(L->router_cm);
         ro.tau = L->tau;
         ro.tau_stride_t = L->tau_stride_t;

@@ -77,7 +77,7 @@ __device__ __forceinline__ void lds_piece_request(const void* lds_ptr, u32x4& q)
 }
 __device__ __forceinline__ void lds_piece_arrived(u32x4& q) { asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(q) : : "memory"); }
 
-// ROUTED: the workgroup routes in place (INT2, <= 16 experts); otherwise the task's expert comes from `map`, its
+// ROUTED: the workgroup routes in place (<= 16 experts, or <= 64 with the logits given); otherwise the task's expert comes from `map`, its
 // threshold from task_tau and its output scale from task_scale (nullptr = 1).
 // kPasses channels-per-wave passes per producer, kDepth of them in flight.  v_out (optional): v[task][f].
 template <int BITS, int UPC, bool G32, bool ROUTED, int kPasses, int kDepth>
@@ -93,8 +93,8 @@ __global__ __launch_bounds__(kFusedThreads, fused_wgs_per_cu) void fused_ffn_ker
     constexpr int kQ = kPasses * CPW;     // queue capacity = channels per producer
     static_assert(kDepth >= 1 && kDepth <= kPasses, "depth of the load pipeline");
     __shared__ float plog[32];                  // router: two partial dot products per expert
-    __shared__ DevExpert tab[32];
-    __shared__ float taus[32];
+    __shared__ DevExpert tab[kFusedMaxRouted + 16];
+    __shared__ float taus[kFusedMaxRouted + 16];
     __shared__ int qj[kFusedProducers][kQ];     // selected channel, -1 = not written yet
     __shared__ float qh[kFusedProducers][kQ];   // its v times the routing weight
     __shared__ int done[kFusedProducers];
@@ -143,44 +143,53 @@ __global__ __launch_bounds__(kFusedThreads, fused_wgs_per_cu) void fused_ffn_ker
             tab[tid] = ro.table[tid];
             taus[tid] = ro.tau[(size_t)t * ro.tau_stride_t + tid];
         }
-        constexpr int kParts = 2, NVR = d / 512 / kParts;
-        constexpr int NW = kFusedThreads / 64;
-        constexpr int kItems = (16 * kParts + NW - 1) / NW;  // items a wave may have to take (<= 16 experts)
-        const int n_items = ro.n_experts * kParts;
-        uint4 rw[kItems][NVR];
+        float lg = 0.0f;  // producers: the logit of the expert this lane stands for
+        if (ro.logits) {
+            // the dot products were formed by a kernel in front (more than 16 experts: a workgroup that repeated them
+            // would pull the whole router matrix through its L2 port); lane e holds expert e
+            if (producer && lane < ro.n_experts) lg = ro.logits[(size_t)t * ro.n_experts + lane];
+            __syncthreads();  // xlds, queues, flags and the table are set up
+        } else {
+            constexpr int kParts = 2, NVR = d / 512 / kParts;
+            constexpr int NW = kFusedThreads / 64;
+            constexpr int kItems = (16 * kParts + NW - 1) / NW;  // items a wave may have to take (<= 16 experts)
+            const int n_items = ro.n_experts * kParts;
+            uint4 rw[kItems][NVR];
 #pragma unroll
-        for (int q = 0; q < kItems; ++q) {
-            const int it = wave + q * NW;
-            if (it >= n_items) break;  // wave-uniform
-            const uint4* wq = reinterpret_cast<const uint4*>(ro.router_cm + (size_t)(it / kParts) * d);
+            for (int q = 0; q < kItems; ++q) {
+                const int it = wave + q * NW;
+                if (it >= n_items) break;  // wave-uniform
+                const uint4* wq = reinterpret_cast<const uint4*>(ro.router_cm + (size_t)(it / kParts) * d);
 #pragma unroll
-            for (int r = 0; r < NVR; ++r) rw[q][r] = wq[((it % kParts) * NVR + r) * kWave + lane];
-        }
-        __syncthreads();  // xlds, queues and flags are set up
-#pragma unroll
-        for (int q = 0; q < kItems; ++q) {
-            const int it = wave + q * NW;
-            if (it >= n_items) break;
-            float acc = 0.0f;
-#pragma unroll
-            for (int r = 0; r < NVR; ++r) {
-                const uint4 xr = xlds[((it % kParts) * NVR + r) * kWave + lane];
-                acc = dot2(xr.x, rw[q][r].x, acc);
-                acc = dot2(xr.y, rw[q][r].y, acc);
-                acc = dot2(xr.z, rw[q][r].z, acc);
-                acc = dot2(xr.w, rw[q][r].w, acc);
+                for (int r = 0; r < NVR; ++r) rw[q][r] = wq[((it % kParts) * NVR + r) * kWave + lane];
             }
-            acc = group_reduce_sum_to_last<64>(acc);
-            if (lane == kWave - 1) plog[it] = acc;
+            __syncthreads();  // xlds, queues and flags are set up
+#pragma unroll
+            for (int q = 0; q < kItems; ++q) {
+                const int it = wave + q * NW;
+                if (it >= n_items) break;
+                float acc = 0.0f;
+#pragma unroll
+                for (int r = 0; r < NVR; ++r) {
+                    const uint4 xr = xlds[((it % kParts) * NVR + r) * kWave + lane];
+                    acc = dot2(xr.x, rw[q][r].x, acc);
+                    acc = dot2(xr.y, rw[q][r].y, acc);
+                    acc = dot2(xr.z, rw[q][r].z, acc);
+                    acc = dot2(xr.w, rw[q][r].w, acc);
+                }
+                acc = group_reduce_sum_to_last<64>(acc);
+                if (lane == kWave - 1) plog[it] = acc;
+            }
+            FLOE_TL(1);
+            __syncthreads();
+            const int l16 = lane & 15;
+            if (producer && l16 < ro.n_experts) lg = plog[2 * l16] + plog[2 * l16 + 1];
         }
-        FLOE_TL(1);
-        __syncthreads();
         ex = ro.n_experts + (slot - ro.top_k);  // a shared expert
         if (producer) {
             if (ro.top_k > 0) {
-                const int l16 = lane & 15;
-                const float lg = l16 < ro.n_experts ? plog[2 * l16] + plog[2 * l16 + 1] : 0.0f;
-                pick = route_pick_wave16(lg, lane, ro.n_experts, ro.top_k);
+                pick = ro.logits ? route_pick_wave64(lg, lane, ro.n_experts, ro.top_k)
+                                 : route_pick_wave16(lg, lane, ro.n_experts, ro.top_k);
                 if (slot < ro.top_k) ex = __builtin_amdgcn_readlane(pick.id, slot);
             }
             if (lane == 0) lds_poke(&expert_of_queue[wave], ex);
@@ -451,11 +460,10 @@ static hipError_t fused_launch_shape(const FusedArgs& a, int gshift, hipStream_t
         default: return hipErrorInvalidValue;                                   \
     }
     if (a.route) {
-        if constexpr (BITS == 2 && !G32) {
-            FLOE_FUSED_PASSES(true)
-        } else {
+        if (a.route->top_k < 1 || a.route->top_k + a.route->n_shared > 16 ||
+            a.route->n_experts > (a.route->logits ? kFusedMaxRouted : 16))
             return hipErrorInvalidValue;
-        }
+        FLOE_FUSED_PASSES(true)
     } else {
         FLOE_FUSED_PASSES(false)
     }

@@ -36,14 +36,23 @@ inline bool route_in_place_ok(int d, int bits, int group, int n_experts, int top
            top_k + n_shared <= 16;
 }
 
+// How the fused kernel gets its routing: 2 = all of S1 inside it (<= 16 experts), 1 = softmax and top-k inside it on
+// logits that router_logits computed in front (<= 64 experts: repeated by every workgroup the dot products would cost
+// more than that launch), 0 = a router kernel in front writes the task table.
+inline int fused_route_mode(int n_experts, int top_k, int n_shared) {
+    if (top_k < 1 || top_k + n_shared > 16) return 0;
+    return n_experts <= 16 ? 2 : (n_experts <= 64 ? 1 : 0);
+}
+
 // (S1 +) S2-S5 of a small decode batch in one kernel (packed shapes, any bit width): every workgroup computes v for
 // its own block of channels, selects among them and runs gate/down on what it selected (fused_ffn.h).
-// With `route` the workgroup also routes in place (shapes of route_in_place_ok); otherwise map / task_tau /
+// With `route` the workgroup also routes in place (fused_route_mode); otherwise map / task_tau /
 // task_scale describe the tasks.  partial[task][blocks][d], wg_count[task][blocks] (selected channels per
 // workgroup), v_out (optional) [task][f].
 constexpr int fused_producers = 4;                          // producer waves per workgroup (+ 2 consumers each)
 constexpr int fused_wgs_per_cu = 1;                         // workgroups per compute unit the block length aims at
 constexpr int fused_passes_long = 28, fused_passes_mid = 14, fused_passes_short = 7;  // channel passes per producer wave
+constexpr int kFusedMaxRouted = 64;       // routed experts a workgroup can pick among in place (one per lane)
 constexpr int kFusedMaxTasks = 16;        // beyond these the partial results outgrow what the fusion saves
 constexpr int kFusedMaxWorkgroups = 2048;
 struct FusedArgs {
@@ -173,6 +182,7 @@ inline bool router_split_pays(int n_experts, int d, int T) {
     return (size_t)n_experts * d * 2 >= (size_t)128 * 1024 && n_experts >= 32 && T <= 4096;
 }
 hipError_t launch_router(const RouterArgs& a, int T, hipStream_t stream);
+hipError_t launch_router_logits(const RouterArgs& a, int T, hipStream_t stream);  // x . W_r only, into a.logits
 
 // stats: (expert, count, weight) per task
 struct SlotStat {

@@ -87,6 +87,48 @@ __device__ __forceinline__ Pick16 route_pick_wave16(float logit, int lane, int n
     }
     return out;
 }
+// The pick for n <= 64 experts (lane e of the wave holds expert e), result laid out like route_pick_wave16's: lane r
+// (< top_k <= 16) receives the r-th pick.  The sum of the exponentials is a DPP tree, as in the stand-alone router's
+// wave-wide selection, so both give the same bits.
+__device__ __forceinline__ Pick16 route_pick_wave64(float logit, int lane, int n, int top_k) {
+    const bool live = lane < n;
+    auto lane_value = [](float v, int l) {
+        return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), l));
+    };
+    float mx = row16_allreduce_max(live ? logit : -INFINITY);
+    mx = fmaxf(fmaxf(lane_value(mx, 0), lane_value(mx, 16)), fmaxf(lane_value(mx, 32), lane_value(mx, 48)));
+    const float p = live ? expf(logit - mx) : 0.0f;
+    Pick16 out;
+    out.sum = wave_allreduce_sum(p);
+    out.p = 0.0f;
+    out.id = 0;
+    float cur = live ? p : -3.0f;
+    for (int r = 0; r < top_k; ++r) {
+        // arg-max with ties to the lower id: inside each row of 16 on the DPP path, then the four row winners (in
+        // ascending id order, so a strict comparison keeps the lower id) through scalar registers
+        float bv = cur;
+        int bi = lane;
+#define FLOE_ARGMAX_STEP(CTRL)                                               \
+    {                                                                        \
+        const float ov = dpp_movf<CTRL>(bv);                                 \
+        const int oi = dpp_movi<CTRL>(bi);                                   \
+        if (ov > bv || (ov == bv && oi < bi)) { bv = ov; bi = oi; }          \
+    }
+        FLOE_ARGMAX_STEP(0x128) FLOE_ARGMAX_STEP(0x124) FLOE_ARGMAX_STEP(0x122) FLOE_ARGMAX_STEP(0x121)
+#undef FLOE_ARGMAX_STEP
+        float wv = lane_value(bv, 0);
+        int wi = __builtin_amdgcn_readlane(bi, 0);
+#pragma unroll
+        for (int row = 1; row < 4; ++row) {
+            const float ov = lane_value(bv, 16 * row);
+            const int oi = __builtin_amdgcn_readlane(bi, 16 * row);
+            if (ov > wv) { wv = ov; wi = oi; }
+        }
+        if (lane == r) { out.p = wv; out.id = wi; }
+        if (lane == wi) cur = -2.0f;  // taken
+    }
+    return out;
+}
 // routing weight of the lane's pick (lane < top_k): p / sum, or that over the sum of the picked ones
 __device__ __forceinline__ float route_weight_wave16(const Pick16& pk, int top_k, int renormalize) {
     const float pw = pk.p / pk.sum;
@@ -114,6 +156,8 @@ __device__ __forceinline__ void route_select_wave16(float logit, int lane, int n
 // What a kernel that routes in place needs (layer path).
 struct RouteArgs {
     const h16* router_cm;     // [n_experts][d]
+    const float* logits;      // nullptr: the kernel forms x . W_r itself (n_experts <= 16); else [T][n_experts], computed
+                              // by a kernel in front (n_experts <= 64)
     const float* tau;         // threshold of (token t, expert e) at tau[t * tau_stride_t + e]
     int32_t tau_stride_t;
     int32_t n_experts, top_k, n_shared, renormalize;

@@ -233,6 +233,25 @@ hipError_t launch_router(const RouterArgs& a, int T, hipStream_t stream) {
     return hipGetLastError();
 }
 
+// Only the dot products, into a.logits [T][n_experts]: for a kernel behind it that does softmax and top-k itself.
+hipError_t launch_router_logits(const RouterArgs& a, int T, hipStream_t stream) {
+    if (T == 0 || a.n_experts == 0) return hipSuccess;
+    if (!a.logits) return hipErrorInvalidValue;
+    int per_token = (a.n_experts + 3) / 4;  // every wave gets at least one expert
+    const int room = 2 * num_cus() / T;
+    per_token = per_token < room ? per_token : (room < 1 ? 1 : room);
+    switch (a.d / 512) {
+#define FLOE_ROUTER_NV(N) \
+    case N: router_logits_kernel<N><<<dim3(per_token, T), dim3(256), 0, stream>>>(a); break;
+        FLOE_ROUTER_NV(1) FLOE_ROUTER_NV(2) FLOE_ROUTER_NV(3) FLOE_ROUTER_NV(4) FLOE_ROUTER_NV(5) FLOE_ROUTER_NV(6)
+        FLOE_ROUTER_NV(7) FLOE_ROUTER_NV(8) FLOE_ROUTER_NV(9) FLOE_ROUTER_NV(10) FLOE_ROUTER_NV(11) FLOE_ROUTER_NV(12)
+        FLOE_ROUTER_NV(13) FLOE_ROUTER_NV(14) FLOE_ROUTER_NV(15) FLOE_ROUTER_NV(16)
+#undef FLOE_ROUTER_NV
+        default: return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
+}
+
 // one wave per task: the lanes share the per-workgroup counts of a fused launch
 __global__ __launch_bounds__(256) void stats_kernel(const int32_t* task_expert, const int32_t* count, int count_parts,
                                                     const float* task_weight, SlotStat* stats, int n_tasks,

@@ -154,10 +154,22 @@ def test_layer_small_batches_through_the_fused_kernel():
     _run_layer_case(22, 3, 4096, 300, 2, 64, 16, 0, 4, True, 2, 60)
     _run_layer_case(23, 3, 4096, 250, 2, 256, 3, 0, 1, False, 2, 0)
     _run_layer_case(24, 3, 1024, 1500, 2, 64, 8, 0, 2, True, 8, 99)
-    # other bit widths and more than 16 experts: the router runs as a kernel of its own in front of the fused one
+    # other bit widths route in place too; more than 16 experts: the router's dot products run in a kernel in front
     _run_layer_case(25, 5, 2048, 1408, 3, 32, 16, 2, 6, False, 2, 85)
     _run_layer_case(26, 5, 1024, 700, 4, 32, 20, 1, 3, True, 3, 70)
     _run_layer_case(27, 3, 4096, 200, 3, 128, 4, 0, 2, True, 1, 50)
+
+
+def test_layer_small_batches_pick_in_place_among_up_to_64_experts():
+    """17 to 64 routed experts and at most 16 (token, slot) tasks: x . W_r is formed by a kernel in front, softmax and
+    top-k run inside the fused kernel with a lane per expert.  64 experts (every lane live), 33 (one live lane in the
+    third row of 16), 17; with and without renormalisation, with shared experts, all three packed widths, top-k up to 8,
+    exactly 16 tasks."""
+    _run_layer_case(51, 5, 2048, 704, 3, 32, 64, 2, 6, False, 1, 85)
+    _run_layer_case(52, 5, 2048, 704, 3, 32, 64, 2, 6, False, 2, 85)
+    _run_layer_case(53, 5, 1024, 500, 2, 64, 33, 1, 4, True, 3, 70)
+    _run_layer_case(54, 3, 4096, 260, 4, 64, 17, 0, 2, True, 5, 60)
+    _run_layer_case(55, 5, 1024, 320, 4, 32, 48, 0, 8, False, 2, 50)
 
 
 def test_layer_with_more_than_64_experts_takes_the_serial_top_k():
