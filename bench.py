@@ -893,7 +893,8 @@ def bench_batch(args, np, torch, S, FL, dev):
             ("configs[2]", 3, 4096, 14336, 2, 64, 8, 0, 2, True, 90, (1, 4, 16, 64)),
             ("configs[4]", 5, 2048, 1408, 3, 32, 64, 2, 6, False, 85, (1, 8, 32, 128))):
         want = [c.split(":") for c in args.batch_cases.split(",") if c]
-        Ts = [T for T in Ts if not want or [name[8], str(T)] in want]
+        if want:  # any batch size may be asked for, not only the ones of the default run
+            Ts = sorted({int(t) for c, t in want if c == name[8]})
         if not Ts:
             continue
         L = make_layer(cfg, d, f, bits, group, n, n_shared, top_k, renorm, pct)

@@ -100,12 +100,22 @@ int floe_profile_kernel(int kernel_id, void* start_event, void* stop_event);
  *                            HBM reads of kernels that run beside the copy.
  *   FLOE_TUNE_GROUPED_GEMV   decode batches (T >= 2; INT2 g64, INT3 / INT4 g32 or g64; d 1024, 2048 or 4096): whether the
  *                            tokens routed to one expert share one pass over its codes on the matrix cores:
- *                            0 = where measurement says it pays (about two tokens per expert; three to four for INT3),
+ *                            0 = where the one-kernel path (FLOE_TUNE_FUSED_TASKS) does not apply and measurement says
+ *                                it pays (about two tokens per expert; three to four for INT3),
  *                            1 = whenever the shape allows, 2 = never (one pass per (token, slot)).
- * Process-wide.  Workspace sizes depend on FLOE_TUNE_UNION_KERNELS and FLOE_TUNE_GROUPED_GEMV: do not change them
+ *   FLOE_TUNE_FUSED_TASKS    up to how many (token, slot) pairs a layer call runs Alg. 1 in one kernel (every workgroup
+ *                            takes a block of channels of one pair through all steps) instead of the batch kernels:
+ *                            0 = the library's rule (16, or four per expert if that is more), else the limit itself
+ *                            (at most 256).
+ * Process-wide.  Workspace sizes depend on FLOE_TUNE_UNION_KERNELS, FLOE_TUNE_GROUPED_GEMV and FLOE_TUNE_FUSED_TASKS: do not change them
  * between a *_workspace_bytes query and the decode call that uses the workspace.  Unknown key or value: FLOE_EINVAL.
  */
-typedef enum { FLOE_TUNE_UNION_KERNELS = 1, FLOE_TUNE_STAGE_WORKGROUPS = 2, FLOE_TUNE_GROUPED_GEMV = 3 } floe_tuning_key;
+typedef enum {
+    FLOE_TUNE_UNION_KERNELS = 1,
+    FLOE_TUNE_STAGE_WORKGROUPS = 2,
+    FLOE_TUNE_GROUPED_GEMV = 3,
+    FLOE_TUNE_FUSED_TASKS = 4
+} floe_tuning_key;
 int floe_tuning(int key, int value);
 
 /* ------------------------------------------------------------------------------------------------

@@ -11,7 +11,7 @@ from .binding import (  # noqa: F401
     floe_layer_workspace_bytes, floe_moe_layer_decode, floe_moe_layer_decode_static, STATIC_SCRATCH_BYTES,
     floe_moe_layer_decode_offloaded, floe_moe_layer_prefetch,
     floe_moe_layer_decode_prefetched, Prefetch, MissPath, PREFETCH_STAT_DTYPE, floe_stage_channels, floe_status_string,
-    words_per_channel, SLOT_STAT_DTYPE, floe_profile_kernel, KERNEL_IDS, floe_tuning, TUNE_UNION_KERNELS, TUNE_STAGE_WORKGROUPS, TUNE_GROUPED_GEMV,
+    words_per_channel, SLOT_STAT_DTYPE, floe_profile_kernel, KERNEL_IDS, floe_tuning, TUNE_UNION_KERNELS, TUNE_STAGE_WORKGROUPS, TUNE_GROUPED_GEMV, TUNE_FUSED_TASKS,
     ChannelCache, floe_channel_cache_load, floe_moe_layer_decode_cached,
     floe_expert_ffn_sparsified, SPARSIFY_UP, SPARSIFY_GATE, SPARSIFY_DOWN,
 )

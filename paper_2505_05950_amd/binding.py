@@ -129,6 +129,7 @@ def floe_profile_kernel(kernel: str, start_event=None, stop_event=None):
 TUNE_UNION_KERNELS = 1
 TUNE_STAGE_WORKGROUPS = 2
 TUNE_GROUPED_GEMV = 3
+TUNE_FUSED_TASKS = 4
 
 
 def floe_tuning(key: int, value: int):

@@ -127,12 +127,15 @@ LayerWs layer_ws(const floe_layer* L, int T) {
     const int slots = L->top_k + L->n_shared;
     w.n_tasks = T * slots;
     w.nblk = gd_blocks(w.n_tasks, L->s.f);
-    w.fused_passes = packed_fast_shape(L->s.d, L->s.bits, L->s.group) ? fused_passes(L->s.d, L->s.f, w.n_tasks) : 0;
-    w.nblk_fused = w.fused_passes ? fused_blocks(L->s.d, L->s.f, w.fused_passes) : 0;
     const int n_all = L->n_experts + L->n_shared;
+    w.fused_passes = packed_fast_shape(L->s.d, L->s.bits, L->s.group)
+                         ? fused_passes(L->s.d, L->s.f, w.n_tasks, fused_task_limit(n_all)) : 0;
+    w.nblk_fused = w.fused_passes ? fused_blocks(L->s.d, L->s.f, w.fused_passes) : 0;
     w.chunk = mfma_chunk(n_all, w.n_tasks);
     w.up = union_plan(L->s.d, L->s.f, w.n_tasks, n_all, w.chunk);
-    w.batch_mfma = T >= 2 && mfma_grouped_shape(L->s.d, L->s.bits, L->s.group) && mfma_batch_pays(n_all, w.n_tasks, L->s.bits);
+    // the grouped up GEMV: when forced, or where the fused kernel does not apply and grouping pays
+    w.batch_mfma = T >= 2 && mfma_grouped_shape(L->s.d, L->s.bits, L->s.group) &&
+                   (grouped_gemv_mode() == 1 || (!w.fused_passes && mfma_batch_pays(n_all, w.n_tasks, L->s.bits)));
     w.use_union = union_kernels_for(n_all, w.n_tasks) != 3 && !L->gd_on_host && T >= 2 && (!w.fused_passes || w.batch_mfma) &&
                   mask_path_ok(L->s.f) && union_shape_ok(L->s.d, L->s.f, w.up);
     int nblk_alloc = w.nblk > w.nblk_fused ? w.nblk : w.nblk_fused;
@@ -275,6 +278,10 @@ int floe_tuning(int key, int value) {
         case FLOE_TUNE_GROUPED_GEMV:
             if (value < 0 || value > 2) return FLOE_EINVAL;
             set_grouped_gemv_mode(value);
+            return FLOE_OK;
+        case FLOE_TUNE_FUSED_TASKS:
+            if (value < 0 || value > kFusedMaxTasks) return FLOE_EINVAL;
+            set_fused_tasks_tuned(value);
             return FLOE_OK;
         case FLOE_TUNE_STAGE_WORKGROUPS:
             if (value < 0 || value > 4096) return FLOE_EINVAL;
@@ -630,7 +637,7 @@ int floe_moe_layer_decode(const floe_layer* L, const floe_half* x, int T, floe_h
         TokenGroup* groups = reinterpret_cast<TokenGroup*>(base + w.groups_off);
         int32_t* n_groups = reinterpret_cast<int32_t*>(base + w.ngroups_off);
         // (only where the grouping kernel runs anyway: on its own it costs what the sharing saves)
-        int32_t* order = (mask_ok && batch_mfma && w.n_tasks > kFusedMaxTasks) ? reinterpret_cast<int32_t*>(base + w.order_off) : nullptr;
+        int32_t* order = (mask_ok && batch_mfma && w.n_tasks > kExpertOrderTasks) ? reinterpret_cast<int32_t*>(base + w.order_off) : nullptr;
         const int n_all = L->n_experts + L->n_shared;
         const int chunk = mfma_chunk(n_all, w.n_tasks);
         if (order || (mask_ok && batch_mfma))

@@ -454,9 +454,12 @@ static hipError_t fused_launch_shape(const FusedArgs& a, int gshift, hipStream_t
                                                                                     a.v_out, a.partial, a.wg_count)
 #define FLOE_FUSED_PASSES(ROUTED)                                               \
     switch (a.passes) {                                                         \
-        case fused_passes_long: FLOE_FUSED_GO(ROUTED, fused_passes_long); break; \
-        case fused_passes_mid: FLOE_FUSED_GO(ROUTED, fused_passes_mid); break;   \
-        case fused_passes_short: FLOE_FUSED_GO(ROUTED, fused_passes_short); break; \
+        case 224: FLOE_FUSED_GO(ROUTED, 224); break;                            \
+        case 112: FLOE_FUSED_GO(ROUTED, 112); break;                            \
+        case 56: FLOE_FUSED_GO(ROUTED, 56); break;                              \
+        case 28: FLOE_FUSED_GO(ROUTED, 28); break;                              \
+        case 14: FLOE_FUSED_GO(ROUTED, 14); break;                              \
+        case 7: FLOE_FUSED_GO(ROUTED, 7); break;                                \
         default: return hipErrorInvalidValue;                                   \
     }
     if (a.route) {

@@ -17,6 +17,10 @@ int num_cus() {
     return n;
 }
 
+static std::atomic<int> g_fused_tasks{0};
+int fused_tasks_tuned() { return g_fused_tasks.load(std::memory_order_relaxed); }
+void set_fused_tasks_tuned(int n) { g_fused_tasks.store(n > 0 ? n : 0, std::memory_order_relaxed); }
+
 hipError_t launch_fused_int2(const FusedArgs& a, hipStream_t stream);
 hipError_t launch_fused_int3(const FusedArgs& a, hipStream_t stream);
 hipError_t launch_fused_int4(const FusedArgs& a, hipStream_t stream);
@@ -26,15 +30,16 @@ int fused_blocks(int d, int f, int passes) {
     return (f + ch - 1) / ch;
 }
 
-// The longest blocks (28 passes per producer wave = 112 channels per workgroup at d = 4096, then 14, then 7) that
-// still give the chip about one workgroup per compute unit.  0 = do not fuse (too many partial results).
-int fused_passes(int d, int f, int n_tasks) {
-    if (n_tasks <= 0 || n_tasks > kFusedMaxTasks) return 0;
-    const int options[3] = {fused_passes_long, fused_passes_mid, fused_passes_short};
-    int pick = fused_passes_short;
-    for (int i = 0; i < 3; ++i) {
-        if ((long long)fused_blocks(d, f, options[i]) * n_tasks >= 200 * fused_wgs_per_cu) {
-            pick = options[i];
+// The longest blocks (224 passes per producer wave = 896 channels per workgroup at d = 4096, then 112, 56, ... 7) that
+// still give the chip about one workgroup per compute unit: every round of workgroups pays the kernel's prologue, the
+// start of its streams and its tail again.  0 = do not fuse (too many partial results).
+int fused_passes(int d, int f, int n_tasks, int max_tasks) {
+    if (n_tasks <= 0 || n_tasks > max_tasks || n_tasks > kFusedMaxTasks) return 0;
+    constexpr int n_options = sizeof(kFusedPassOptions) / sizeof(kFusedPassOptions[0]);
+    int pick = kFusedPassOptions[n_options - 1];
+    for (int i = 0; i < n_options; ++i) {
+        if ((long long)fused_blocks(d, f, kFusedPassOptions[i]) * n_tasks >= 200 * fused_wgs_per_cu) {
+            pick = kFusedPassOptions[i];
             break;
         }
     }

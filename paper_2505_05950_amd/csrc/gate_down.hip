@@ -260,7 +260,7 @@ int gd_blocks(int n_tasks, int f) {
     nblk = nblk < 1 ? 1 : nblk;
     // batches: a multiple of the 8 XCDs, so that block b of every task runs on
     // XCD b % 8 (workgroups go to the XCDs in turn) and tasks that share an expert share its rows in that XCD's L2
-    if (n_tasks > kFusedMaxTasks) nblk = (nblk + 7) / 8 * 8;
+    if (n_tasks > kExpertOrderTasks) nblk = (nblk + 7) / 8 * 8;
     const int by_f = (f + 3) / 4;  // a workgroup should have at least a few channels to look at
     nblk = nblk > by_f ? by_f : nblk;
     return nblk < 1 ? 1 : nblk;

@@ -51,9 +51,23 @@ inline int fused_route_mode(int n_experts, int top_k, int n_shared) {
 // workgroup), v_out (optional) [task][f].
 constexpr int fused_producers = 4;                          // producer waves per workgroup (+ 2 consumers each)
 constexpr int fused_wgs_per_cu = 1;                         // workgroups per compute unit the block length aims at
-constexpr int fused_passes_long = 28, fused_passes_mid = 14, fused_passes_short = 7;  // channel passes per producer wave
+// channel passes per producer wave: the block lengths a launch can choose from, longest first
+constexpr int kFusedPassOptions[] = {224, 112, 56, 28, 14, 7};
 constexpr int kFusedMaxRouted = 64;       // routed experts a workgroup can pick among in place (one per lane)
-constexpr int kFusedMaxTasks = 16;        // beyond these the partial results outgrow what the fusion saves
+constexpr int kFusedMaxTasks = 256;       // (token, slot) tasks up to which the fused kernel is considered
+// Up to how many tasks a layer call takes the fused kernel.  Measured against the batch kernels (grouped up GEMV, union
+// gate/down), it wins while experts see few tokens each: config 3 (8 experts) 16 tasks 97 against 132 us, 32 tasks 181
+// against 184, 64 tasks 348 against 313; config 5 (66 experts) 64 tasks 38 against 54, 256 tasks 131 against 145.
+// Rule: up to 16 tasks always, beyond that up to four tasks per expert.  fused_tasks_tuned() > 0 replaces the rule.
+int fused_tasks_tuned();
+void set_fused_tasks_tuned(int n);
+inline int fused_task_limit(int n_all) {
+    const int t = fused_tasks_tuned();
+    const int rule = 4 * n_all > 16 ? 4 * n_all : 16;
+    const int lim = t > 0 ? t : rule;
+    return lim < kFusedMaxTasks ? lim : kFusedMaxTasks;
+}
+constexpr int kExpertOrderTasks = 16;     // batches of more tasks run their per-task kernels in expert order
 constexpr int kFusedMaxWorkgroups = 2048;
 struct FusedArgs {
     TaskMap map;
@@ -66,7 +80,7 @@ struct FusedArgs {
     int32_t* wg_count;
     int d, f, group, n_tasks, passes;
 };
-int fused_passes(int d, int f, int n_tasks);  // 0: not fused
+int fused_passes(int d, int f, int n_tasks, int max_tasks = kExpertOrderTasks);  // 0: not fused
 int fused_blocks(int d, int f, int passes);
 hipError_t launch_fused(const FusedArgs& a, int bits, hipStream_t stream);
 

@@ -210,6 +210,7 @@ def test_layer_batches_read_the_union_of_selected_rows_once(kernels):
     any (99 %), ragged f, d from 512 to 4096, every up-GEMV kernel in front (matrix-core, packed, generic)."""
     import paper_2505_05950_amd as F
     F.floe_tuning(F.TUNE_UNION_KERNELS, {"expert_order": 3, "matrix_cores": 1, "lds_ring": 2}[kernels])
+    F.floe_tuning(F.TUNE_FUSED_TASKS, 16)       # beyond 16 tasks the batch kernels, whatever the library's rule says
     try:
         _run_layer_case(40, 3, 4096, 530, 4, 64, 2, 0, 2, True, 24, 80)
         _run_layer_case(41, 5, 2048, 1408, 3, 32, 16, 2, 6, False, 12, 85)
@@ -221,6 +222,26 @@ def test_layer_batches_read_the_union_of_selected_rows_once(kernels):
         _run_layer_case(47, 5, 2048, 97, 3, 32, 30, 2, 4, False, 9, 50, gap=True)
     finally:
         F.floe_tuning(F.TUNE_UNION_KERNELS, 0)
+        F.floe_tuning(F.TUNE_FUSED_TASKS, 0)
+
+
+def test_layer_batches_through_the_fused_kernel_with_many_tasks():
+    """Up to 256 (token, slot) tasks in the one-kernel path (forced here; the library's rule takes it up to four tasks
+    per expert): every block length it can choose (224, 112, 56, 28 passes per producer wave), a block count that is a
+    multiple of eight with many tasks on one expert (tasks of a channel block side by side on one XCD), more than 64
+    experts (router kernel in front), 17-64 experts (pick in place) with 256 tasks, every packed width."""
+    import paper_2505_05950_amd as F
+    F.load()
+    F.floe_tuning(F.TUNE_FUSED_TASKS, 256)
+    try:
+        _run_layer_case(61, 3, 4096, 2100, 2, 64, 8, 0, 2, True, 16, 90)
+        _run_layer_case(62, 5, 2048, 704, 3, 32, 64, 2, 6, False, 32, 85)
+        _run_layer_case(63, 5, 1024, 320, 2, 64, 80, 1, 4, False, 20, 70)
+        _run_layer_case(64, 3, 1024, 7000, 4, 32, 3, 0, 1, False, 40, 60)
+        _run_layer_case(65, 3, 1024, 7000, 2, 64, 8, 0, 2, True, 50, 90)
+        _run_layer_case(66, 5, 2048, 1800, 3, 64, 10, 0, 2, True, 35, 80)
+    finally:
+        F.floe_tuning(F.TUNE_FUSED_TASKS, 0)
 
 
 def test_layer_with_more_than_65536_channels():
