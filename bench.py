@@ -94,6 +94,7 @@ def main():
     ap.add_argument("--stack-parts", default="plain,budget,cache,prefetch",
                     help="stack workload only: which measurements to run (a short list makes a short profile)")
     ap.add_argument("--grouped-gemv", type=int, default=0, help="floe_tuning(FLOE_TUNE_GROUPED_GEMV): 0 = library default")
+    ap.add_argument("--fused-tasks", type=int, default=0, help="floe_tuning(FLOE_TUNE_FUSED_TASKS): 0 = library default")
     ap.add_argument("--copy-workgroups", type=int, default=0, help="floe_tuning(FLOE_TUNE_STAGE_WORKGROUPS): 0 = library default")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0)
@@ -115,6 +116,8 @@ def main():
         FL.floe_tuning(FL.TUNE_UNION_KERNELS, args.union_kernels)
     if args.grouped_gemv:
         FL.floe_tuning(FL.TUNE_GROUPED_GEMV, args.grouped_gemv)
+    if args.fused_tasks:
+        FL.floe_tuning(FL.TUNE_FUSED_TASKS, args.fused_tasks)
     if args.copy_workgroups:
         FL.floe_tuning(FL.TUNE_STAGE_WORKGROUPS, args.copy_workgroups)
     K, W, R = args.steps, args.warmup, max(1, args.copies)

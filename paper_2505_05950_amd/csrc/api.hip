@@ -96,7 +96,7 @@ struct ExpertWs {
 ExpertWs expert_ws(const floe_shape* s, int T) {
     ExpertWs w;
     w.nblk = gd_blocks(T, s->f);
-    w.fused_passes = packed_fast_shape(s->d, s->bits, s->group) ? fused_passes(s->d, s->f, T) : 0;
+    w.fused_passes = packed_fast_shape(s->d, s->bits, s->group) ? fused_passes(s->d, s->f, s->bits, T) : 0;
     w.nblk_fused = w.fused_passes ? fused_blocks(s->d, s->f, w.fused_passes) : 0;
     const int nblk_alloc = w.nblk > w.nblk_fused ? w.nblk : w.nblk_fused;
     size_t o = 0;
@@ -129,7 +129,7 @@ LayerWs layer_ws(const floe_layer* L, int T) {
     w.nblk = gd_blocks(w.n_tasks, L->s.f);
     const int n_all = L->n_experts + L->n_shared;
     w.fused_passes = packed_fast_shape(L->s.d, L->s.bits, L->s.group)
-                         ? fused_passes(L->s.d, L->s.f, w.n_tasks, fused_task_limit(n_all)) : 0;
+                         ? fused_passes(L->s.d, L->s.f, L->s.bits, w.n_tasks, fused_task_limit(n_all)) : 0;
     w.nblk_fused = w.fused_passes ? fused_blocks(L->s.d, L->s.f, w.fused_passes) : 0;
     w.chunk = mfma_chunk(n_all, w.n_tasks);
     w.up = union_plan(L->s.d, L->s.f, w.n_tasks, n_all, w.chunk);

@@ -79,18 +79,22 @@ __device__ __forceinline__ void lds_piece_arrived(u32x4& q) { asm volatile("s_wa
 
 // ROUTED: the workgroup routes in place (<= 16 experts, or <= 64 with the logits given); otherwise the task's expert comes from `map`, its
 // threshold from task_tau and its output scale from task_scale (nullptr = 1).
-// kPasses channels-per-wave passes per producer, kDepth of them in flight.  v_out (optional): v[task][f].
+// n_pass channels-per-wave passes per producer (at most kPasses, which sizes the queues), kDepth of them in flight; with
+// codes staged through LDS n_pass is a multiple of kDepth.  v_out (optional): v[task][f].
 template <int BITS, int UPC, bool G32, bool ROUTED, int kPasses, int kDepth>
 __global__ __launch_bounds__(kFusedThreads, fused_wgs_per_cu) void fused_ffn_kernel(TaskMap map, const h16* __restrict__ x, RouteArgs ro,
                                                                   const float* __restrict__ task_tau,
                                                                   const float* __restrict__ task_scale, int f,
-                                                                  int gshift, float* __restrict__ v_out,
+                                                                  int n_pass_arg, int gshift, float* __restrict__ v_out,
                                                                   float* __restrict__ partial,
                                                                   int32_t* __restrict__ wg_count) {
     constexpr int d = 64 * UPC;
     constexpr int CPW = kWave / UPC;      // channels per wave pass
     constexpr int NV = d / 512;           // uint4 per lane of a gate column / down row
-    constexpr int kQ = kPasses * CPW;     // queue capacity = channels per producer
+    constexpr int kQ = kPasses * CPW;     // queue capacity
+    // the small size runs exactly kPasses passes, the large one what the launch says
+    const int n_pass = kPasses == kFusedMaxPasses ? n_pass_arg : kPasses;
+    const int nq = n_pass * CPW;          // channels per producer = the most a queue can receive
     static_assert(kDepth >= 1 && kDepth <= kPasses, "depth of the load pipeline");
     __shared__ float plog[32];                  // router: two partial dot products per expert
     __shared__ DevExpert tab[kFusedMaxRouted + 16];
@@ -117,7 +121,9 @@ __global__ __launch_bounds__(kFusedThreads, fused_wgs_per_cu) void fused_ffn_ker
     const int t = task / map.slots;
     const int slot = task - t * map.slots;
     const h16* xt = x + (size_t)t * d;
-    for (int i = tid; i < kFusedProducers * kQ; i += kFusedThreads) (&qj[0][0])[i] = -1;
+#pragma unroll
+    for (int w = 0; w < kFusedProducers; ++w)
+        for (int i = tid; i < nq; i += kFusedThreads) qj[w][i] = -1;
     if (tid < kFusedProducers) {
         done[tid] = 0;
         expert_of_queue[tid] = -1;
@@ -206,7 +212,7 @@ __global__ __launch_bounds__(kFusedThreads, fused_wgs_per_cu) void fused_ffn_ker
     if (producer) {
         // ================================================================ producer: codes -> v -> queue
         const int G = d >> gshift;
-        const int jw = (blk * kFusedProducers + wave) * kQ;
+        const int jw = (blk * kFusedProducers + wave) * nq;
         auto channel_of = [&](int p) {
             const int j = jw + p * CPW + sub;
             return j < f ? j : f - 1;  // keep the address in bounds; a clamped lane's result is not used
@@ -291,11 +297,11 @@ __global__ __launch_bounds__(kFusedThreads, fused_wgs_per_cu) void fused_ffn_ker
             lds_piece_request(stage + lane * 16, cw_next);
         }
 #pragma unroll 1
-        for (int p0 = 0; p0 < kPasses; p0 += kDepth) {
+        for (int p0 = 0; p0 < n_pass; p0 += kDepth) {
 #pragma unroll
             for (int i = 0; i < kDepth; ++i) {
                 const int p = p0 + i;
-                if (kPasses % kDepth != 0 && p >= kPasses) break;  // last, shorter round (wave-uniform)
+                if (!kStaged && p >= n_pass) break;  // last, shorter round (wave-uniform); staged: n_pass % kDepth == 0
                 const int j = jw + p * CPW + sub;
                 if constexpr (kStaged) {
                     lds_piece_arrived(cw_next);
@@ -315,13 +321,13 @@ __global__ __launch_bounds__(kFusedThreads, fused_wgs_per_cu) void fused_ffn_ker
                     // (a cache hit that nobody reads) so that every round has the same, unconditional sequence of
                     // requests: with a condition here the compiler has to assume that no request follows and makes
                     // each round wait for all of its loads at once.
-                    const int pn = p + kDepth < kPasses ? p + kDepth : kPasses - 1;
+                    const int pn = p + kDepth < n_pass ? p + kDepth : n_pass - 1;
                     issue(i, pn);
                 } else {
-                    if (p + kDepth < kPasses) issue(i, p + kDepth);
+                    if (p + kDepth < n_pass) issue(i, p + kDepth);
                 }
                 part = group_reduce_sum_to_last<UPC>(part) * inv_p;
-                const bool mine = u == UPC - 1 && j < f;
+                const bool mine = u == UPC - 1 && p < n_pass && j < f;
                 if (v_out && mine) v_out[(size_t)task * f + j] = part;
                 const bool hit = mine && fabsf(part) > tau;
                 unsigned long long hits = __ballot(hit);
@@ -359,7 +365,7 @@ __global__ __launch_bounds__(kFusedThreads, fused_wgs_per_cu) void fused_ffn_ker
 #pragma unroll
         for (int i = 0; i < 8 * NV; ++i) acc[i] = 0.0f;
         int k = c % kFusedCpp;
-        while (k < kQ) {  // the queue cannot hold more than its producer has channels
+        while (k < nq) {  // the queue cannot hold more than its producer has channels
             // The wait is a loop of its own that touches no accumulator: as a second way back to the head of the
             // outer loop it made the compiler copy all of them (64 moves) on every empty poll.
             int j;
@@ -448,19 +454,21 @@ static hipError_t fused_launch_shape(const FusedArgs& a, int gshift, hipStream_t
     constexpr int kWant = BITS == 2 ? 14 : 7;
     constexpr int kFit = staged_codes<BITS>() ? kFusedCpp * UPC * 64 * 4 / stage_slot_bytes<BITS>() : 4;
     constexpr int kDepth = staged_codes<BITS>() ? (kWant < kFit ? kWant : kFit) : 4;
+    // a.passes passes per producer at run time; the template argument only sizes the queues and caps the depth
+    if (a.passes < 1 || a.passes > kFusedMaxPasses) return hipErrorInvalidValue;
+    static_assert(kDepth == fused_depth(UPC * 64, BITS), "the host rounds the pass count to this depth");
+    constexpr int kDepthSmall = kDepth < kFusedMinPasses ? kDepth : kFusedMinPasses;
+    // staged codes: whole rounds of the ring (the waits in the kernel count on it)
+    if (staged_codes<BITS>() && a.passes % (a.passes <= kFusedMinPasses ? kDepthSmall : kDepth) != 0) return hipErrorInvalidValue;
 #define FLOE_FUSED_GO(ROUTED, P)                                                                                 \
     fused_ffn_kernel<BITS, UPC, G32, ROUTED, P, (kDepth < P ? kDepth : P)><<<grid, block, 0, stream>>>(a.map, a.x, ro, a.task_tau,   \
-                                                                                    a.task_scale, a.f, gshift,    \
+                                                                                    a.task_scale, a.f, a.passes, gshift, \
                                                                                     a.v_out, a.partial, a.wg_count)
 #define FLOE_FUSED_PASSES(ROUTED)                                               \
-    switch (a.passes) {                                                         \
-        case 224: FLOE_FUSED_GO(ROUTED, 224); break;                            \
-        case 112: FLOE_FUSED_GO(ROUTED, 112); break;                            \
-        case 56: FLOE_FUSED_GO(ROUTED, 56); break;                              \
-        case 28: FLOE_FUSED_GO(ROUTED, 28); break;                              \
-        case 14: FLOE_FUSED_GO(ROUTED, 14); break;                              \
-        case 7: FLOE_FUSED_GO(ROUTED, 7); break;                                \
-        default: return hipErrorInvalidValue;                                   \
+    if (a.passes <= kFusedMinPasses) {                                          \
+        FLOE_FUSED_GO(ROUTED, kFusedMinPasses);                                 \
+    } else {                                                                    \
+        FLOE_FUSED_GO(ROUTED, kFusedMaxPasses);                                 \
     }
     if (a.route) {
         if (a.route->top_k < 1 || a.route->top_k + a.route->n_shared > 16 ||

@@ -30,20 +30,25 @@ int fused_blocks(int d, int f, int passes) {
     return (f + ch - 1) / ch;
 }
 
-// The longest blocks (224 passes per producer wave = 896 channels per workgroup at d = 4096, then 112, 56, ... 7) that
-// still give the chip about one workgroup per compute unit: every round of workgroups pays the kernel's prologue, the
-// start of its streams and its tail again.  0 = do not fuse (too many partial results).
-int fused_passes(int d, int f, int n_tasks, int max_tasks) {
-    if (n_tasks <= 0 || n_tasks > max_tasks || n_tasks > kFusedMaxTasks) return 0;
-    constexpr int n_options = sizeof(kFusedPassOptions) / sizeof(kFusedPassOptions[0]);
-    int pick = kFusedPassOptions[n_options - 1];
-    for (int i = 0; i < n_options; ++i) {
-        if ((long long)fused_blocks(d, f, kFusedPassOptions[i]) * n_tasks >= 200 * fused_wgs_per_cu) {
-            pick = kFusedPassOptions[i];
-            break;
-        }
+// Passes per producer wave such that the launch is about one workgroup per compute unit, all of them with the same
+// number of channels: every round of workgroups pays the kernel's prologue, the start of its streams and its tail again,
+// and a round that is not full leaves compute units idle.  0 = do not fuse.
+int fused_passes(int d, int f, int bits, int n_tasks, int max_tasks) {
+    if (n_tasks <= 0 || n_tasks > max_tasks || n_tasks > kFusedMaxTasks || f <= 0) return 0;
+    const int unit = fused_producers * (64 / (d / 64));  // channels of one pass of all producers
+    const int cus = num_cus() * fused_wgs_per_cu;
+    int want_blocks = cus / n_tasks;  // rounded down: a few workgroups more than compute units cost a whole second round
+    if (want_blocks < 1) want_blocks = 1;
+    const int per_block = (f + want_blocks - 1) / want_blocks;
+    int passes = (per_block + unit - 1) / unit;
+    if (passes <= kFusedMinPasses) {
+        passes = kFusedMinPasses;
+    } else if (bits == 2) {  // staged codes: whole rounds of the ring
+        const int depth = fused_depth(d, bits);
+        passes = (passes + depth - 1) / depth * depth;
     }
-    return (long long)fused_blocks(d, f, pick) * n_tasks <= kFusedMaxWorkgroups ? pick : 0;
+    if (passes > kFusedMaxPasses) passes = kFusedMaxPasses / 14 * 14;
+    return (long long)fused_blocks(d, f, passes) * n_tasks <= kFusedMaxWorkgroups ? passes : 0;
 }
 
 hipError_t launch_fused(const FusedArgs& a, int bits, hipStream_t stream) {

@@ -51,8 +51,12 @@ inline int fused_route_mode(int n_experts, int top_k, int n_shared) {
 // workgroup), v_out (optional) [task][f].
 constexpr int fused_producers = 4;                          // producer waves per workgroup (+ 2 consumers each)
 constexpr int fused_wgs_per_cu = 1;                         // workgroups per compute unit the block length aims at
-// channel passes per producer wave: the block lengths a launch can choose from, longest first
-constexpr int kFusedPassOptions[] = {224, 112, 56, 28, 14, 7};
+// Channel passes per producer wave: a launch argument between these two.  The kernel exists in two sizes, for blocks of
+// kFusedMinPasses passes (all of them in flight at once) and for anything up to kFusedMaxPasses (which sizes its queues).
+constexpr int kFusedMinPasses = 7, kFusedMaxPasses = 448;
+// passes in flight per producer wave: INT2 stages its codes in LDS, as deep as the ring fits the two result slabs it
+// borrows (8 d bytes, 1 KiB per pass); INT3 and INT4 hold 4 passes in registers
+constexpr int fused_depth(int d, int bits) { return bits == 2 ? (d / 128 < 14 ? d / 128 : 14) : 4; }
 constexpr int kFusedMaxRouted = 64;       // routed experts a workgroup can pick among in place (one per lane)
 constexpr int kFusedMaxTasks = 256;       // (token, slot) tasks up to which the fused kernel is considered
 // Up to how many tasks a layer call takes the fused kernel.  Measured against the batch kernels (grouped up GEMV, union
@@ -80,7 +84,7 @@ struct FusedArgs {
     int32_t* wg_count;
     int d, f, group, n_tasks, passes;
 };
-int fused_passes(int d, int f, int n_tasks, int max_tasks = kExpertOrderTasks);  // 0: not fused
+int fused_passes(int d, int f, int bits, int n_tasks, int max_tasks = kExpertOrderTasks);  // 0: not fused
 int fused_blocks(int d, int f, int passes);
 hipError_t launch_fused(const FusedArgs& a, int bits, hipStream_t stream);
 
