@@ -77,11 +77,12 @@ __device__ __forceinline__ void lds_piece_request(const void* lds_ptr, u32x4& q)
 }
 __device__ __forceinline__ void lds_piece_arrived(u32x4& q) { asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(q) : : "memory"); }
 
-// ROUTED: the workgroup routes in place (<= 16 experts, or <= 64 with the logits given); otherwise the task's expert comes from `map`, its
+// ROUTED: 2 = the workgroup routes in place (<= 16 experts), 1 = it picks in place on logits formed by a kernel in front
+// (<= 64 experts), 0 = the task's expert comes from `map`, its
 // threshold from task_tau and its output scale from task_scale (nullptr = 1).
 // n_pass channels-per-wave passes per producer (at most kPasses, which sizes the queues), kDepth of them in flight; with
 // codes staged through LDS n_pass is a multiple of kDepth.  v_out (optional): v[task][f].
-template <int BITS, int UPC, bool G32, bool ROUTED, int kPasses, int kDepth>
+template <int BITS, int UPC, bool G32, int ROUTED, int kPasses, int kDepth>
 __global__ __launch_bounds__(kFusedThreads, fused_wgs_per_cu) void fused_ffn_kernel(TaskMap map, const h16* __restrict__ x, RouteArgs ro,
                                                                   const float* __restrict__ task_tau,
                                                                   const float* __restrict__ task_scale, int f,
@@ -150,7 +151,7 @@ __global__ __launch_bounds__(kFusedThreads, fused_wgs_per_cu) void fused_ffn_ker
             taus[tid] = ro.tau[(size_t)t * ro.tau_stride_t + tid];
         }
         float lg = 0.0f;  // producers: the logit of the expert this lane stands for
-        if (ro.logits) {
+        if constexpr (ROUTED == 1) {
             // the dot products were formed by a kernel in front (more than 16 experts: a workgroup that repeated them
             // would pull the whole router matrix through its L2 port); lane e holds expert e
             if (producer && lane < ro.n_experts) lg = ro.logits[(size_t)t * ro.n_experts + lane];
@@ -194,8 +195,8 @@ __global__ __launch_bounds__(kFusedThreads, fused_wgs_per_cu) void fused_ffn_ker
         ex = ro.n_experts + (slot - ro.top_k);  // a shared expert
         if (producer) {
             if (ro.top_k > 0) {
-                pick = ro.logits ? route_pick_wave64(lg, lane, ro.n_experts, ro.top_k)
-                                 : route_pick_wave16(lg, lane, ro.n_experts, ro.top_k);
+                if constexpr (ROUTED == 1) pick = route_pick_wave64(lg, lane, ro.n_experts, ro.top_k);
+                else pick = route_pick_wave16(lg, lane, ro.n_experts, ro.top_k);
                 if (slot < ro.top_k) ex = __builtin_amdgcn_readlane(pick.id, slot);
             }
             if (lane == 0) lds_poke(&expert_of_queue[wave], ex);
@@ -474,9 +475,13 @@ static hipError_t fused_launch_shape(const FusedArgs& a, int gshift, hipStream_t
         if (a.route->top_k < 1 || a.route->top_k + a.route->n_shared > 16 ||
             a.route->n_experts > (a.route->logits ? kFusedMaxRouted : 16))
             return hipErrorInvalidValue;
-        FLOE_FUSED_PASSES(true)
+        if (a.route->logits) {
+            FLOE_FUSED_PASSES(1)
+        } else {
+            FLOE_FUSED_PASSES(2)
+        }
     } else {
-        FLOE_FUSED_PASSES(false)
+        FLOE_FUSED_PASSES(0)
     }
 #undef FLOE_FUSED_PASSES
 #undef FLOE_FUSED_GO

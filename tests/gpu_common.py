@@ -58,3 +58,14 @@ def check_index_set(idx_gpu: np.ndarray, v_ref: np.ndarray, tau: float):
 
 def rel_err(y, y_ref):
     return float(np.abs(y - y_ref).max() / np.abs(y_ref).max())
+
+
+def tau_in_widest_gap(v, pct, window=64):
+    """A threshold for about pct % sparsity that no channel sits close to: the middle of the widest gap between
+    neighbouring |v| within `window` ranks of the order statistic of Eq. 6.  Returns (tau, distance to the nearest |v|)."""
+    a = np.sort(np.abs(v.astype(np.float64)))
+    z = -(-v.size * pct // 100)
+    lo, hi = max(1, z - window), min(v.size - 1, z + window)
+    k = max(range(lo, hi + 1), key=lambda i: a[i] - a[i - 1])
+    tau = np.float32(0.5 * (a[k] + a[k - 1]))
+    return tau, float(min(float(tau) - a[k - 1], a[k] - float(tau)))

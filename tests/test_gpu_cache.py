@@ -30,8 +30,9 @@ def test_cached_decode_matches_offloaded_decode_and_oracle(d, f):
     tau = np.zeros((T, n), np.float32)
     for t in range(T):
         for e in range(n):
-            tau[t, e] = O.threshold_for_sparsity(O.up_gemv(*experts_np[e][:3], d, bits, group, x[t]), pct)
-    tau *= np.float32(1.0 + 2e-3)          # off the order statistic: no channel sits exactly on its threshold
+            # in a gap between neighbouring |v|: no channel close enough to its threshold for rounding to decide it
+            tau[t, e], margin = G.tau_in_widest_gap(O.up_gemv(*experts_np[e][:3], d, bits, group, x[t]), pct, window=8)
+            assert margin > 1e-4 * tau[t, e]
     ref = O.moe_layer(experts_np, 0, top_k, True, wr, x, tau, bits, group)
     pinned = [torch.from_numpy(e[3]).pin_memory() for e in experts_np]
     ex_host = [F.Expert(d, f, bits, group, e[1].up_codes, e[1].up_scale, e[1].up_zero, pinned[i]) for i, e in enumerate(experts)]

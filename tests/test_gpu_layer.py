@@ -25,17 +25,6 @@ def _routing_is_stable(wr, x, top_k):
     return (s[top_k - 1] - s[top_k]) > 1e-3 * s[top_k - 1]
 
 
-def _tau_in_widest_gap(v, pct, window=64):
-    """A threshold for about pct % sparsity that no channel sits close to: the middle of the widest gap between
-    neighbouring |v| within `window` ranks of the order statistic of Eq. 6.  Returns (tau, distance to the nearest |v|)."""
-    a = np.sort(np.abs(v.astype(np.float64)))
-    z = -(-v.size * pct // 100)
-    lo, hi = max(1, z - window), min(v.size - 1, z + window)
-    k = max(range(lo, hi + 1), key=lambda i: a[i] - a[i - 1])
-    tau = np.float32(0.5 * (a[k] + a[k - 1]))
-    return tau, float(min(float(tau) - a[k - 1], a[k] - float(tau)))
-
-
 def _reference(experts_np, n_shared, top_k, renorm, wr, x, pct, d, f, bits, group, gap=False):
     """Oracle composition per (token, slot) with the band bookkeeping the layer-level bar needs.
     gap: thresholds in the widest gap near the order statistic; decisive[t] then says that every |v| of the token's
@@ -61,7 +50,7 @@ def _reference(experts_np, n_shared, top_k, renorm, wr, x, pct, d, f, bits, grou
             ex = experts_np[e]
             v = O.up_gemv(*ex[:3], d, bits, group, x[t])
             if gap:
-                tau[t, e], margin = _tau_in_widest_gap(v, pct)
+                tau[t, e], margin = G.tau_in_widest_gap(v, pct)
                 decisive[t] &= margin > G.V_RTOL_RMS * float(np.sqrt(np.mean(v.astype(np.float64) ** 2)))
             else:
                 tau[t, e] = O.threshold_for_sparsity(v, pct)
