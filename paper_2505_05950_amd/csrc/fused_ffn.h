@@ -456,7 +456,7 @@ static hipError_t fused_launch_shape(const FusedArgs& a, int gshift, hipStream_t
     constexpr int kFit = staged_codes<BITS>() ? kFusedCpp * UPC * 64 * 4 / stage_slot_bytes<BITS>() : 4;
     constexpr int kDepth = staged_codes<BITS>() ? (kWant < kFit ? kWant : kFit) : 4;
     // a.passes passes per producer at run time; the template argument only sizes the queues and caps the depth
-    if (a.passes < 1 || a.passes > kFusedMaxPasses) return hipErrorInvalidValue;
+    if (a.passes < kFusedMinPasses || a.passes > kFusedMaxPasses) return hipErrorInvalidValue;  // (the grid follows a.passes)
     static_assert(kDepth == fused_depth(UPC * 64, BITS), "the host rounds the pass count to this depth");
     constexpr int kDepthSmall = kDepth < kFusedMinPasses ? kDepth : kFusedMinPasses;
     // staged codes: whole rounds of the ring (the waits in the kernel count on it)

@@ -312,7 +312,8 @@ def test_expert_config2_full_size(bits, pct):
     assert np.all(np.abs(y.cpu().numpy()[0] - y_ref) <= G.Y_BAR * np.abs(y_ref).max() + slack)
 
 
-@pytest.mark.parametrize("T", [2, 24])     # the fused kernel; router, token grouping and the matrix-core GEMV
+# the fused kernel (short and long blocks); router, token grouping and the matrix-core GEMV; the matrix-core gate/down pair
+@pytest.mark.parametrize("T", [2, 16, 24, 64])
 def test_layer_decode_replayed_from_a_hip_graph_matches_eager(T):
     """The benchmark replays the layer from a HIP graph: every replay must reproduce the eager result
     bit for bit (sums are formed in a fixed order), with eager work and synchronisations between replays."""
