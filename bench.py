@@ -355,11 +355,17 @@ def main():
             t1 = time.perf_counter()
             O.moe_layer(ex_np, 0, TOP_K, True, wr, xt, tau_np, BITS, GROUP)
             spent += time.perf_counter() - t1
+            if n_tok == 0:
+                tau_first = tau_np
             n_tok += 1
         cpu = {"value": round(spent / n_tok * 1e6, 1), "unit": "us per MoE layer-token", "cores": threads, "kind": "oracle",
                "sample": f"{n_tok} of the {N_TOKENS} benchmark tokens through the same layer (router, up GEMV, select, "
                          f"gate/down, combine); threshold calibration not timed"}
+        # the same call on one thread (the oracle as its definition reads), on the first token only
         O.set_threads(1)
+        t1 = time.perf_counter()
+        O.moe_layer(ex_np, 0, TOP_K, True, wr, xs[0:1], tau_first, BITS, GROUP)
+        cpu["one_thread_us"] = round((time.perf_counter() - t1) * 1e6, 1)
 
     out = {
         "metric": "us per MoE layer-token (Mixtral-shape compressed sparse expert layer, decode)",

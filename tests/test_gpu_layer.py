@@ -344,7 +344,16 @@ def test_layer_decode_replayed_from_a_hip_graph_matches_eager(T):
             torch.cuda.synchronize()
             graph.replay()
             torch.cuda.synchronize()
-            assert torch.equal(y_static, eager[i]), (rep, i)
+            if not torch.equal(y_static, eager[i]):
+                # say which side is the odd one out: the stored eager result, this replay, or an input left over
+                diff = (y_static.float() - eager[i].float()).abs()
+                again = F.floe_moe_layer_decode(L, x).clone()
+                torch.cuda.synchronize()
+                raise AssertionError(dict(
+                    rep=rep, i=i, max_diff_per_token=diff.max(dim=1).values.tolist(), n_differing=int((diff > 0).sum()),
+                    replay_equals_eager_of=[j for j in range(len(xs)) if torch.equal(y_static, eager[j])],
+                    eager_again_equals_stored=bool(torch.equal(again, eager[i])),
+                    eager_again_equals_replay=bool(torch.equal(again, y_static))))
             _ = (y_static.float() * 2).sum().item()          # eager work between replays
 
 
