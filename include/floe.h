@@ -84,7 +84,7 @@ int floe_profile_kernel(int kernel_id, void* start_event, void* stop_event);
 
 /*
  * Tuning switch (no part of the method; every setting gives results within the same parity bars).
- *   FLOE_TUNE_UNION_KERNELS  how Alg. 1 steps 4-5 run for decode batches (more than 16 (token, slot) pairs), where
+ *   FLOE_TUNE_UNION_KERNELS  how Alg. 1 steps 4-5 run for decode batches (those beyond FLOE_TUNE_FUSED_TASKS), where
  *                            the tokens of an expert select overlapping rows:
  *                            0 = chosen per call (default): 1 once the experts see about a dozen tokens each, else 3;
  *                            1 = per expert group, the union of the selected rows read once, gate and down
