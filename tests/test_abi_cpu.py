@@ -65,3 +65,45 @@ def test_argument_validation_happens_before_any_device_work(lib):
     assert lib.floe_expert_ffn_sparse(C.byref(e_bad), fake, 1, fake, None, fake, fake, fake, ws, need, None) == -1
     assert lib.floe_stage_channels(None, 4096, 16, fake, fake, 4, fake, None, None, None) == -1
     assert lib.floe_expert_workspace_bytes(C.byref(_Shape(4096, 16, 7, 64)), 1) == 0
+
+
+def test_tuning_switch_validates_its_arguments(lib):
+    bad = [(1, 4), (1, -1), (2, 4097), (2, -1), (3, 3), (3, -1), (4, 257), (4, -1), (0, 0), (9, 0)]
+    for key, value in bad:
+        assert lib.floe_tuning(key, value) == -1, (key, value)
+    try:
+        for key, values in ((1, (1, 2, 3)), (2, (1, 32, 4096)), (3, (1, 2)), (4, (1, 16, 256))):
+            for v in values:
+                assert lib.floe_tuning(key, v) == 0, (key, v)
+    finally:
+        for key in (1, 2, 3, 4):
+            assert lib.floe_tuning(key, 0) == 0
+
+
+def test_layer_workspace_query_for_every_path_the_dispatch_can_take(lib):
+    """The workspace plan (host logic only) for the two layer shapes of the benchmark at batch sizes on both sides of
+    every dispatch boundary, under every tuning: a size is returned, it holds at least the partial results of one block
+    per (token, slot), and it is the same when asked twice (the decode call sizes its pointers with the same routine)."""
+    from paper_2505_05950_amd.binding import _Layer, _Shape
+    lib.floe_layer_workspace_bytes.restype = C.c_size_t
+    fake = C.c_void_p(4096)
+    shapes = [(4096, 14336, 2, 64, 8, 2, 0), (2048, 1408, 3, 32, 64, 6, 2), (1024, 300, 4, 128, 3, 1, 1),
+              (1536, 700, 8, 64, 100, 4, 0)]
+    try:
+        for fused_tasks in (0, 16, 256):
+            for grouped in (0, 1, 2):
+                for union in (0, 1, 2, 3):
+                    lib.floe_tuning(4, fused_tasks), lib.floe_tuning(3, grouped), lib.floe_tuning(1, union)
+                    for d, f, bits, group, n, top_k, n_shared in shapes:
+                        L = _Layer(n, top_k, n_shared, 1, _Shape(d, f, bits, group), 4096, None, 4096, 0, 4096, 0)
+                        slots = top_k + n_shared
+                        for T in (1, 2, 3, 4, 8, 9, 16, 17, 32, 33, 64, 128, 500, 4096):
+                            need = lib.floe_layer_workspace_bytes(C.byref(L), T)
+                            assert need >= T * slots * d * 4, (d, f, bits, n, T, fused_tasks, grouped, union)
+                            assert need == lib.floe_layer_workspace_bytes(C.byref(L), T)
+                            assert need < (64 << 30)
+                        assert lib.floe_layer_workspace_bytes(C.byref(L), -1) == 0
+                        assert lib.floe_moe_layer_decode(C.byref(L), fake, 1, fake, None, fake, 16, None) == -4
+    finally:
+        for key in (1, 3, 4):
+            lib.floe_tuning(key, 0)
