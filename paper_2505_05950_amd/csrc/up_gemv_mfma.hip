@@ -207,7 +207,7 @@ __global__ __launch_bounds__(kMfmaThreads, BITS == 3 ? 4 : 1) void up_gemv_mfma_
         const float amax = __builtin_bit_cast(float, tok_amax[tid]);
         const int down = (amax >= 512.0f && amax < 3.0e38f) ? ilogbf(amax) - 8 : 0;  // |x'| < 512
         tok_down[tid] = down;
-        tok_inv_p[tid] = ldexpf(1.0f, down);
+        tok_inv_p[tid] = ldexpf(1.0f, down) * kScaleBack;  // undoes the token's pre-scaling and the 2^(pmax - 24) of the products
     }
     __syncthreads();
     FLOE_TL(1);
@@ -248,7 +248,9 @@ __global__ __launch_bounds__(kMfmaThreads, BITS == 3 ? 4 : 1) void up_gemv_mfma_
                     *reinterpret_cast<uint32_t*>(ubase + ((j * 4 + gq) * NTPAD) * 16 + 4 * pr) = as_u32(val);
                 }
 #pragma unroll
-        for (int q2 = 0; q2 < GPU_; ++q2) xg[(size_t)(U * GPU_ + q2) * NTPAD + n] = gsum[q2];
+        // (times 2^(pmax - 24): the matrix products carry that factor, and the zero-point term is subtracted from them
+        // before the scale is applied)
+        for (int q2 = 0; q2 < GPU_; ++q2) xg[(size_t)(U * GPU_ + q2) * NTPAD + n] = gsum[q2] * (1.0f / kScaleBack);
     }
     __syncthreads();
 
@@ -389,26 +391,29 @@ __global__ __launch_bounds__(kMfmaThreads, BITS == 3 ? 4 : 1) void up_gemv_mfma_
                 weight_frag<BITS, G32>(w, 0, g, r0);
                 weight_frag<BITS, G32>(w, 1, g, r1);
                 const f32x4 zero4 = {0.f, 0.f, 0.f, 0.f};
-                auto half_of = [](const uint32_t (&m)[kMetaRegs], int k) -> float {
+                // scale and zero stay halves: the multiply-adds below take them as such (mixed-precision FMA), which
+                // saves the two conversions and two products per unit that fp32 copies of s and s*z cost
+                auto half_of = [](const uint32_t (&m)[kMetaRegs], int k) -> h16 {
                     const h16x2 p = as_h2(m[k >> 1]);
-                    return (k & 1) ? (float)p.y : (float)p.x;
+                    return (k & 1) ? p.y : p.x;
                 };
                 if (G32) {  // each half unit is a quantization group of its own
                     const f32x4 c0 = __builtin_amdgcn_mfma_f32_16x16x32_f16(xa[0], as_h8(r0), zero4, 0, 0, 0);
                     const f32x4 c1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(xa[1], as_h8(r1), zero4, 0, 0, 0);
-                    const float s0 = half_of(bs[tt], 2 * uu), z0 = half_of(bz[tt], 2 * uu);
-                    const float s1 = half_of(bs[tt], 2 * uu + 1), z1 = half_of(bz[tt], 2 * uu + 1);
-                    const float a0 = s0 * kScaleBack, a1 = s1 * kScaleBack, b0 = s0 * z0, b1 = s1 * z1;
+                    const h16 s0 = half_of(bs[tt], 2 * uu), z0 = half_of(bz[tt], 2 * uu);
+                    const h16 s1 = half_of(bs[tt], 2 * uu + 1), z1 = half_of(bz[tt], 2 * uu + 1);
 #pragma unroll
-                    for (int i = 0; i < 4; ++i)
-                        acc[tt][i] = fmaf(-b1, xgv[GPU_ - 1][i], fmaf(a1, c1[i], fmaf(-b0, xgv[0][i], fmaf(a0, c0[i], acc[tt][i]))));
+                    for (int i = 0; i < 4; ++i) {
+                        const float t0 = fmaf(-(float)z0, xgv[0][i], c0[i]);
+                        const float t1 = fmaf(-(float)z1, xgv[GPU_ - 1][i], c1[i]);
+                        acc[tt][i] = fmaf((float)s1, t1, fmaf((float)s0, t0, acc[tt][i]));
+                    }
                 } else {
                     f32x4 cc = __builtin_amdgcn_mfma_f32_16x16x32_f16(xa[0], as_h8(r0), zero4, 0, 0, 0);
                     cc = __builtin_amdgcn_mfma_f32_16x16x32_f16(xa[1], as_h8(r1), cc, 0, 0, 0);
-                    const float s = half_of(bs[tt], uu), z = half_of(bz[tt], uu);
-                    const float s16 = s * kScaleBack, sz = s * z;
+                    const h16 s_h = half_of(bs[tt], uu), z_h = half_of(bz[tt], uu);
 #pragma unroll
-                    for (int i = 0; i < 4; ++i) acc[tt][i] = fmaf(-sz, xgv[0][i], fmaf(s16, cc[i], acc[tt][i]));
+                    for (int i = 0; i < 4; ++i) acc[tt][i] = fmaf((float)s_h, fmaf(-(float)z_h, xgv[0][i], cc[i]), acc[tt][i]);
                 }
             }
             __builtin_amdgcn_sched_barrier(0);  // keep the LDS reads of later units from being hoisted up here
@@ -448,7 +453,7 @@ __global__ __launch_bounds__(kMfmaThreads, BITS == 3 ? 4 : 1) void up_gemv_mfma_
         for (int i = 0; i < 4; ++i) {
             const int n = 4 * g + i;
             const bool live = n < n_tok;
-            const float val = acc[tt][i] * tok_inv_p[n & 15];
+            const float val = acc[tt][i] * tok_inv_p[n & 15];  // (tok_inv_p carries 2^(24 - pmax) as well)
             const int task = tok_task[n & 15];
             if (live && chan[tt] < f) v[(size_t)task * f + chan[tt]] = val;
             const bool keep = live && chan[tt] < f && fabsf(val) > tok_tau[n & 15];
