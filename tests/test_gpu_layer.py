@@ -340,7 +340,9 @@ def test_layer_decode_replayed_from_a_hip_graph_matches_eager(T):
             F.floe_moe_layer_decode(L, x_static, y_static)
     for rep in range(2):
         for i, x in enumerate(xs):
-            x_static.copy_(x)
+            # the new input is written by a kernel, as in a decode loop where the previous layer's kernels produce it (a
+            # device-to-device memcpy may run on a copy engine instead)
+            torch.mul(x, 1.0, out=x_static)
             torch.cuda.synchronize()
             graph.replay()
             torch.cuda.synchronize()
