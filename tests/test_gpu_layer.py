@@ -424,17 +424,29 @@ def test_layer_randomized_shapes():
     """Seeded sweep over shapes, widths, routing and sparsity levels (every dispatch branch several times over)."""
     import random
     rng = random.Random(20250505)
-    for i in range(24):
-        d = rng.choice([1024, 2048, 4096, 4096])
-        bits = rng.choice([2, 2, 2, 3, 4])
-        group = rng.choice([32, 64, 64, 128])
-        f = rng.choice([rng.randint(120, 400), rng.randint(400, 1800)]) if d == 4096 else rng.randint(120, 2500)
-        n = rng.randint(2, 16)
-        n_shared = rng.choice([0, 0, 1, 2])
-        top_k = rng.randint(1, min(n, 6))
-        renorm = rng.choice([True, False])
-        T = rng.choice([1, 1, 2, 3, 5, 8])
-        pct = rng.choice([0, 50, 80, 90, 95])
-        print(f"case {i}: d={d} f={f} bits={bits} group={group} n={n}+{n_shared} top{top_k} renorm={renorm} T={T} pct={pct}",
-              flush=True)
-        _run_layer_case(2000 + i, 3, d, f, bits, group, n, n_shared, top_k, renorm, T, pct)
+    import paper_2505_05950_amd as F
+    F.load()
+    try:
+        for i in range(28):
+            d = rng.choice([1024, 2048, 4096, 4096])
+            bits = rng.choice([2, 2, 2, 3, 4])
+            group = rng.choice([32, 64, 64, 128])
+            f = rng.choice([rng.randint(120, 400), rng.randint(400, 1800)]) if d == 4096 else rng.randint(120, 2500)
+            # up to 16 experts (all of the router inside the fused kernel), up to 64 (pick inside it), more (router in front)
+            n = rng.choice([rng.randint(2, 16), rng.randint(2, 16), rng.randint(17, 64), rng.randint(65, 90)])
+            n_shared = rng.choice([0, 0, 1, 2])
+            top_k = rng.randint(1, min(n, 6))
+            renorm = rng.choice([True, False])
+            T = rng.choice([1, 1, 2, 3, 5, 8, 13, 21, 40])
+            pct = rng.choice([0, 50, 80, 90, 95])
+            # the last third of the cases also moves the dispatch boundaries (union kernels, grouped GEMV, fused-task limit)
+            tune = (0, 0, 0) if i < 19 else (rng.choice([0, 1, 2, 3]), rng.choice([0, 1, 2]), rng.choice([0, 16, 40, 256]))
+            F.floe_tuning(F.TUNE_UNION_KERNELS, tune[0])
+            F.floe_tuning(F.TUNE_GROUPED_GEMV, tune[1])
+            F.floe_tuning(F.TUNE_FUSED_TASKS, tune[2])
+            print(f"case {i}: d={d} f={f} bits={bits} group={group} n={n}+{n_shared} top{top_k} renorm={renorm} T={T} "
+                  f"pct={pct} tuning={tune}", flush=True)
+            _run_layer_case(2000 + i, 3, d, f, bits, group, n, n_shared, top_k, renorm, T, pct)
+    finally:
+        for key in (F.TUNE_UNION_KERNELS, F.TUNE_GROUPED_GEMV, F.TUNE_FUSED_TASKS):
+            F.floe_tuning(key, 0)
